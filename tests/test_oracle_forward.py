@@ -1,0 +1,170 @@
+"""Pins for the CPU oracle of the model forward pass (oracle/forward.py).
+
+The paper treats M_i as a black box (Sec. 3.1), so absolute logits of a random-init model
+have no published value to compare with: they are pinned by invariants and by special
+cases that reduce to library routines (torch's scaled_dot_product_attention / rms_norm /
+silu / complex multiplication for the rotary embedding), all in fp64.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import forward as fwd
+from paper_2510_26527_amd import synth
+
+
+def _model(shape, seed=0, std=0.3):
+    w = synth.make_weights(shape, seed, torch.float32, std=std)
+    g = torch.Generator().manual_seed(seed + 1)
+    for k in w:                                    # non-trivial gains so a dropped gain shows
+        if k.endswith("norm"):
+            w[k] = 1.0 + 0.2 * torch.randn(w[k].shape, generator=g)
+    cfg = fwd.ModelConfig(**shape.asdict())
+    return cfg, {k: synth.as_numpy(v) for k, v in w.items()}
+
+
+SMALL = synth.Shape(2, 32, 4, 2, 8, 48, 29, 10000.0, 1e-5)
+
+
+def test_zero_layer_model_is_norm_then_head():
+    shape = synth.Shape(0, 16, 2, 2, 8, 32, 11)
+    cfg, w = _model(shape)
+    toks = np.array([[3, 7, 7, 0]])
+    out = fwd.forward(cfg, w, toks, fwd.KVCache(cfg, 1, 8))
+    e = torch.tensor(w["embed"][toks[0]], dtype=torch.float64)
+    ref = F.rms_norm(e, (16,), torch.tensor(w["final_norm"], dtype=torch.float64), 1e-5) \
+        @ torch.tensor(w["lm_head"], dtype=torch.float64).T
+    np.testing.assert_allclose(out[0], ref.numpy(), atol=1e-12)
+
+
+def test_attention_single_key_returns_v_and_matches_sdpa():
+    rng = np.random.default_rng(0)
+    q = rng.normal(size=(1, 4, 8)); k = rng.normal(size=(2, 1, 8)); v = rng.normal(size=(2, 1, 8))
+    out = fwd.attention(q, k, v, 0)
+    np.testing.assert_allclose(out[0, :2], np.repeat(v[0], 2, 0), atol=1e-15)
+    np.testing.assert_allclose(out[0, 2:], np.repeat(v[1], 2, 0), atol=1e-15)
+    # general case against torch's library attention with an explicit causal mask
+    R, S, hq, hkv, dh = 5, 7, 6, 2, 16
+    q = rng.normal(size=(R, hq, dh)); k = rng.normal(size=(hkv, S + R, dh)); v = rng.normal(size=(hkv, S + R, dh))
+    out = fwd.attention(q, k, v, S)
+    tq = torch.tensor(q).permute(1, 0, 2)[None]
+    tk = torch.tensor(k).repeat_interleave(hq // hkv, 0)[None]
+    tv = torch.tensor(v).repeat_interleave(hq // hkv, 0)[None]
+    mask = torch.arange(S + R)[None, :] <= (S + torch.arange(R))[:, None]
+    ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)[0].permute(1, 0, 2)
+    np.testing.assert_allclose(out, ref.numpy(), atol=1e-12)
+
+
+def test_rope_properties():
+    rng = np.random.default_rng(1)
+    x = rng.normal(size=(6, 3, 16)); y = rng.normal(size=(6, 3, 16))
+    pos = np.array([0, 1, 5, 17, 100, 4095])
+    r = fwd.rope(x, pos, 1e4)
+    np.testing.assert_allclose(r[0], x[0], atol=1e-15)                                   # position 0
+    np.testing.assert_allclose(np.linalg.norm(r, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    # complex-number form: (x_i + i x_{i+half}) * exp(i pos theta^(-2i/d))
+    half = 8
+    z = torch.tensor(x[..., :half]) + 1j * torch.tensor(x[..., half:])
+    ang = torch.tensor(pos, dtype=torch.float64)[:, None] * (1e4 ** (-torch.arange(half, dtype=torch.float64) / half))
+    zr = z * torch.polar(torch.ones_like(ang), ang)[:, None, :]
+    np.testing.assert_allclose(r, torch.cat([zr.real, zr.imag], -1).numpy(), atol=1e-12)
+    # scores depend on the position difference only
+    a = fwd.rope(x[:1], np.array([40]), 1e4); b = fwd.rope(y[:1], np.array([33]), 1e4)
+    c = fwd.rope(x[:1], np.array([1007]), 1e4); d = fwd.rope(y[:1], np.array([1000]), 1e4)
+    np.testing.assert_allclose((a * b).sum(-1), (c * d).sum(-1), atol=1e-10)
+
+
+def _torch_reference(cfg, w, toks):
+    """Full-sequence, cache-free recompute with torch fp64 library ops."""
+    t = lambda n: torch.tensor(w[n], dtype=torch.float64)
+    x = t("embed")[torch.tensor(toks)]
+    R = x.shape[0]
+    half = cfg.d_head // 2
+    ang = torch.arange(R, dtype=torch.float64)[:, None] * \
+        (cfg.rope_theta ** (-torch.arange(half, dtype=torch.float64) * 2 / cfg.d_head))
+    rot = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+
+    def rope(v):
+        z = torch.complex(v[..., :half], v[..., half:]) * rot
+        return torch.cat([z.real, z.imag], -1)
+    for l in range(cfg.n_layers):
+        n = F.rms_norm(x, (cfg.d_model,), t(f"l{l}.attn_norm"), cfg.rms_eps)
+        q = rope(F.linear(n, t(f"l{l}.wq")).view(R, cfg.n_q_heads, cfg.d_head))
+        k = rope(F.linear(n, t(f"l{l}.wk")).view(R, cfg.n_kv_heads, cfg.d_head))
+        v = F.linear(n, t(f"l{l}.wv")).view(R, cfg.n_kv_heads, cfg.d_head)
+        a = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None],
+                                           v.permute(1, 0, 2)[None], is_causal=True, enable_gqa=True)
+        x = x + F.linear(a[0].permute(1, 0, 2).reshape(R, -1), t(f"l{l}.wo"))
+        n = F.rms_norm(x, (cfg.d_model,), t(f"l{l}.ffn_norm"), cfg.rms_eps)
+        x = x + F.linear(F.silu(F.linear(n, t(f"l{l}.w_gate"))) * F.linear(n, t(f"l{l}.w_up")), t(f"l{l}.w_down"))
+    return F.linear(F.rms_norm(x, (cfg.d_model,), t("final_norm"), cfg.rms_eps), t("lm_head")).numpy()
+
+
+def test_matches_library_recompute_and_is_cache_consistent():
+    cfg, w = _model(SMALL)
+    toks = synth.make_tokens(SMALL.vocab, (9,), 4)
+    ref = _torch_reference(cfg, w, toks)
+    # one call with all rows
+    kv = fwd.KVCache(cfg, 1, 16)
+    out = fwd.forward(cfg, w, toks[None], kv)[0]
+    np.testing.assert_allclose(out, ref, atol=1e-10)
+    assert kv.lens[0] == 9
+    # one row at a time, and 4 + 5
+    kv1 = fwd.KVCache(cfg, 1, 16)
+    rows = [fwd.forward(cfg, w, toks[None, i:i + 1], kv1)[0, 0] for i in range(9)]
+    np.testing.assert_allclose(np.stack(rows), ref, atol=1e-10)
+    kv2 = fwd.KVCache(cfg, 1, 16)
+    a = fwd.forward(cfg, w, toks[None, :4], kv2)[0]
+    b = fwd.forward(cfg, w, toks[None, 4:], kv2)[0]
+    np.testing.assert_allclose(np.concatenate([a, b]), ref, atol=1e-10)
+
+
+def test_truncate_then_rerun_equals_fresh_run():
+    cfg, w = _model(SMALL, seed=3)
+    toks = synth.make_tokens(SMALL.vocab, (12,), 5)
+    alt = synth.make_tokens(SMALL.vocab, (4,), 6)
+    kv = fwd.KVCache(cfg, 1, 16)
+    fwd.forward(cfg, w, toks[None], kv)
+    kv.truncate(7)                                   # roll back to 7 accepted positions
+    out = fwd.forward(cfg, w, alt[None], kv)[0]
+    ref = _torch_reference(cfg, w, np.concatenate([toks[:7], alt]))[7:]
+    np.testing.assert_allclose(out, ref, atol=1e-10)
+    with pytest.raises(ValueError):
+        kv.truncate(40)
+
+
+def test_batch_rows_are_independent_with_ragged_lengths():
+    cfg, w = _model(SMALL, seed=8)
+    t0 = synth.make_tokens(SMALL.vocab, (10,), 1); t1 = synth.make_tokens(SMALL.vocab, (6,), 2)
+    kv = fwd.KVCache(cfg, 2, 16)
+    # bring the two sequences to different lengths (7 and 3), then step both by 3
+    ka = fwd.KVCache(cfg, 1, 16); kb = fwd.KVCache(cfg, 1, 16)
+    fwd.forward(cfg, w, t0[None, :7], ka); fwd.forward(cfg, w, t1[None, :3], kb)
+    for l in range(cfg.n_layers):
+        kv.k[l][0], kv.v[l][0] = ka.k[l][0], ka.v[l][0]
+        kv.k[l][1], kv.v[l][1] = kb.k[l][0], kb.v[l][0]
+    kv.lens = np.array([7, 3])
+    out = fwd.forward(cfg, w, np.stack([t0[7:10], t1[3:6]]), kv)
+    np.testing.assert_allclose(out[0], _torch_reference(cfg, w, t0)[7:10], atol=1e-10)
+    np.testing.assert_allclose(out[1], _torch_reference(cfg, w, t1)[3:6], atol=1e-10)
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    cfg, w = _model(SMALL, seed=2)
+    mha_shape = synth.Shape(2, 32, 4, 4, 8, 48, 29)
+    cfg2 = fwd.ModelConfig(**mha_shape.asdict())
+    w2 = dict(w)
+    for l in range(2):
+        for n in ("wk", "wv"):
+            m = w[f"l{l}.{n}"].reshape(2, 8, 32)
+            w2[f"l{l}.{n}"] = np.repeat(m, 2, axis=0).reshape(32, 32)
+    toks = synth.make_tokens(29, (1, 6), 9)
+    a = fwd.forward(cfg, w, toks, fwd.KVCache(cfg, 1, 8))
+    b = fwd.forward(cfg2, w2, toks, fwd.KVCache(cfg2, 1, 8))
+    np.testing.assert_allclose(a, b, atol=1e-12)
+
+
+def test_bf16_bit_patterns_are_widened_exactly():
+    t = torch.randn(257, generator=torch.Generator().manual_seed(0)).to(torch.bfloat16)
+    np.testing.assert_array_equal(fwd.widen(synth.as_numpy(t)), t.double().numpy())
