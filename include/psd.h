@@ -1,0 +1,168 @@
+/*
+ * psd - the verify path of polybasic speculative decoding on one MI355X (gfx950).
+ *
+ * A chain of models M_1 (target) ... M_n (draft) shares a vocabulary; each
+ * level i verifies, with ONE forward pass, the block of tokens proposed by the
+ * level below it and applies the speculative-sampling acceptance test
+ * (Sec. 3.1 "Problem Formulation"; Sec. 3.3 "Staged Verification";
+ * Algorithm 1).  This library is that hot path:
+ *
+ *   psd_model_forward   p_i(. | x_<=t) = M_i(x_<=t) for the new rows of a block
+ *                       (Sec. 3.1; the cost T_i of Eq. 2)
+ *   psd_spec_accept     VERIFY of Algorithm 1: accept with prob. min(1, p/q),
+ *                       first rejection -> one draw from norm(max(0, p - q))
+ *   psd_kv_truncate     the "partial rollback" of Sec. 3.3: KV length <- accepted length
+ *
+ * Conventions
+ *   - Every array argument marked "device" is a pointer to GPU memory owned by
+ *     the caller, who keeps it alive while a handle or an enqueued call uses it.
+ *     Handles (psd_model, psd_kv) are small host objects; they own no device
+ *     memory.  The library allocates no device memory at all: scratch space is
+ *     the caller's `workspace`, sized by the *_workspace_bytes calls.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on that stream and never synchronise.
+ *   - Arguments are checked on the host before anything is launched: a negative
+ *     status means nothing was enqueued and no output was touched.
+ *   - A handle may be used from one host thread at a time.
+ */
+#ifndef PSD_H
+#define PSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t psd_status;
+#define PSD_OK 0
+#define PSD_ERR_NULL (-1)          /* a required pointer is NULL                         */
+#define PSD_ERR_SHAPE (-2)         /* a size is out of the supported range               */
+#define PSD_ERR_DTYPE (-3)         /* dtype is neither PSD_F32 nor PSD_BF16              */
+#define PSD_ERR_CAPACITY (-4)      /* the KV cache cannot take n_new more positions      */
+#define PSD_ERR_TEMPERATURE (-5)   /* temperature is not a finite number > 0             */
+#define PSD_ERR_WORKSPACE (-6)     /* workspace is NULL, misaligned or too small         */
+#define PSD_ERR_HIP (-7)           /* a HIP launch failed (see psd_last_hip_error)       */
+#define PSD_ERR_UNIMPLEMENTED (-8)
+
+#define PSD_F32 0
+#define PSD_BF16 1
+
+/* bits of psd_spec_accept's out_flags */
+#define PSD_FLAG_NEAR_TIE 1       /* some tested position had |u - p/q| < 1e-5           */
+#define PSD_FLAG_ZERO_RESIDUAL 2  /* residual mass was 0: the draw used p instead        */
+
+typedef struct psd_model psd_model;
+typedef struct psd_kv psd_kv;
+
+/* Decoder-only transformer: pre-norm, RMSNorm, rotary embedding with rotate-half pairing
+ * (element i pairs with i + d_head/2, angle = position * rope_theta^(-2i/d_head)),
+ * grouped-query causal attention, SwiGLU MLP, no biases, untied lm_head.
+ * dtype is the storage type of every weight and of the KV cache; PSD_BF16 models
+ * multiply on the bf16 matrix cores with fp32 accumulation and keep the residual
+ * stream in fp32, PSD_F32 models compute in fp32 throughout.
+ * Limits: d_head in {32, 64, 128}; n_q_heads a multiple of n_kv_heads;
+ * d_model, d_ffn and every projection width multiples of 32. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, d_head, d_ffn, vocab;
+    float rope_theta, rms_eps;
+    int32_t dtype;
+} psd_model_desc;
+
+const char *psd_status_string(psd_status s);
+/* hipError_t of the most recent failed launch on this host thread, as an int (0 = none). */
+int32_t psd_last_hip_error(void);
+
+/* weight_ptrs: n_ptrs = 3 + 9 * n_layers device pointers in this order:
+ *   embed [vocab, d_model];
+ *   per layer: attn_norm [d_model], wq [n_q_heads*d_head, d_model], wk [n_kv_heads*d_head, d_model],
+ *              wv [n_kv_heads*d_head, d_model], wo [d_model, n_q_heads*d_head], ffn_norm [d_model],
+ *              w_gate [d_ffn, d_model], w_up [d_ffn, d_model], w_down [d_model, d_ffn];
+ *   final_norm [d_model]; lm_head [vocab, d_model].
+ * Every matrix is row-major [out_features, in_features] (in_features contiguous), 16-byte
+ * aligned, of the model's dtype.  Pointers may alias another model's (a draft that shares
+ * the target's embed / lm_head).  On success *out is a new handle. */
+psd_status psd_model_create(const psd_model_desc *desc, const void *const *weight_ptrs,
+                            int32_t n_ptrs, psd_model **out);
+psd_status psd_model_destroy(psd_model *m);
+
+/* Bytes of workspace psd_model_forward needs for this batch / n_new / cache length
+ * (0 on a bad argument).  The workspace must be 256-byte aligned. */
+size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_new, int32_t max_len);
+
+/* KV cache descriptor over caller memory.  Layout (elements of the model's dtype):
+ *   k_mem [n_layers][batch][n_kv_heads][max_len][d_head]
+ *   v_mem [n_layers][batch][n_kv_heads][d_head][max_len]     (V is stored transposed)
+ * each of psd_kv_bytes() bytes, 256-byte aligned; max_len a multiple of 64.
+ * lens_dev: device int32[batch], the number of valid positions per sequence; the caller
+ * initialises it and states an upper bound of its entries in len_upper_bound (the host
+ * never reads lens_dev; it tracks only this bound for capacity checks).  Positions at or
+ * beyond lens[b] may hold anything. */
+size_t psd_kv_bytes(const psd_model *m, int32_t batch, int32_t max_len);
+psd_status psd_kv_create(const psd_model *m, int32_t batch, int32_t max_len, void *k_mem,
+                         void *v_mem, int32_t *lens_dev, int32_t len_upper_bound, psd_kv **out);
+psd_status psd_kv_destroy(psd_kv *kv);
+/* The host-side upper bound of lens (for tests and capacity planning). */
+int32_t psd_kv_len_upper_bound(const psd_kv *kv);
+
+/* One forward pass of M_i over n_new tokens per sequence (Sec. 3.1; Algorithm 1's
+ * "M_2(x_<=t, x~_1:K)" / "M_1(x_<=t, accepted)").
+ *   tokens_dev     device int32[batch][n_new]; sequence b's tokens go to positions
+ *                  lens[b] .. lens[b]+n_new-1.  Ids outside [0, vocab) are clamped.
+ *   n_logit_rows   0..n_new: the lm_head is applied to the LAST n_logit_rows rows only
+ *                  (0 for a prefill that needs no logits).
+ *   logits_out_dev device fp32[batch][n_logit_rows][vocab]; row r is the distribution of
+ *                  the token that follows input token n_new - n_logit_rows + r.
+ *                  May be NULL iff n_logit_rows == 0.
+ * Appends the new rows' K/V to the cache and advances lens[b] by n_new (on the stream).
+ * PSD_ERR_CAPACITY if len_upper_bound + n_new > max_len. */
+psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
+                             float *logits_out_dev, int32_t n_logit_rows, void *workspace,
+                             size_t ws_bytes, void *hip_stream);
+
+/* Speculative-sampling acceptance for `rows` independent sequences (VERIFY loop of
+ * Algorithm 1 with its break; the rule keeps the verifier's distribution, Sec. 3.1).
+ *   p_logits   device [rows][n_p_rows][vocab] verifier logits, n_p_rows = gamma or gamma+1;
+ *              consecutive sequences are p_seq_stride elements apart, rows are dense
+ *   q_logits   device [rows][gamma][vocab] drafter logits, q_seq_stride likewise
+ *   dtype      PSD_F32 or PSD_BF16, the same for both
+ *   draft_tokens device int32[rows][gamma], each in [0, vocab)
+ *   uniforms   device fp32[rows][gamma+1] in [0,1): u[j] decides position j, u[gamma]
+ *              drives the single inverse-CDF draw
+ *   temperature both distributions are softmax(logits / temperature), temperature > 0
+ * For each sequence, with p_j, q_j the softmaxes of position j: accept x_j iff
+ * u_j < min(1, p_j[x_j]/q_j[x_j]), stop at the first failure; n = number accepted.
+ *   out_accept_len device int32[rows] <- n in [0, gamma]
+ *   out_token  device int32[rows] <- if n < gamma: smallest k with
+ *              sum_{i<=k} r_i > u_gamma * sum_i r_i, r = max(0, p_n - q_n) (r = p_n if that
+ *              sum is 0); if n == gamma and n_p_rows == gamma+1: the same draw with
+ *              r = p_gamma; else -1
+ *   out_flags  device int32[rows] or NULL <- PSD_FLAG_* bits
+ * The ratio test runs in fp32 (softmax statistics by wavefront reductions); the draw runs
+ * in fp64 in a fixed summation order, so it is reproducible bit for bit.
+ * gamma = 0 with n_p_rows = 1 is plain sampling from softmax(p_0 / temperature).
+ * Limits: 0 <= gamma <= 64, vocab >= 1, rows >= 0 (rows = 0 is a no-op). */
+size_t psd_spec_accept_workspace_bytes(int32_t rows, int32_t gamma, int32_t n_p_rows, int32_t vocab);
+psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int32_t *draft_tokens,
+                           int32_t gamma, const float *uniforms, float temperature,
+                           int32_t *out_accept_len, int32_t *out_token,
+                           int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype,
+                           int64_t p_seq_stride, int64_t q_seq_stride, int32_t *out_flags,
+                           void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Rollback after verification (Sec. 3.3): on the stream, for every sequence b,
+ *   lens[b] <- min(lens[b], base_lens_dev[b] + keep_dev[b] + keep_offset)   (never below 0).
+ * base_lens_dev / keep_dev are device int32[batch] (e.g. the lengths before the verify
+ * forward and psd_spec_accept's out_accept_len; keep_offset = 1 keeps the x* row too).
+ * No data moves; stale rows are overwritten by the next append. */
+psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *keep_dev,
+                           int32_t keep_offset, void *hip_stream);
+/* Host-scalar variant: lens[b] <- min(lens[b], new_len) for all b; also lowers the host
+ * upper bound to new_len. */
+psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSD_H */

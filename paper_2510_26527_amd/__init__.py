@@ -1,0 +1,160 @@
+"""Python binding of libpsd (include/psd.h): argument marshalling only.
+
+Every function has the name and the argument order of its C entry point and takes
+torch tensors (device memory) where the C call takes device pointers; PyTorch is used for
+allocation and streams, nothing is computed here.  There is no fallback: if the HIP
+library has not been built (python -m paper_2510_26527_amd.build) or cannot be loaded,
+the first call raises.
+"""
+import ctypes
+import os
+
+PSD_OK = 0
+PSD_ERR_NULL, PSD_ERR_SHAPE, PSD_ERR_DTYPE, PSD_ERR_CAPACITY = -1, -2, -3, -4
+PSD_ERR_TEMPERATURE, PSD_ERR_WORKSPACE, PSD_ERR_HIP, PSD_ERR_UNIMPLEMENTED = -5, -6, -7, -8
+PSD_F32, PSD_BF16 = 0, 1
+PSD_FLAG_NEAR_TIE, PSD_FLAG_ZERO_RESIDUAL = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpsd.so")
+HEADER_PATH = os.path.join(os.path.dirname(_HERE), "include", "psd.h")
+
+_vp, _i32, _i64, _sz, _f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+
+
+class psd_model_desc(ctypes.Structure):
+    _fields_ = [("n_layers", _i32), ("d_model", _i32), ("n_q_heads", _i32), ("n_kv_heads", _i32),
+                ("d_head", _i32), ("d_ffn", _i32), ("vocab", _i32), ("rope_theta", _f32),
+                ("rms_eps", _f32), ("dtype", _i32)]
+
+
+_SIGNATURES = {
+    "psd_status_string": (ctypes.c_char_p, [_i32]),
+    "psd_last_hip_error": (_i32, []),
+    "psd_model_create": (_i32, [ctypes.POINTER(psd_model_desc), ctypes.POINTER(_vp), _i32, ctypes.POINTER(_vp)]),
+    "psd_model_destroy": (_i32, [_vp]),
+    "psd_model_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32]),
+    "psd_kv_bytes": (_sz, [_vp, _i32, _i32]),
+    "psd_kv_create": (_i32, [_vp, _i32, _i32, _vp, _vp, _vp, _i32, ctypes.POINTER(_vp)]),
+    "psd_kv_destroy": (_i32, [_vp]),
+    "psd_kv_len_upper_bound": (_i32, [_vp]),
+    "psd_model_forward": (_i32, [_vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "psd_spec_accept_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
+    "psd_spec_accept": (_i32, [_vp, _vp, _vp, _i32, _vp, _f32, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i64,
+                               _vp, _vp, _sz, _vp]),
+    "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _vp]),
+    "psd_kv_truncate_to": (_i32, [_vp, _i32, _vp]),
+}
+
+_lib = None
+
+
+class PsdError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib():
+    """The loaded shared library; raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2510_26527_amd.build`; "
+                               "there is no CPU fallback")
+        l = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def status_string(status):
+    return lib().psd_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != PSD_OK:
+        raise PsdError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def dtype_code(torch_dtype):
+    import torch
+    return {torch.float32: PSD_F32, torch.bfloat16: PSD_BF16}[torch_dtype]
+
+
+# ---------------------------------------------------------------- handles
+def psd_model_create(desc: psd_model_desc, weight_ptrs):
+    """weight_ptrs: device addresses (ints) in the header's order.  Returns the handle."""
+    arr = (_vp * len(weight_ptrs))(*weight_ptrs)
+    out = _vp()
+    _check(lib().psd_model_create(ctypes.byref(desc), arr, len(weight_ptrs), ctypes.byref(out)), "psd_model_create")
+    return out
+
+
+def psd_model_destroy(model):
+    _check(lib().psd_model_destroy(model), "psd_model_destroy")
+
+
+def psd_model_workspace_bytes(model, batch, n_new, max_len):
+    return lib().psd_model_workspace_bytes(model, batch, n_new, max_len)
+
+
+def psd_kv_bytes(model, batch, max_len):
+    return lib().psd_kv_bytes(model, batch, max_len)
+
+
+def psd_kv_create(model, batch, max_len, k_mem, v_mem, lens_dev, len_upper_bound):
+    out = _vp()
+    _check(lib().psd_kv_create(model, batch, max_len, _ptr(k_mem), _ptr(v_mem), _ptr(lens_dev), len_upper_bound,
+                               ctypes.byref(out)), "psd_kv_create")
+    return out
+
+
+def psd_kv_destroy(kv):
+    _check(lib().psd_kv_destroy(kv), "psd_kv_destroy")
+
+
+def psd_kv_len_upper_bound(kv):
+    return lib().psd_kv_len_upper_bound(kv)
+
+
+# ---------------------------------------------------------------- the hot path
+def psd_model_forward(model, tokens_dev, n_new, kv, logits_out_dev, n_logit_rows, workspace, stream=None):
+    _check(lib().psd_model_forward(model, _ptr(tokens_dev), n_new, kv, _ptr(logits_out_dev), n_logit_rows,
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream_ptr(stream)), "psd_model_forward")
+
+
+def psd_spec_accept_workspace_bytes(rows, gamma, n_p_rows, vocab):
+    return lib().psd_spec_accept_workspace_bytes(rows, gamma, n_p_rows, vocab)
+
+
+def psd_spec_accept(p_logits, q_logits, draft_tokens, gamma, uniforms, temperature, out_accept_len, out_token,
+                    rows, n_p_rows, vocab, dtype, p_seq_stride, q_seq_stride, out_flags, workspace, stream=None):
+    _check(lib().psd_spec_accept(_ptr(p_logits), _ptr(q_logits), _ptr(draft_tokens), gamma, _ptr(uniforms),
+                                 float(temperature), _ptr(out_accept_len), _ptr(out_token), rows, n_p_rows, vocab,
+                                 dtype, p_seq_stride, q_seq_stride, _ptr(out_flags), _ptr(workspace),
+                                 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                 _stream_ptr(stream)), "psd_spec_accept")
+
+
+def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, stream=None):
+    _check(lib().psd_kv_truncate(kv, _ptr(base_lens_dev), _ptr(keep_dev), keep_offset, _stream_ptr(stream)),
+           "psd_kv_truncate")
+
+
+def psd_kv_truncate_to(kv, new_len, stream=None):
+    _check(lib().psd_kv_truncate_to(kv, new_len, _stream_ptr(stream)), "psd_kv_truncate_to")

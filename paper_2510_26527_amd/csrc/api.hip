@@ -1,0 +1,346 @@
+// C ABI of the library (include/psd.h): argument validation on the host, workspace carving,
+// and the launch sequence of one forward pass.  No kernel lives here.
+#include <cmath>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "../../include/psd.h"
+#include "kernels.h"
+
+using namespace psd;
+
+struct psd_model {
+    psd_model_desc d;
+    std::vector<const void *> w;     // the caller's weight pointers, in header order
+    const void *embed() const { return w[0]; }
+    const void *layer(int l, int which) const { return w[1 + 9 * l + which]; }
+    const void *final_norm() const { return w[1 + 9 * d.n_layers]; }
+    const void *lm_head() const { return w[2 + 9 * d.n_layers]; }
+};
+enum { W_ATTN_NORM = 0, W_Q, W_K, W_V, W_O, W_FFN_NORM, W_GATE, W_UP, W_DOWN };
+
+struct psd_kv {
+    const psd_model *m;
+    int batch, max_len;
+    void *k, *v;
+    int32_t *lens;
+    int len_ub;                      // host upper bound of every lens[b]
+};
+
+static thread_local int32_t g_last_hip_error = 0;
+
+static psd_status check_launch() {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = (int32_t)e;
+        return PSD_ERR_HIP;
+    }
+    return PSD_OK;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+static size_t elem_size(int dtype) { return dtype == PSD_BF16 ? 2 : 4; }
+
+extern "C" {
+
+const char *psd_status_string(psd_status s) {
+    switch (s) {
+        case PSD_OK: return "ok";
+        case PSD_ERR_NULL: return "null pointer";
+        case PSD_ERR_SHAPE: return "unsupported shape";
+        case PSD_ERR_DTYPE: return "unsupported dtype";
+        case PSD_ERR_CAPACITY: return "KV cache capacity exceeded";
+        case PSD_ERR_TEMPERATURE: return "temperature must be finite and > 0";
+        case PSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PSD_ERR_HIP: return "HIP launch failed";
+        case PSD_ERR_UNIMPLEMENTED: return "not implemented";
+        default: return "unknown status";
+    }
+}
+
+int32_t psd_last_hip_error(void) { return g_last_hip_error; }
+
+psd_status psd_model_create(const psd_model_desc *desc, const void *const *weight_ptrs, int32_t n_ptrs,
+                            psd_model **out) {
+    if (!desc || !weight_ptrs || !out) return PSD_ERR_NULL;
+    const psd_model_desc &d = *desc;
+    if (d.dtype != PSD_F32 && d.dtype != PSD_BF16) return PSD_ERR_DTYPE;
+    if (d.n_layers < 0 || d.d_model <= 0 || d.n_q_heads <= 0 || d.n_kv_heads <= 0 || d.d_ffn <= 0 || d.vocab <= 0)
+        return PSD_ERR_SHAPE;
+    if (d.d_head != 32 && d.d_head != 64 && d.d_head != 128) return PSD_ERR_SHAPE;
+    if (d.n_q_heads % d.n_kv_heads) return PSD_ERR_SHAPE;
+    const int align = d.dtype == PSD_BF16 ? 128 : 32;      // the bf16 GEMMs step K by 128
+    if (d.d_model % align || d.d_ffn % align || (d.n_q_heads * d.d_head) % align) return PSD_ERR_SHAPE;
+    if (d.dtype == PSD_BF16 && d.d_head == 32) return PSD_ERR_SHAPE;
+    if (!(d.rope_theta > 0.f) || !(d.rms_eps >= 0.f)) return PSD_ERR_SHAPE;
+    if (n_ptrs != 3 + 9 * d.n_layers) return PSD_ERR_SHAPE;
+    for (int i = 0; i < n_ptrs; ++i) {
+        if (!weight_ptrs[i]) return PSD_ERR_NULL;
+        if ((uintptr_t)weight_ptrs[i] % 16) return PSD_ERR_SHAPE;
+    }
+    psd_model *m = new (std::nothrow) psd_model;
+    if (!m) return PSD_ERR_NULL;
+    m->d = d;
+    m->w.assign(weight_ptrs, weight_ptrs + n_ptrs);
+    *out = m;
+    return PSD_OK;
+}
+
+psd_status psd_model_destroy(psd_model *m) {
+    if (!m) return PSD_ERR_NULL;
+    delete m;
+    return PSD_OK;
+}
+
+size_t psd_kv_bytes(const psd_model *m, int32_t batch, int32_t max_len) {
+    if (!m || batch <= 0 || max_len <= 0 || max_len % 64) return 0;
+    return (size_t)m->d.n_layers * batch * m->d.n_kv_heads * max_len * m->d.d_head * elem_size(m->d.dtype);
+}
+
+psd_status psd_kv_create(const psd_model *m, int32_t batch, int32_t max_len, void *k_mem, void *v_mem,
+                         int32_t *lens_dev, int32_t len_upper_bound, psd_kv **out) {
+    if (!m || !k_mem || !v_mem || !lens_dev || !out) return PSD_ERR_NULL;
+    if (batch <= 0 || batch > 65535 || max_len <= 0 || max_len % 64) return PSD_ERR_SHAPE;
+    if (m->d.dtype == PSD_F32 && max_len > 12288) return PSD_ERR_SHAPE;   // fp32 attention keeps a row of scores in LDS
+    if (len_upper_bound < 0 || len_upper_bound > max_len) return PSD_ERR_CAPACITY;
+    if ((uintptr_t)k_mem % 256 || (uintptr_t)v_mem % 256) return PSD_ERR_SHAPE;
+    psd_kv *kv = new (std::nothrow) psd_kv;
+    if (!kv) return PSD_ERR_NULL;
+    kv->m = m; kv->batch = batch; kv->max_len = max_len; kv->k = k_mem; kv->v = v_mem;
+    kv->lens = lens_dev; kv->len_ub = len_upper_bound;
+    *out = kv;
+    return PSD_OK;
+}
+
+psd_status psd_kv_destroy(psd_kv *kv) {
+    if (!kv) return PSD_ERR_NULL;
+    delete kv;
+    return PSD_OK;
+}
+
+int32_t psd_kv_len_upper_bound(const psd_kv *kv) { return kv ? kv->len_ub : -1; }
+
+}  // extern "C"
+
+// ------------------------------------------------------------------ forward-pass workspace
+namespace {
+
+struct ForwardPlan {
+    int M, width_qkv;
+    int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
+    size_t off_x, off_xn, off_qkv, off_q, off_attn, off_gu, off_h, off_partial, off_po, off_pml, total;
+};
+
+ForwardPlan plan_forward(const psd_model_desc &d, int batch, int n_new, int n_logit_rows, int len_bound) {
+    ForwardPlan p{};
+    const int M = batch * n_new;
+    p.M = M;
+    const int hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
+    p.width_qkv = hd + 2 * kvd;
+    const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
+    p.sk_qkv = gemm_pick_splitk(d.dtype, M, d.d_model, p.width_qkv, n_qkv, 3);
+    p.sk_o = gemm_pick_splitk(d.dtype, M, hd, d.d_model, n_o, 1);
+    p.sk_gu = gemm_pick_splitk(d.dtype, M, d.d_model, 2 * d.d_ffn, n_gu, 2);
+    p.sk_down = gemm_pick_splitk(d.dtype, M, d.d_ffn, d.d_model, n_o, 1);
+    const int Ml = batch * n_logit_rows;
+    p.sk_head = Ml > 0 ? gemm_pick_splitk(d.dtype, Ml, d.d_model, d.vocab, n_v, 1) : 1;
+    p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
+    const size_t act = elem_size(d.dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align256(bytes); return o; };
+    p.off_x = take((size_t)M * d.d_model * 4);
+    p.off_xn = take((size_t)M * d.d_model * act);
+    p.off_qkv = take((size_t)M * p.width_qkv * 4);
+    p.off_q = take((size_t)M * hd * act);
+    p.off_attn = take((size_t)M * hd * act);
+    p.off_gu = take((size_t)M * 2 * d.d_ffn * 4);
+    p.off_h = take((size_t)M * d.d_ffn * act);
+    size_t part = 0;
+    auto need = [&](int sk, int rows, int N) { if (sk > 1) { const size_t b = (size_t)sk * rows * N * 4; if (b > part) part = b; } };
+    need(p.sk_qkv, M, p.width_qkv); need(p.sk_o, M, d.d_model); need(p.sk_gu, M, 2 * d.d_ffn);
+    need(p.sk_down, M, d.d_model); need(p.sk_head, Ml, d.vocab);
+    p.off_partial = take(part);
+    p.off_po = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * d.d_head * 4 : 0);
+    p.off_pml = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * 2 * 4 : 0);
+    p.total = off;
+    return p;
+}
+
+bool forward_shape_ok(const psd_model *m, int batch, int n_new) {
+    if (batch <= 0 || batch > 65535 || n_new <= 0) return false;
+    if ((long)batch * n_new > 65535) return false;
+    if ((long)(m->d.n_q_heads / m->d.n_kv_heads) * n_new > 4096) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_new, int32_t max_len) {
+    if (!m || max_len <= 0 || !forward_shape_ok(m, batch, n_new)) return 0;
+    // split choices depend on the cache length bound and on how many rows get logits:
+    // take the largest need over all of them
+    size_t worst = 0;
+    for (int rows = 0; rows <= n_new; ++rows) {
+        const size_t a = plan_forward(m->d, batch, n_new, rows, max_len).total;
+        const size_t b = plan_forward(m->d, batch, n_new, rows, n_new).total;
+        worst = a > worst ? a : worst;
+        worst = b > worst ? b : worst;
+    }
+    return worst;
+}
+
+psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
+                             float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
+                             void *hip_stream) {
+    if (!m || !tokens_dev || !kv) return PSD_ERR_NULL;
+    if (kv->m != m) return PSD_ERR_SHAPE;
+    const psd_model_desc &d = m->d;
+    const int B = kv->batch;
+    if (!forward_shape_ok(m, B, n_new)) return PSD_ERR_SHAPE;
+    if (n_logit_rows < 0 || n_logit_rows > n_new) return PSD_ERR_SHAPE;
+    if (n_logit_rows > 0 && !logits_out_dev) return PSD_ERR_NULL;
+    if (kv->len_ub + n_new > kv->max_len) return PSD_ERR_CAPACITY;
+    const int len_bound = kv->len_ub + n_new;
+    const ForwardPlan p = plan_forward(d, B, n_new, n_logit_rows, len_bound);
+    if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < p.total) return PSD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    float *x = (float *)(ws + p.off_x);
+    void *xn = ws + p.off_xn;
+    float *qkv = (float *)(ws + p.off_qkv);
+    void *q = ws + p.off_q;
+    void *attn = ws + p.off_attn;
+    float *gu = (float *)(ws + p.off_gu);
+    void *h = ws + p.off_h;
+    float *partial = (float *)(ws + p.off_partial);
+    const int M = p.M, hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
+    const size_t es = elem_size(d.dtype);
+    const size_t kv_layer = (size_t)B * d.n_kv_heads * kv->max_len * d.d_head * es;
+
+    (void)hipGetLastError();
+    launch_embed(d.dtype, m->embed(), tokens_dev, x, M, d.d_model, d.vocab, st);
+    for (int l = 0; l < d.n_layers; ++l) {
+        launch_rmsnorm(d.dtype, x, m->layer(l, W_ATTN_NORM), xn, M, d.d_model, d.rms_eps, d.d_model, st);
+        GemmArgs g{};
+        g.x = xn; g.w[0] = m->layer(l, W_Q); g.w[1] = m->layer(l, W_K); g.w[2] = m->layer(l, W_V);
+        g.n[0] = hd; g.n[1] = kvd; g.n[2] = kvd; g.nseg = 3;
+        g.M = M; g.K = d.d_model; g.N = p.width_qkv; g.out = qkv; g.ldo = p.width_qkv; g.accumulate = 0;
+        g.partial = partial; g.splitk = p.sk_qkv;
+        launch_gemm(d.dtype, g, st);
+
+        char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
+        launch_rope_append(d.dtype, qkv, q, kl, vl, kv->lens, B, n_new, d.n_q_heads, d.n_kv_heads, d.d_head,
+                           kv->max_len, d.rope_theta, st);
+        AttnArgs a{};
+        a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn;
+        a.B = B; a.R = n_new; a.h_q = d.n_q_heads; a.h_kv = d.n_kv_heads; a.d_h = d.d_head; a.max_len = kv->max_len;
+        a.len_bound = len_bound; a.part_o = (float *)(ws + p.off_po); a.part_ml = (float *)(ws + p.off_pml);
+        a.splits = p.attn_splits;
+        launch_attention(d.dtype, a, st);
+
+        GemmArgs o{};
+        o.x = attn; o.w[0] = m->layer(l, W_O); o.n[0] = d.d_model; o.nseg = 1;
+        o.M = M; o.K = hd; o.N = d.d_model; o.out = x; o.ldo = d.d_model; o.accumulate = 1;
+        o.partial = partial; o.splitk = p.sk_o;
+        launch_gemm(d.dtype, o, st);
+
+        launch_rmsnorm(d.dtype, x, m->layer(l, W_FFN_NORM), xn, M, d.d_model, d.rms_eps, d.d_model, st);
+        GemmArgs u{};
+        u.x = xn; u.w[0] = m->layer(l, W_GATE); u.w[1] = m->layer(l, W_UP); u.n[0] = d.d_ffn; u.n[1] = d.d_ffn; u.nseg = 2;
+        u.M = M; u.K = d.d_model; u.N = 2 * d.d_ffn; u.out = gu; u.ldo = 2 * d.d_ffn; u.accumulate = 0;
+        u.partial = partial; u.splitk = p.sk_gu;
+        launch_gemm(d.dtype, u, st);
+        launch_swiglu(d.dtype, gu, h, M, d.d_ffn, st);
+
+        GemmArgs dn{};
+        dn.x = h; dn.w[0] = m->layer(l, W_DOWN); dn.n[0] = d.d_model; dn.nseg = 1;
+        dn.M = M; dn.K = d.d_ffn; dn.N = d.d_model; dn.out = x; dn.ldo = d.d_model; dn.accumulate = 1;
+        dn.partial = partial; dn.splitk = p.sk_down;
+        launch_gemm(d.dtype, dn, st);
+    }
+    if (n_logit_rows > 0) {
+        // final norm + lm_head on the last n_logit_rows rows of every sequence
+        const int Ml = B * n_logit_rows;
+        if (n_logit_rows == n_new) {
+            launch_rmsnorm(d.dtype, x, m->final_norm(), xn, M, d.d_model, d.rms_eps, d.d_model, st);
+        } else {
+            for (int b = 0; b < B; ++b)
+                launch_rmsnorm(d.dtype, x + ((size_t)b * n_new + (n_new - n_logit_rows)) * d.d_model, m->final_norm(),
+                               (char *)xn + (size_t)b * n_logit_rows * d.d_model * es, n_logit_rows, d.d_model,
+                               d.rms_eps, d.d_model, st);
+        }
+        GemmArgs hg{};
+        hg.x = xn; hg.w[0] = m->lm_head(); hg.n[0] = d.vocab; hg.nseg = 1;
+        hg.M = Ml; hg.K = d.d_model; hg.N = d.vocab; hg.out = logits_out_dev; hg.ldo = d.vocab; hg.accumulate = 0;
+        hg.partial = partial; hg.splitk = p.sk_head;
+        launch_gemm(d.dtype, hg, st);
+    }
+    launch_advance_lens(kv->lens, B, n_new, kv->max_len, st);
+    const psd_status s = check_launch();
+    if (s == PSD_OK) kv->len_ub += n_new;
+    return s;
+}
+
+size_t psd_spec_accept_workspace_bytes(int32_t rows, int32_t gamma, int32_t n_p_rows, int32_t vocab) {
+    if (rows < 0 || gamma < 0 || gamma > 64 || vocab <= 0) return 0;
+    if (n_p_rows != gamma && n_p_rows != gamma + 1) return 0;
+    AcceptArgs a{};
+    accept_plan(rows, gamma, n_p_rows, vocab, PSD_F32, false, &a);   // the unaligned plan needs the most
+    return accept_workspace_bytes(a);
+}
+
+psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int32_t *draft_tokens, int32_t gamma,
+                           const float *uniforms, float temperature, int32_t *out_accept_len, int32_t *out_token,
+                           int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype, int64_t p_seq_stride,
+                           int64_t q_seq_stride, int32_t *out_flags, void *workspace, size_t ws_bytes,
+                           void *hip_stream) {
+    if (dtype != PSD_F32 && dtype != PSD_BF16) return PSD_ERR_DTYPE;
+    if (rows < 0 || gamma < 0 || gamma > 64 || vocab <= 0) return PSD_ERR_SHAPE;
+    if (n_p_rows != gamma && n_p_rows != gamma + 1) return PSD_ERR_SHAPE;
+    if (gamma == 0 && n_p_rows == 0) return PSD_ERR_SHAPE;
+    if ((long)rows * (n_p_rows + gamma) > (1L << 24)) return PSD_ERR_SHAPE;
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) return PSD_ERR_TEMPERATURE;
+    if (rows == 0) return PSD_OK;
+    if (!p_logits || !uniforms || !out_accept_len || !out_token) return PSD_ERR_NULL;
+    if (gamma > 0 && (!q_logits || !draft_tokens)) return PSD_ERR_NULL;
+    if (p_seq_stride < (int64_t)n_p_rows * vocab || (gamma > 0 && q_seq_stride < (int64_t)gamma * vocab))
+        return PSD_ERR_SHAPE;
+    const size_t es = elem_size(dtype);
+    if ((uintptr_t)p_logits % es || (uintptr_t)q_logits % es) return PSD_ERR_SHAPE;
+    const int epl = (int)(16 / es);
+    const bool vec = vocab % epl == 0 && p_seq_stride % epl == 0 && q_seq_stride % epl == 0 &&
+                     (uintptr_t)p_logits % 16 == 0 && (uintptr_t)q_logits % 16 == 0;
+    AcceptArgs a{};
+    accept_plan(rows, gamma, n_p_rows, vocab, dtype, vec, &a);
+    if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < accept_workspace_bytes(a)) return PSD_ERR_WORKSPACE;
+    accept_bind_workspace(&a, workspace, out_flags);
+    a.p = p_logits; a.q = q_logits; a.x = draft_tokens; a.u = uniforms;
+    a.p_stride = p_seq_stride; a.q_stride = q_seq_stride; a.temperature = temperature;
+    a.out_n = out_accept_len; a.out_tok = out_token;
+    (void)hipGetLastError();
+    launch_accept(a, vec, (hipStream_t)hip_stream);
+    return check_launch();
+}
+
+psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *keep_dev, int32_t keep_offset,
+                           void *hip_stream) {
+    if (!kv || !base_lens_dev || !keep_dev) return PSD_ERR_NULL;
+    (void)hipGetLastError();
+    launch_truncate(kv->lens, base_lens_dev, keep_dev, keep_offset, kv->batch, (hipStream_t)hip_stream);
+    return check_launch();
+}
+
+psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream) {
+    if (!kv) return PSD_ERR_NULL;
+    if (new_len < 0) return PSD_ERR_SHAPE;
+    (void)hipGetLastError();
+    launch_truncate_to(kv->lens, new_len, kv->batch, (hipStream_t)hip_stream);
+    const psd_status s = check_launch();
+    if (s == PSD_OK && new_len < kv->len_ub) kv->len_ub = new_len;
+    return s;
+}
+
+}  // extern "C"

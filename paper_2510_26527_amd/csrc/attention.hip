@@ -1,0 +1,314 @@
+// Verify attention on gfx950: the n_new query rows of a verify step against the model's KV
+// cache, causal among the new rows, grouped-query heads sharing their K/V loads.
+//
+//   attn_simple_kernel   any dtype, one wavefront per (sequence, row, head): scores to LDS,
+//                        softmax, then P.V.  Used by fp32 models (parity, not speed).
+//   attn_mfma_kernel     bf16.  Split over the KV length (grid.x) and, inside a block, over its
+//                        four wavefronts; each wavefront streams 64-key tiles of K and of the
+//                        transposed V straight from HBM into MFMA operand registers with
+//                        16-byte loads, computes S^T = K Q^T and O^T += V^T P^T on the matrix
+//                        cores for up to 64 query rows (all heads of the group x all new rows),
+//                        and keeps an online softmax per query column with two cross-lane
+//                        shuffles.  Wavefronts are merged through LDS in a fixed order, splits
+//                        by attn_combine_kernel.
+//
+// Why V is stored transposed ([d_head][max_len]): the contraction index of P.V is the key, and an
+// MFMA operand wants 8 consecutive contraction values per lane; with V^T those are one 16-byte
+// load, and the score accumulator of S^T = K Q^T already holds P^T in exactly the operand layout
+// the second MFMA needs (keys are numbered kb + 8g + 4t + v so that the two 16-key score tiles
+// of a lane are 8 consecutive keys).
+#include "common.h"
+#include "kernels.h"
+#include "../../include/psd.h"
+
+namespace psd {
+namespace {
+
+template <typename TA, typename TC>
+__global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a, float scale) {
+    extern __shared__ float sc[];
+    const int lane = threadIdx.x;
+    const int h = blockIdx.x, m = blockIdx.y, b = m / a.R, r = m % a.R;
+    const int d_h = a.d_h;
+    const int n_keys = min(a.lens[b] + r + 1, a.max_len);
+    const int hk = h / (a.h_q / a.h_kv);
+    const TA *q = (const TA *)a.q + ((size_t)m * a.h_q + h) * d_h;
+    const TC *K = (const TC *)a.k + ((size_t)b * a.h_kv + hk) * a.max_len * d_h;
+    const TC *Vt = (const TC *)a.v + ((size_t)b * a.h_kv + hk) * d_h * (size_t)a.max_len;
+    float mx = -INFINITY;
+    for (int k = lane; k < n_keys; k += 64) {
+        float s = 0.f;
+        for (int d = 0; d < d_h; ++d) s += load_elem(q, d) * load_elem(K, (size_t)k * d_h + d);
+        s *= scale;
+        sc[k] = s;
+        mx = fmaxf(mx, s);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int k = lane; k < n_keys; k += 64) {
+        const float e = expf(sc[k] - mx);
+        sc[k] = e;
+        sum += e;
+    }
+    sum = wave_sum(sum);
+    __syncthreads();
+    TA *out = (TA *)a.out + ((size_t)m * a.h_q + h) * d_h;
+    for (int d = lane; d < d_h; d += 64) {
+        float acc = 0.f;
+        for (int k = 0; k < n_keys; ++k) acc += sc[k] * load_elem(Vt, (size_t)d * a.max_len + k);
+        store_elem(out, d, acc / sum);
+    }
+}
+
+constexpr int kKeysPerWaveIter = 64;
+constexpr int kKeysPerBlockIter = 256;
+
+template <int DH, int QT>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_log2, int range) {
+    constexpr int KS = DH / 32;      // MFMA k-steps of S^T = K Q^T
+    constexpr int DT = DH / 16;      // 16-row d tiles of O^T
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int split = blockIdx.x, qchunk = blockIdx.y;
+    const int b = blockIdx.z / a.h_kv, hk = blockIdx.z % a.h_kv;
+    const int group = a.h_q / a.h_kv;
+    const int NQ = group * a.R;
+    const int S_b = a.lens[b];
+    const int n_keys = min(S_b + a.R, a.max_len);
+    const int kb0 = split * range, kb1 = min(n_keys, kb0 + range);
+    const size_t max_len = a.max_len;
+    const uint16_t *Kc = (const uint16_t *)a.k + ((size_t)b * a.h_kv + hk) * max_len * DH;
+    const uint16_t *Vt = (const uint16_t *)a.v + ((size_t)b * a.h_kv + hk) * DH * max_len;
+
+    // Q operand (B of S^T = K Q^T): column i of tile qt is query q0 + qt*16 + i; lane group g
+    // holds d_head elements [g*DH/4, (g+1)*DH/4), k-step s the 8 starting at 8*s inside them.
+    bf16x8 qb[QT][KS];
+    int limit[QT];                   // last key this lane's query may see, -1 for a padding column
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int qi = (qchunk * QT + qt) * 16 + i;
+        const bool valid = qi < NQ;
+        const int hl = valid ? qi / a.R : 0, r = valid ? qi % a.R : 0;
+        limit[qt] = valid ? S_b + r : -1;
+        const uint16_t *qp = (const uint16_t *)a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            bf16x8 v = *reinterpret_cast<const bf16x8 *>(qp + 8 * s);
+            if (!valid) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            qb[qt][s] = v;
+        }
+    }
+
+    f32x4 o[QT][DT];
+    float mrun[QT], lrun[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        mrun[qt] = -INFINITY;
+        lrun[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int kt = kb0 + wave * kKeysPerWaveIter; kt < kb1; kt += kKeysPerBlockIter) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int kb = kt + sub * 32;
+            if (kb >= kb1) break;
+            // K rows of the two 16-key score tiles: row i of tile t is key kb + 8*(i/4) + 4*t + i%4
+            bf16x8 ka[2][KS];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int key = kb + 8 * (i >> 2) + 4 * t + (i & 3);     // < max_len: kb + 32 <= max_len
+                const uint16_t *kp = Kc + (size_t)key * DH + g * (DH / 4);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) ka[t][s] = *reinterpret_cast<const bf16x8 *>(kp + 8 * s);
+            }
+            // V^T rows d = dt*16 + i, keys kb + 8g .. kb + 8g + 7
+            bf16x8 va[DT];
+            const bool tail = kb + 32 > n_keys;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + (size_t)(dt * 16 + i) * max_len + kb + 8 * g);
+                if (tail) {          // stale cache rows may hold anything, even NaN: zero them
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int key = kb + 8 * g + 2 * e;
+                        if (key >= n_keys) raw[e] = 0u;
+                        else if (key + 1 >= n_keys) raw[e] &= 0xffffu;
+                    }
+                }
+                va[dt] = __builtin_bit_cast(bf16x8, raw);
+            }
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                f32x4 c[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < KS; ++s)
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qb[qt][s], c[t], 0, 0, 0);
+                }
+                // lane (query column i, group g): c[t][v] is key kb + 8g + 4t + v
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int key = kb + 8 * g + 4 * t + v;
+                        const float s = key <= limit[qt] ? c[t][v] * scale_log2 : -INFINITY;
+                        c[t][v] = s;
+                        tmax = fmaxf(tmax, s);
+                    }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                const float mnew = fmaxf(mrun[qt], tmax);
+                float alpha = 1.f;
+                float p[8];
+                if (mnew > -INFINITY) {
+                    alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+                    float ps = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        p[e] = __builtin_amdgcn_exp2f(c[e >> 2][e & 3] - mnew);
+                        ps += p[e];
+                    }
+                    lrun[qt] = lrun[qt] * alpha + ps;
+                    mrun[qt] = mnew;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p[e] = 0.f;
+                }
+                u32x4 praw;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) praw[e] = pack_bf16x2(p[2 * e], p[2 * e + 1]);
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, praw);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, o[qt][dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- merge the four wavefronts in wavefront order through LDS
+    __shared__ float sm_o[QT * 16][DH + 1];
+    __shared__ float sm_m[QT * 16], sm_l[QT * 16];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        lrun[qt] += __shfl_xor(lrun[qt], 16, 64);
+        lrun[qt] += __shfl_xor(lrun[qt], 32, 64);
+    }
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                const int qc = qt * 16 + i;
+                float fo = 0.f, fn = 1.f, M = mrun[qt], L = lrun[qt];
+                if (w > 0) {
+                    const float mo = sm_m[qc], lo = sm_l[qc];
+                    M = fmaxf(mo, mrun[qt]);
+                    fo = mo > -INFINITY ? __builtin_amdgcn_exp2f(mo - M) : 0.f;
+                    fn = mrun[qt] > -INFINITY ? __builtin_amdgcn_exp2f(mrun[qt] - M) : 0.f;
+                    L = lo * fo + lrun[qt] * fn;
+                }
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int d = dt * 16 + 4 * g + v;
+                        const float mine = o[qt][dt][v] * fn;
+                        sm_o[qc][d] = w > 0 ? sm_o[qc][d] * fo + mine : mine;
+                    }
+                __builtin_amdgcn_wave_barrier();
+                if (g == 0) { sm_m[qc] = M; sm_l[qc] = L; }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- write: directly when there is one split, else the unnormalised partial
+    for (int e = threadIdx.x; e < QT * 16 * DH; e += 256) {
+        const int qc = e / DH, d = e % DH;
+        const int qi = qchunk * QT * 16 + qc;
+        if (qi >= NQ) continue;
+        const int hl = qi / a.R, r = qi % a.R;
+        const size_t row = ((size_t)(b * a.R + r)) * a.h_q + hk * group + hl;       // [B][R][h_q]
+        if (a.splits == 1) {
+            ((uint16_t *)a.out)[row * DH + d] = (uint16_t)f32_to_bf16_bits(sm_o[qc][d] / sm_l[qc]);
+        } else {
+            a.part_o[(row * a.splits + split) * DH + d] = sm_o[qc][d];
+            if (d == 0) {
+                a.part_ml[(row * a.splits + split) * 2] = sm_m[qc];
+                a.part_ml[(row * a.splits + split) * 2 + 1] = sm_l[qc];
+            }
+        }
+    }
+}
+
+// one block per (sequence, row, head); thread d merges the splits in split order
+__global__ void attn_combine_kernel(AttnArgs a) {
+    const size_t row = blockIdx.x;
+    const int d = threadIdx.x, DH = a.d_h;
+    const float *ml = a.part_ml + row * a.splits * 2;
+    float M = -INFINITY;
+    for (int s = 0; s < a.splits; ++s) M = fmaxf(M, ml[2 * s]);
+    float L = 0.f, acc = 0.f;
+    for (int s = 0; s < a.splits; ++s) {
+        const float ms = ml[2 * s];
+        if (!(ms > -INFINITY)) continue;
+        const float f = __builtin_amdgcn_exp2f(ms - M);
+        L += ml[2 * s + 1] * f;
+        acc += a.part_o[(row * a.splits + s) * DH + d] * f;
+    }
+    ((uint16_t *)a.out)[row * DH + d] = (uint16_t)f32_to_bf16_bits(acc / L);
+}
+
+inline int q_tiles(int NQ) { return NQ <= 16 ? 1 : (NQ <= 32 ? 2 : 4); }
+
+}  // namespace
+
+int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound) {
+    (void)d_h;
+    if (dtype != PSD_BF16) return 1;
+    const int NQ = (h_q / h_kv) * R;
+    const int QT = q_tiles(NQ);
+    const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
+    const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
+    int by_grid = 1024 / (B * h_kv * chunks);
+    if (by_grid < 1) by_grid = 1;
+    int s = by_len < by_grid ? by_len : by_grid;
+    return s < 1 ? 1 : s;
+}
+
+template <int DH>
+static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
+    const int NQ = (a.h_q / a.h_kv) * a.R;
+    const int QT = q_tiles(NQ);
+    const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
+    int range = (a.len_bound + a.splits - 1) / a.splits;
+    range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+    dim3 grid(a.splits, chunks, a.B * a.h_kv);
+    if (QT == 1) attn_mfma_kernel<DH, 1><<<grid, 256, 0, stream>>>(a, scale_log2, range);
+    else if (QT == 2) attn_mfma_kernel<DH, 2><<<grid, 256, 0, stream>>>(a, scale_log2, range);
+    else attn_mfma_kernel<DH, 4><<<grid, 256, 0, stream>>>(a, scale_log2, range);
+    if (a.splits > 1) attn_combine_kernel<<<a.B * a.R * a.h_q, DH, 0, stream>>>(a);
+}
+
+void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream) {
+    if (dtype == PSD_BF16 && (a.d_h == 128 || a.d_h == 64)) {
+        if (a.d_h == 128) launch_mfma<128>(a, stream);
+        else launch_mfma<64>(a, stream);
+        return;
+    }
+    const float scale = 1.0f / sqrtf((float)a.d_h);
+    dim3 grid(a.h_q, a.B * a.R);
+    const size_t smem = (size_t)a.len_bound * sizeof(float);
+    if (dtype == PSD_BF16) attn_simple_kernel<uint16_t, uint16_t><<<grid, 64, smem, stream>>>(a, scale);
+    else attn_simple_kernel<float, float><<<grid, 64, smem, stream>>>(a, scale);
+}
+
+}  // namespace psd

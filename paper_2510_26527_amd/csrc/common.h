@@ -1,0 +1,52 @@
+// Shared device helpers for the gfx950 kernels: bf16 conversion, wavefront (64-lane)
+// reductions, MFMA operand types.  Host code includes it only for the typedefs.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace psd {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;   // one MFMA A/B operand (8 k-values)
+typedef __attribute__((ext_vector_type(4))) float f32x4;     // 16x16 MFMA accumulator
+typedef __attribute__((ext_vector_type(16))) float f32x16;   // 32x32 MFMA accumulator
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // a 16-byte load
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// round-to-nearest-even fp32 -> bf16 bit pattern (NaN stays NaN)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// element loads / stores by storage type
+__device__ __forceinline__ float load_elem(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const uint16_t *p, size_t i) { return bf16_bits_to_f32(p[i]); }
+__device__ __forceinline__ void store_elem(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_elem(uint16_t *p, size_t i, float v) { p[i] = (uint16_t)f32_to_bf16_bits(v); }
+
+template <typename T>
+__device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        T other = __shfl_xor(v, o, kWave);
+        v = other > v ? other : v;
+    }
+    return v;
+}
+// butterfly sum: every lane ends with the same value, summed in a fixed tree order
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+}  // namespace psd

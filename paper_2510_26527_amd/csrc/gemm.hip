@@ -1,0 +1,345 @@
+// Decoder projections y[m][n] = sum_k x[m][k] W[n][k] on gfx950.
+//
+// Three kernels, chosen by model dtype and row count M (M = batch * n_new of a verify step):
+//   gemm_f32_kernel          fp32 weights, plain ALU dot products, one wavefront per output
+//                            column (the tiny fp32 chain; fp32 1e-4 parity, not speed).
+//   gemm_bf16_skinny_kernel  M <= 64.  HBM-bound weight streaming: W rows go straight from
+//                            global memory into MFMA A-operand registers with 16-byte loads
+//                            (no LDS), the few activation rows are the B operand, K is split
+//                            over the four wavefronts of a block and over blocks.
+//   gemm_bf16_tiled_kernel   M > 64.  128x128x64 LDS-staged tiles, 32x32x16 bf16 MFMA.
+// Split-K partial sums are written to scratch and added in split order by a second kernel,
+// so results are bit-reproducible.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/psd.h"
+
+namespace psd {
+namespace {
+
+// ------------------------------------------------------------------------------ fp32
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + wave;
+    if (n >= g.N) return;
+    int seg = 0, nl = n;
+    while (seg < g.nseg - 1 && nl >= g.n[seg]) { nl -= g.n[seg]; ++seg; }
+    const float *wrow = (const float *)g.w[seg] + (size_t)nl * g.K;
+    const float *x = (const float *)g.x;
+    for (int m0 = 0; m0 < g.M; m0 += 8) {
+        float acc[8];
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm) acc[mm] = 0.f;
+        for (int k = lane; k < g.K; k += 64) {
+            const float w = wrow[k];
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm)
+                if (m0 + mm < g.M) acc[mm] += w * x[(size_t)(m0 + mm) * g.K + k];
+        }
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm) acc[mm] = wave_sum(acc[mm]);
+        if (lane == 0) {
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm)
+                if (m0 + mm < g.M) {
+                    float *o = g.out + (size_t)(m0 + mm) * g.ldo + n;
+                    *o = g.accumulate ? *o + acc[mm] : acc[mm];
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ bf16 helpers
+struct TileRef {
+    int seg;       // which weight matrix
+    int row0;      // first row of the tile inside that matrix
+    int col0;      // first output column of that matrix in the concatenated output
+};
+__device__ __forceinline__ TileRef find_tile(const GemmArgs &g, int tile, int tile_rows) {
+    TileRef t;
+    t.seg = 0;
+    t.col0 = 0;
+    while (t.seg < g.nseg - 1) {
+        const int nt = (g.n[t.seg] + tile_rows - 1) / tile_rows;
+        if (tile < nt) break;
+        tile -= nt;
+        t.col0 += g.n[t.seg];
+        ++t.seg;
+    }
+    t.row0 = tile * tile_rows;
+    return t;
+}
+
+__device__ __forceinline__ void store_out(const GemmArgs &g, int ks, int m, int col, float v) {
+    if (g.splitk > 1) {
+        g.partial[((size_t)ks * g.M + m) * g.N + col] = v;
+    } else {
+        float *o = g.out + (size_t)m * g.ldo + col;
+        *o = g.accumulate ? *o + v : v;
+    }
+}
+
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs g) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)g.M * g.N) return;
+    const size_t m = idx / g.N, col = idx % g.N;
+    float v = 0.f;
+    for (int ks = 0; ks < g.splitk; ++ks) v += g.partial[(size_t)ks * g.M * g.N + idx];
+    float *o = g.out + m * g.ldo + col;
+    *o = g.accumulate ? *o + v : v;
+}
+
+// ------------------------------------------------------------------------------ bf16 skinny
+// Block = 4 wavefronts, one 64-row tile of W (4 strips of 16 rows per wavefront, all four
+// wavefronts on the same rows, each on its own K range).  Per 128-wide K step a lane issues
+// 16 independent 16-byte loads of W (4 strips x 4) and keeps the next step's loads in flight
+// while the current one feeds the MFMAs.  The K index inside a step is permuted so that a
+// lane's four loads of one row are 2 x 32 contiguous bytes and the four lane groups of a row
+// cover 2 x 128 contiguous bytes; the activation operand uses the same permutation.
+constexpr int kSkinnyRows = 64;
+constexpr int kSkinnyStepK = 128;
+
+template <int MT>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, gq = lane >> 4;
+    const TileRef t = find_tile(g, blockIdx.x, kSkinnyRows);
+    const int seg_rows = g.n[t.seg];
+    const uint16_t *W = (const uint16_t *)g.w[t.seg];
+    const uint16_t *X = (const uint16_t *)g.x;
+    const int K = g.K;
+
+    const int nsteps = K / kSkinnyStepK;
+    const int S = g.splitk * 4, slot = blockIdx.y * 4 + wave;
+    const int s0 = (int)((long)slot * nsteps / S), s1 = (int)((long)(slot + 1) * nsteps / S);
+
+    const uint16_t *wp[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int r = min(t.row0 + s * 16 + i, seg_rows - 1);
+        wp[s] = W + (size_t)r * K + gq * 16;
+    }
+    const uint16_t *xp[MT];
+    bool xvalid[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int tok = mt * 16 + i;
+        xvalid[mt] = tok < g.M;
+        xp[mt] = X + (size_t)min(tok, g.M - 1) * K + gq * 16;
+    }
+
+    f32x4 acc[4][MT];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    bf16x8 a_cur[4][4], a_nxt[4][4];
+    auto load_a = [&](bf16x8 (&dst)[4][4], int step) {
+        const int kk = step * kSkinnyStepK;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                dst[s][q] = *reinterpret_cast<const bf16x8 *>(wp[s] + kk + (q >> 1) * 64 + (q & 1) * 8);
+    };
+    if (s0 < s1) load_a(a_cur, s0);
+    for (int step = s0; step < s1; ++step) {
+        if (step + 1 < s1) load_a(a_nxt, step + 1);
+        const int kk = step * kSkinnyStepK;
+        bf16x8 bx[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x8 v = *reinterpret_cast<const bf16x8 *>(xp[mt] + kk + (q >> 1) * 64 + (q & 1) * 8);
+                if (!xvalid[mt]) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                bx[mt][q] = v;
+            }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_cur[s][q], bx[mt][q], acc[s][mt], 0, 0, 0);
+        if (step + 1 < s1) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a_cur[s][q] = a_nxt[s][q];
+        }
+    }
+
+    // acc[s][mt][v] = y[token mt*16 + i][row0 + s*16 + 4*gq + v]: add the four wavefronts (K split)
+    __shared__ float red[4][kSkinnyRows][17];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if (mt) __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][mt][v];
+        __syncthreads();
+        const int nn = threadIdx.x & 63;
+        const int row = t.row0 + nn;
+        if (row < seg_rows) {
+            for (int mm = threadIdx.x >> 6; mm < 16; mm += 4) {
+                const int tok = mt * 16 + mm;
+                if (tok < g.M) {
+                    const float v = ((red[0][nn][mm] + red[1][nn][mm]) + red[2][nn][mm]) + red[3][nn][mm];
+                    store_out(g, blockIdx.y, tok, t.col0 + row, v);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ bf16 tiled
+constexpr int kBM = 128, kBN = 128, kBK = 64, kLdsStride = 72;   // 72 elements = 144 B rows: no bank conflicts
+
+__global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[kBM * kLdsStride];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[kBN * kLdsStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int m_tiles = (g.M + kBM - 1) / kBM;
+    const int mt = blockIdx.x % m_tiles;                 // M tiles of one W tile are neighbours: W is re-read from L2
+    const TileRef t = find_tile(g, blockIdx.x / m_tiles, kBN);
+    const int seg_rows = g.n[t.seg];
+    const uint16_t *W = (const uint16_t *)g.w[t.seg];
+    const uint16_t *X = (const uint16_t *)g.x;
+    const int K = g.K;
+    const int nk = K / kBK;
+    const int k0 = (int)((long)blockIdx.y * nk / g.splitk), k1 = (int)((long)(blockIdx.y + 1) * nk / g.splitk);
+    const int m_base = mt * kBM;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;   // this wavefront's 64x64 sub-tile
+
+    // global -> register staging: 4 x 16 bytes of X and of W per thread and K tile
+    const uint16_t *xg[4], *wg[4];
+    int lds_off[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
+        xg[c] = X + (size_t)min(m_base + row, g.M - 1) * K + col;
+        wg[c] = W + (size_t)min(t.row0 + row, seg_rows - 1) * K + col;
+        lds_off[c] = row * kLdsStride + col;
+    }
+    u32x4 xr[4], wr[4];
+    auto load_tiles = [&](int kt) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            xr[c] = *reinterpret_cast<const u32x4 *>(xg[c] + (size_t)kt * kBK);
+            wr[c] = *reinterpret_cast<const u32x4 *>(wg[c] + (size_t)kt * kBK);
+        }
+    };
+    auto store_tiles = [&]() {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            *reinterpret_cast<u32x4 *>(&Xs[lds_off[c]]) = xr[c];
+            *reinterpret_cast<u32x4 *>(&Ws[lds_off[c]]) = wr[c];
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    if (k0 < k1) {
+        load_tiles(k0);
+        store_tiles();
+    }
+    __syncthreads();
+    for (int kt = k0; kt < k1; ++kt) {
+        if (kt + 1 < k1) load_tiles(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < kBK / 16; ++ks) {
+            bf16x8 fa[2], fb[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                fa[a] = *reinterpret_cast<const bf16x8 *>(&Xs[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                fb[b] = *reinterpret_cast<const bf16x8 *>(&Ws[(wn + b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+        if (kt + 1 < k1) store_tiles();
+        __syncthreads();
+    }
+    // acc[a][b][v] = y[m_base + wm + a*32 + 8*(v/4) + 4*lg + v%4][row0 + wn + b*32 + li]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int row = t.row0 + wn + b * 32 + li;
+            if (row >= seg_rows) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m_base + wm + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                if (m < g.M) store_out(g, blockIdx.y, m, t.col0 + row, acc[a][b][v]);
+            }
+        }
+}
+
+int tiles_of(const int *n, int nseg, int rows) {
+    int t = 0;
+    for (int s = 0; s < nseg; ++s) t += (n[s] + rows - 1) / rows;
+    return t;
+}
+
+}  // namespace
+
+int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
+    (void)N;
+    if (dtype != PSD_BF16) return 1;
+    if (M <= 64) {
+        const int tiles = tiles_of(n, nseg, kSkinnyRows);
+        const int nsteps = K / kSkinnyStepK;
+        int want = (512 + tiles - 1) / tiles;             // aim at >= 512 blocks (2048 wavefronts)
+        int cap = nsteps / 8;                             // keep >= 2 K steps per wavefront
+        if (cap < 1) cap = 1;
+        if (want > cap) want = cap;
+        if (want > 16) want = 16;
+        return want < 1 ? 1 : want;
+    }
+    const int tiles = tiles_of(n, nseg, kBN) * ((M + kBM - 1) / kBM);
+    int want = (256 + tiles - 1) / tiles;
+    int cap = K / kBK / 4;
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want > 8) want = 8;
+    return want < 1 ? 1 : want;
+}
+
+void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
+    if (dtype != PSD_BF16) {
+        gemm_f32_kernel<<<(g.N + 3) / 4, 256, 0, stream>>>(g);
+        return;
+    }
+    if (g.M <= 64) {
+        dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
+        const int mt = (g.M + 15) / 16;
+        if (mt == 1) gemm_bf16_skinny_kernel<1><<<grid, 256, 0, stream>>>(g);
+        else if (mt == 2) gemm_bf16_skinny_kernel<2><<<grid, 256, 0, stream>>>(g);
+        else if (mt == 3) gemm_bf16_skinny_kernel<3><<<grid, 256, 0, stream>>>(g);
+        else gemm_bf16_skinny_kernel<4><<<grid, 256, 0, stream>>>(g);
+    } else {
+        dim3 grid(tiles_of(g.n, g.nseg, kBN) * ((g.M + kBM - 1) / kBM), g.splitk);
+        gemm_bf16_tiled_kernel<<<grid, 256, 0, stream>>>(g);
+    }
+    if (g.splitk > 1) {
+        const unsigned blocks = (unsigned)(((size_t)g.M * g.N + 255) / 256);
+        gemm_splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(g);
+    }
+}
+
+}  // namespace psd

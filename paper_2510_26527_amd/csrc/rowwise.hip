@@ -1,0 +1,147 @@
+// Row-wise pieces of the decoder forward pass on gfx950: embedding gather, RMSNorm, rotary
+// embedding + KV append, SwiGLU, and the KV-length bookkeeping (the rollback of Sec. 3.3).
+// All are bandwidth-trivial next to the weight streaming of the GEMMs; they exist so that no
+// step of the forward pass leaves the GPU.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/psd.h"
+
+namespace psd {
+namespace {
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T *embed, const int32_t *tokens, float *x,
+                                                    int d, int vocab) {
+    const int m = blockIdx.x;
+    int tok = tokens[m];
+    tok = min(max(tok, 0), vocab - 1);
+    const T *row = embed + (size_t)tok * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = load_elem(row, i);
+}
+
+// One block per row.  The sum of squares is taken in fp32 in a fixed order: per-thread strided
+// partial, butterfly inside the wavefront, then the four wavefront totals left to right.
+template <typename TW, typename TA>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const TW *gain, TA *out, int d,
+                                                      float eps, int row_stride_x) {
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const float *row = x + (size_t)m * row_stride_x;
+    float ss = 0.f;
+    for (int i = tid; i < d; i += 256) { const float v = row[i]; ss += v * v; }
+    __shared__ float red[4];
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = ((red[0] + red[1]) + red[2]) + red[3];
+    const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = tid; i < d; i += 256) store_elem(out, (size_t)m * d + i, row[i] * scale * load_elem(gain, i));
+}
+
+// One block per new row (b, r).  Thread i < d_h/2 owns the rotation pair (i, i + d_h/2): the angle
+// position * theta^(-2i/d_h) is evaluated once in fp64 and reused for every head.
+template <typename TA, typename TC>
+__global__ __launch_bounds__(64) void rope_append_kernel(const float *qkv, TA *q_out, TC *k_cache, TC *v_cache,
+                                                         const int32_t *lens, int R, int h_q, int h_kv, int d_h,
+                                                         int max_len, float theta) {
+    const int m = blockIdx.x, b = m / R, r = m % R;
+    const int pos = lens[b] + r;
+    if (pos >= max_len) return;            // capacity was checked on the host; never write outside
+    const int half = d_h / 2;
+    const int width = (h_q + 2 * h_kv) * d_h;
+    const float *row = qkv + (size_t)m * width;
+    const int i = threadIdx.x;
+    if (i < half) {
+        const double inv_freq = exp2(-2.0 * (double)i / (double)d_h * log2((double)theta));
+        double sn, cs;
+        sincos((double)pos * inv_freq, &sn, &cs);
+        const float c = (float)cs, s = (float)sn;
+        for (int h = 0; h < h_q; ++h) {
+            const float x1 = row[h * d_h + i], x2 = row[h * d_h + half + i];
+            TA *dst = q_out + ((size_t)m * h_q + h) * d_h;
+            store_elem(dst, i, x1 * c - x2 * s);
+            store_elem(dst, half + i, x2 * c + x1 * s);
+        }
+        for (int h = 0; h < h_kv; ++h) {
+            const float *kr = row + (size_t)(h_q + h) * d_h;
+            const float x1 = kr[i], x2 = kr[half + i];
+            TC *dst = k_cache + (((size_t)b * h_kv + h) * max_len + pos) * d_h;
+            store_elem(dst, i, x1 * c - x2 * s);
+            store_elem(dst, half + i, x2 * c + x1 * s);
+        }
+    }
+    // V is stored transposed: v_cache[b][h][d][pos]
+    for (int e = threadIdx.x; e < h_kv * d_h; e += blockDim.x) {
+        const int h = e / d_h, dd = e % d_h;
+        const float v = row[(size_t)(h_q + h_kv) * d_h + e];
+        store_elem(v_cache, (((size_t)b * h_kv + h) * d_h + dd) * max_len + pos, v);
+    }
+}
+
+template <typename TA>
+__global__ __launch_bounds__(256) void swiglu_kernel(const float *gu, TA *h, int M, int f) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)M * f) return;
+    const size_t m = idx / f, j = idx % f;
+    const float g = gu[m * 2 * f + j], u = gu[m * 2 * f + f + j];
+    store_elem(h, idx, g / (1.0f + __expf(-g)) * u);
+}
+
+__global__ void advance_lens_kernel(int32_t *lens, int B, int delta, int max_len) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) lens[b] = min(lens[b] + delta, max_len);
+}
+
+__global__ void truncate_kernel(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) lens[b] = max(0, min(lens[b], base[b] + keep[b] + offset));
+}
+
+__global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) lens[b] = max(0, min(lens[b], new_len));
+}
+
+}  // namespace
+
+void launch_embed(int dtype, const void *embed, const int32_t *tokens, float *x, int M, int d, int vocab,
+                  hipStream_t stream) {
+    if (dtype == PSD_BF16) embed_kernel<uint16_t><<<M, 256, 0, stream>>>((const uint16_t *)embed, tokens, x, d, vocab);
+    else embed_kernel<float><<<M, 256, 0, stream>>>((const float *)embed, tokens, x, d, vocab);
+}
+
+void launch_rmsnorm(int dtype, const float *x, const void *gain, void *out, int M, int d, float eps,
+                    int row_stride_x, hipStream_t stream) {
+    if (dtype == PSD_BF16)
+        rmsnorm_kernel<uint16_t, uint16_t><<<M, 256, 0, stream>>>(x, (const uint16_t *)gain, (uint16_t *)out, d, eps, row_stride_x);
+    else
+        rmsnorm_kernel<float, float><<<M, 256, 0, stream>>>(x, (const float *)gain, (float *)out, d, eps, row_stride_x);
+}
+
+void launch_rope_append(int dtype, const float *qkv, void *q_out, void *k_cache, void *v_cache,
+                        const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
+                        float theta, hipStream_t stream) {
+    if (dtype == PSD_BF16)
+        rope_append_kernel<uint16_t, uint16_t><<<B * R, 64, 0, stream>>>(qkv, (uint16_t *)q_out, (uint16_t *)k_cache,
+                                                                         (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
+    else
+        rope_append_kernel<float, float><<<B * R, 64, 0, stream>>>(qkv, (float *)q_out, (float *)k_cache, (float *)v_cache,
+                                                                   lens, R, h_q, h_kv, d_h, max_len, theta);
+}
+
+void launch_swiglu(int dtype, const float *gu, void *h, int M, int f, hipStream_t stream) {
+    const unsigned blocks = (unsigned)(((size_t)M * f + 255) / 256);
+    if (dtype == PSD_BF16) swiglu_kernel<uint16_t><<<blocks, 256, 0, stream>>>(gu, (uint16_t *)h, M, f);
+    else swiglu_kernel<float><<<blocks, 256, 0, stream>>>(gu, (float *)h, M, f);
+}
+
+void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream) {
+    advance_lens_kernel<<<(B + 63) / 64, 64, 0, stream>>>(lens, B, delta, max_len);
+}
+void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B, hipStream_t stream) {
+    truncate_kernel<<<(B + 63) / 64, 64, 0, stream>>>(lens, base, keep, offset, B);
+}
+void launch_truncate_to(int32_t *lens, int new_len, int B, hipStream_t stream) {
+    truncate_to_kernel<<<(B + 63) / 64, 64, 0, stream>>>(lens, new_len, B);
+}
+
+}  // namespace psd

@@ -1,0 +1,120 @@
+"""CPU-side checks of the C boundary: the library loads without a GPU, exports every symbol
+include/psd.h declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_26527_amd as psd
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(psd.LIB_PATH):
+        from paper_2510_26527_amd import build
+        build.build()
+    return psd.lib()
+
+
+def _declared():
+    text = open(psd.HEADER_PATH).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(psd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = _declared()
+    assert {"psd_model_forward", "psd_spec_accept", "psd_kv_truncate"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(psd._SIGNATURES), "binding and header disagree"
+
+
+def _desc(**kw):
+    base = dict(n_layers=1, d_model=128, n_q_heads=2, n_kv_heads=2, d_head=64, d_ffn=256, vocab=512,
+                rope_theta=1e4, rms_eps=1e-5, dtype=psd.PSD_BF16)
+    base.update(kw)
+    return psd.psd_model_desc(**base)
+
+
+def _create(desc, n_ptrs=None, ptr=0x1000):
+    n = 3 + 9 * desc.n_layers if n_ptrs is None else n_ptrs
+    return psd.psd_model_create(desc, [ptr] * n)
+
+
+def test_model_create_validation(lib):
+    m = _create(_desc())
+    psd.psd_model_destroy(m)
+    for bad, code in ((dict(dtype=7), psd.PSD_ERR_DTYPE), (dict(d_head=48), psd.PSD_ERR_SHAPE),
+                      (dict(n_q_heads=3), psd.PSD_ERR_SHAPE), (dict(d_model=96), psd.PSD_ERR_SHAPE),
+                      (dict(vocab=0), psd.PSD_ERR_SHAPE), (dict(rope_theta=0.0), psd.PSD_ERR_SHAPE)):
+        with pytest.raises(psd.PsdError) as e:
+            _create(_desc(**bad))
+        assert e.value.status == code, bad
+    with pytest.raises(psd.PsdError) as e:
+        _create(_desc(), n_ptrs=5)
+    assert e.value.status == psd.PSD_ERR_SHAPE
+    with pytest.raises(psd.PsdError) as e:
+        _create(_desc(), ptr=0)
+    assert e.value.status == psd.PSD_ERR_NULL
+    with pytest.raises(psd.PsdError) as e:
+        _create(_desc(), ptr=0x1004)          # not 16-byte aligned
+    assert e.value.status == psd.PSD_ERR_SHAPE
+    assert psd.status_string(psd.PSD_ERR_CAPACITY) == "KV cache capacity exceeded"
+
+
+def test_kv_and_forward_validation(lib):
+    m = _create(_desc())
+    assert psd.psd_kv_bytes(m, 2, 128) == 1 * 2 * 2 * 128 * 64 * 2
+    assert psd.psd_kv_bytes(m, 2, 100) == 0                      # max_len must be a multiple of 64
+    out = ctypes.c_void_p()
+    L = lib
+    assert L.psd_kv_create(m, 1, 100, 0x1000, 0x2000, 0x3000, 0, ctypes.byref(out)) == psd.PSD_ERR_SHAPE
+    assert L.psd_kv_create(m, 1, 128, 0, 0x2000, 0x3000, 0, ctypes.byref(out)) == psd.PSD_ERR_NULL
+    assert L.psd_kv_create(m, 1, 128, 0x1000, 0x2000, 0x3000, 129, ctypes.byref(out)) == psd.PSD_ERR_CAPACITY
+    assert L.psd_kv_create(m, 1, 128, 0x1000, 0x2000, 0x3000, 120, ctypes.byref(out)) == psd.PSD_OK
+    kv = out
+    assert psd.psd_kv_len_upper_bound(kv) == 120
+    need = psd.psd_model_workspace_bytes(m, 1, 9, 128)
+    assert need > 0 and psd.psd_model_workspace_bytes(m, 0, 9, 128) == 0
+    f = L.psd_model_forward
+    assert f(m, 0, 4, kv, 0x5000, 4, 0x10000, need, 0) == psd.PSD_ERR_NULL            # no tokens
+    assert f(m, 0x4000, 9, kv, 0x5000, 9, 0x10000, need, 0) == psd.PSD_ERR_CAPACITY   # 120 + 9 > 128
+    assert f(m, 0x4000, 4, kv, 0x5000, 5, 0x10000, need, 0) == psd.PSD_ERR_SHAPE      # more logit rows than rows
+    assert f(m, 0x4000, 4, kv, 0, 4, 0x10000, need, 0) == psd.PSD_ERR_NULL            # logits wanted, no buffer
+    assert f(m, 0x4000, 4, kv, 0x5000, 4, 0x10000, 16, 0) == psd.PSD_ERR_WORKSPACE    # too small
+    assert f(m, 0x4000, 4, kv, 0x5000, 4, 0x10010, need, 0) == psd.PSD_ERR_WORKSPACE  # misaligned
+    assert f(m, 0x4000, 0, kv, 0x5000, 0, 0x10000, need, 0) == psd.PSD_ERR_SHAPE
+    assert L.psd_kv_truncate(kv, 0, 0x1000, 1, 0) == psd.PSD_ERR_NULL
+    assert L.psd_kv_truncate_to(kv, -1, 0) == psd.PSD_ERR_SHAPE
+    psd.psd_kv_destroy(kv)
+    psd.psd_model_destroy(m)
+
+
+def test_spec_accept_validation(lib):
+    a = lib.psd_spec_accept
+    ws = psd.psd_spec_accept_workspace_bytes(4, 8, 9, 32000)
+    assert ws > 0 and psd.psd_spec_accept_workspace_bytes(4, 8, 7, 32000) == 0
+    P, Q, X, U, N, T, W = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000, 0x70000
+
+    def call(gamma=8, temp=1.0, rows=4, n_p=9, V=32000, dtype=psd.PSD_BF16, ps=None, qs=None, p=P, q=Q, x=X, u=U,
+             n=N, t=T, w=W, wb=ws):
+        ps = n_p * V if ps is None else ps
+        qs = gamma * V if qs is None else qs
+        return a(p, q, x, gamma, u, temp, n, t, rows, n_p, V, dtype, ps, qs, 0, w, wb, 0)
+
+    assert call(temp=0.0) == psd.PSD_ERR_TEMPERATURE
+    assert call(temp=float("nan")) == psd.PSD_ERR_TEMPERATURE
+    assert call(temp=float("inf")) == psd.PSD_ERR_TEMPERATURE
+    assert call(dtype=3) == psd.PSD_ERR_DTYPE
+    assert call(gamma=65, n_p=65) == psd.PSD_ERR_SHAPE
+    assert call(n_p=7) == psd.PSD_ERR_SHAPE
+    assert call(V=0) == psd.PSD_ERR_SHAPE
+    assert call(ps=100) == psd.PSD_ERR_SHAPE
+    assert call(p=0) == psd.PSD_ERR_NULL
+    assert call(q=0) == psd.PSD_ERR_NULL
+    assert call(n=0) == psd.PSD_ERR_NULL
+    assert call(w=0) == psd.PSD_ERR_WORKSPACE
+    assert call(wb=8) == psd.PSD_ERR_WORKSPACE
+    assert call(rows=0) == psd.PSD_OK                     # nothing to do, nothing launched
