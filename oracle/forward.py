@@ -35,7 +35,11 @@ class ModelConfig:
 
 
 def widen(a):
-    """Any stored weight/cache array -> fp64.  uint16 arrays hold bfloat16 bit patterns."""
+    """Any stored weight/cache array -> fp64.  uint16 arrays hold bfloat16 bit patterns; a CPU
+    torch tensor (fp32 or bf16) is converted by torch, which does it on all cores."""
+    if hasattr(a, "detach"):
+        import torch
+        return a.detach().to(torch.float64).numpy()
     a = np.asarray(a)
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
@@ -115,7 +119,7 @@ def forward(cfg: ModelConfig, weights: dict, tokens, kv: KVCache):
     if np.any(kv.lens + R > kv.max_len):
         raise ValueError("KV cache capacity exceeded")
     h_q, h_kv, d_h = cfg.n_q_heads, cfg.n_kv_heads, cfg.d_head
-    x = widen(weights["embed"][tokens.reshape(-1)]).reshape(B, R, cfg.d_model)
+    x = widen(weights["embed"][tokens.reshape(-1).astype(np.int64)]).reshape(B, R, cfg.d_model)
     for l in range(cfg.n_layers):
         w = lambda name: widen(weights[f"l{l}.{name}"])
         n = rmsnorm(x, w("attn_norm"), cfg.rms_eps)
