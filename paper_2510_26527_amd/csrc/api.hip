@@ -146,7 +146,7 @@ ForwardPlan plan_forward(const psd_model_desc &d, int batch, int n_new, int n_lo
     const int Ml = batch * n_logit_rows;
     p.sk_head = Ml > 0 ? gemm_pick_splitk(d.dtype, Ml, d.d_model, d.vocab, n_v, 1) : 1;
     p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
-    const size_t act = elem_size(d.dtype);
+    const size_t act = 4;                                    // activations are fp32 for both dtypes
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += align256(bytes); return o; };
     p.off_x = take((size_t)M * d.d_model * 4);
@@ -209,12 +209,12 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
     hipStream_t st = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     float *x = (float *)(ws + p.off_x);
-    void *xn = ws + p.off_xn;
+    float *xn = (float *)(ws + p.off_xn);
     float *qkv = (float *)(ws + p.off_qkv);
-    void *q = ws + p.off_q;
-    void *attn = ws + p.off_attn;
+    float *q = (float *)(ws + p.off_q);
+    float *attn = (float *)(ws + p.off_attn);
     float *gu = (float *)(ws + p.off_gu);
-    void *h = ws + p.off_h;
+    float *h = (float *)(ws + p.off_h);
     float *partial = (float *)(ws + p.off_partial);
     const int M = p.M, hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
     const size_t es = elem_size(d.dtype);
@@ -269,7 +269,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         } else {
             for (int b = 0; b < B; ++b)
                 launch_rmsnorm(d.dtype, x + ((size_t)b * n_new + (n_new - n_logit_rows)) * d.d_model, m->final_norm(),
-                               (char *)xn + (size_t)b * n_logit_rows * d.d_model * es, n_logit_rows, d.d_model,
+                               xn + (size_t)b * n_logit_rows * d.d_model, n_logit_rows, d.d_model,
                                d.rms_eps, d.d_model, st);
         }
         GemmArgs hg{};

@@ -7,7 +7,9 @@
 //                        four wavefronts; each wavefront streams 64-key tiles of K and of the
 //                        transposed V straight from HBM into MFMA operand registers with
 //                        16-byte loads, computes S^T = K Q^T and O^T += V^T P^T on the matrix
-//                        cores for up to 64 query rows (all heads of the group x all new rows),
+//                        cores for up to 32 (d_head 128) or 64 (d_head 64) query rows - all heads
+//                        of the group x all new rows; queries and probabilities go in as bf16
+//                        hi + lo pairs, the cache operands as stored -
 //                        and keeps an online softmax per query column with two cross-lane
 //                        shuffles.  Wavefronts are merged through LDS in a fixed order, splits
 //                        by attn_combine_kernel.
@@ -24,7 +26,7 @@
 namespace psd {
 namespace {
 
-template <typename TA, typename TC>
+template <typename TC>
 __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a, float scale) {
     extern __shared__ float sc[];
     const int lane = threadIdx.x;
@@ -32,13 +34,13 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a, float scale
     const int d_h = a.d_h;
     const int n_keys = min(a.lens[b] + r + 1, a.max_len);
     const int hk = h / (a.h_q / a.h_kv);
-    const TA *q = (const TA *)a.q + ((size_t)m * a.h_q + h) * d_h;
+    const float *q = a.q + ((size_t)m * a.h_q + h) * d_h;
     const TC *K = (const TC *)a.k + ((size_t)b * a.h_kv + hk) * a.max_len * d_h;
     const TC *Vt = (const TC *)a.v + ((size_t)b * a.h_kv + hk) * d_h * (size_t)a.max_len;
     float mx = -INFINITY;
     for (int k = lane; k < n_keys; k += 64) {
         float s = 0.f;
-        for (int d = 0; d < d_h; ++d) s += load_elem(q, d) * load_elem(K, (size_t)k * d_h + d);
+        for (int d = 0; d < d_h; ++d) s += q[d] * load_elem(K, (size_t)k * d_h + d);
         s *= scale;
         sc[k] = s;
         mx = fmaxf(mx, s);
@@ -52,11 +54,11 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a, float scale
     }
     sum = wave_sum(sum);
     __syncthreads();
-    TA *out = (TA *)a.out + ((size_t)m * a.h_q + h) * d_h;
+    float *out = a.out + ((size_t)m * a.h_q + h) * d_h;
     for (int d = lane; d < d_h; d += 64) {
         float acc = 0.f;
         for (int k = 0; k < n_keys; ++k) acc += sc[k] * load_elem(Vt, (size_t)d * a.max_len + k);
-        store_elem(out, d, acc / sum);
+        out[d] = acc / sum;
     }
 }
 
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
 
     // Q operand (B of S^T = K Q^T): column i of tile qt is query q0 + qt*16 + i; lane group g
     // holds d_head elements [g*DH/4, (g+1)*DH/4), k-step s the 8 starting at 8*s inside them.
-    bf16x8 qb[QT][KS];
+    bf16x8 qh[QT][KS], ql[QT][KS];
     int limit[QT];                   // last key this lane's query may see, -1 for a padding column
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
@@ -90,12 +92,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         const bool valid = qi < NQ;
         const int hl = valid ? qi / a.R : 0, r = valid ? qi % a.R : 0;
         limit[qt] = valid ? S_b + r : -1;
-        const uint16_t *qp = (const uint16_t *)a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
+        const float *qp = a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            bf16x8 v = *reinterpret_cast<const bf16x8 *>(qp + 8 * s);
-            if (!valid) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            qb[qt][s] = v;
+            f32x8 v = load_f32x8(qp + 8 * s);
+            if (!valid) v = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            split_bf16(v, &qh[qt][s], &ql[qt][s]);
         }
     }
 
@@ -146,8 +148,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                 for (int t = 0; t < 2; ++t) {
                     c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int s = 0; s < KS; ++s)
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qb[qt][s], c[t], 0, 0, 0);
+                    for (int s = 0; s < KS; ++s) {
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[t], 0, 0, 0);
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[t], 0, 0, 0);
+                    }
                 }
                 // lane (query column i, group g): c[t][v] is key kb + 8g + 4t + v
                 float tmax = -INFINITY;
@@ -179,15 +183,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
 #pragma unroll
                     for (int e = 0; e < 8; ++e) p[e] = 0.f;
                 }
-                u32x4 praw;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) praw[e] = pack_bf16x2(p[2 * e], p[2 * e + 1]);
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, praw);
+                bf16x8 ph, pl;
+                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph, &pl);
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, o[qt][dt], 0, 0, 0);
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph, o[qt][dt], 0, 0, 0);
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl, o[qt][dt], 0, 0, 0);
                 }
             }
         }
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         const int hl = qi / a.R, r = qi % a.R;
         const size_t row = ((size_t)(b * a.R + r)) * a.h_q + hk * group + hl;       // [B][R][h_q]
         if (a.splits == 1) {
-            ((uint16_t *)a.out)[row * DH + d] = (uint16_t)f32_to_bf16_bits(sm_o[qc][d] / sm_l[qc]);
+            a.out[row * DH + d] = sm_o[qc][d] / sm_l[qc];
         } else {
             a.part_o[(row * a.splits + split) * DH + d] = sm_o[qc][d];
             if (d == 0) {
@@ -263,18 +266,18 @@ __global__ void attn_combine_kernel(AttnArgs a) {
         L += ml[2 * s + 1] * f;
         acc += a.part_o[(row * a.splits + s) * DH + d] * f;
     }
-    ((uint16_t *)a.out)[row * DH + d] = (uint16_t)f32_to_bf16_bits(acc / L);
+    a.out[row * DH + d] = acc / L;
 }
 
-inline int q_tiles(int NQ) { return NQ <= 16 ? 1 : (NQ <= 32 ? 2 : 4); }
+// query tiles of 16 per block: bounded by registers (hi+lo query operands and fp32 outputs)
+inline int q_tiles(int NQ, int d_h) { return NQ <= 16 ? 1 : ((NQ <= 32 || d_h > 64) ? 2 : 4); }
 
 }  // namespace
 
 int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound) {
-    (void)d_h;
     if (dtype != PSD_BF16) return 1;
     const int NQ = (h_q / h_kv) * R;
-    const int QT = q_tiles(NQ);
+    const int QT = q_tiles(NQ, d_h);
     const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
     const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
     int by_grid = 1024 / (B * h_kv * chunks);
@@ -286,7 +289,7 @@ int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int le
 template <int DH>
 static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     const int NQ = (a.h_q / a.h_kv) * a.R;
-    const int QT = q_tiles(NQ);
+    const int QT = q_tiles(NQ, DH);
     const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
     int range = (a.len_bound + a.splits - 1) / a.splits;
     range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
@@ -294,7 +297,7 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     dim3 grid(a.splits, chunks, a.B * a.h_kv);
     if (QT == 1) attn_mfma_kernel<DH, 1><<<grid, 256, 0, stream>>>(a, scale_log2, range);
     else if (QT == 2) attn_mfma_kernel<DH, 2><<<grid, 256, 0, stream>>>(a, scale_log2, range);
-    else attn_mfma_kernel<DH, 4><<<grid, 256, 0, stream>>>(a, scale_log2, range);
+    else if constexpr (DH <= 64) attn_mfma_kernel<DH, 4><<<grid, 256, 0, stream>>>(a, scale_log2, range);
     if (a.splits > 1) attn_combine_kernel<<<a.B * a.R * a.h_q, DH, 0, stream>>>(a);
 }
 
@@ -307,8 +310,8 @@ void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream) {
     const float scale = 1.0f / sqrtf((float)a.d_h);
     dim3 grid(a.h_q, a.B * a.R);
     const size_t smem = (size_t)a.len_bound * sizeof(float);
-    if (dtype == PSD_BF16) attn_simple_kernel<uint16_t, uint16_t><<<grid, 64, smem, stream>>>(a, scale);
-    else attn_simple_kernel<float, float><<<grid, 64, smem, stream>>>(a, scale);
+    if (dtype == PSD_BF16) attn_simple_kernel<uint16_t><<<grid, 64, smem, stream>>>(a, scale);
+    else attn_simple_kernel<float><<<grid, 64, smem, stream>>>(a, scale);
 }
 
 }  // namespace psd

@@ -11,7 +11,22 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;     // 16x16 MFMA accum
 typedef __attribute__((ext_vector_type(16))) float f32x16;   // 32x32 MFMA accumulator
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // a 16-byte load
 
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+
 constexpr int kWave = 64;
+
+// An fp32 activation as a pair of bf16 values hi + lo (hi = RNE(x), lo = RNE(x - hi)): fed to
+// two MFMAs it carries ~16 mantissa bits through the bf16 matrix cores.
+__device__ __forceinline__ void split_bf16(const f32x8 &x, bf16x8 *hi, bf16x8 *lo) {
+    const bf16x8 h = __builtin_convertvector(x, bf16x8);
+    *hi = h;
+    *lo = __builtin_convertvector(x - __builtin_convertvector(h, f32x8), bf16x8);
+}
+__device__ __forceinline__ f32x8 load_f32x8(const float *p) {
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+    const f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+    return f32x8{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+}
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 

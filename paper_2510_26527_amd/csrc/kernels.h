@@ -34,7 +34,7 @@ void launch_accept(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
 // y[m][n] = sum_k x[m][k] * W[n][k]; W is up to three row-major [n_i][K] matrices whose
 // outputs are concatenated along n (QKV, gate|up).
 struct GemmArgs {
-    const void *x;                // [M][K] activations: fp32 (f32 model) or bf16 (bf16 model)
+    const float *x;               // [M][K] fp32 activations
     const void *w[3];
     int n[3];
     int nseg;
@@ -50,11 +50,11 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention (attention.hip)
 struct AttnArgs {
-    const void *q;                // [B][R][h_q][d_h] rotated queries, activation dtype
+    const float *q;               // [B][R][h_q][d_h] rotated queries, fp32
     const void *k;                // this layer's K cache [B][h_kv][max_len][d_h]
     const void *v;                // this layer's V cache [B][h_kv][d_h][max_len]
     const int32_t *lens;          // [B] valid positions BEFORE this forward
-    void *out;                    // [B][R][h_q*d_h] activation dtype
+    float *out;                   // [B][R][h_q*d_h] fp32
     int B, R, h_q, h_kv, d_h, max_len;
     int len_bound;                // host upper bound of lens[b] + R
     float *part_o;                // split scratch [B][h_q][R][splits][d_h]
@@ -67,14 +67,14 @@ void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 // ---------------------------------------------------------------- row-wise kernels (rowwise.hip)
 void launch_embed(int dtype, const void *embed, const int32_t *tokens, float *x, int M, int d,
                   int vocab, hipStream_t stream);
-// out = x * rsqrt(mean(x^2) + eps) * gain, written in the activation dtype
+// out = x * rsqrt(mean(x^2) + eps) * gain (fp32); gain has the model's dtype
 void launch_rmsnorm(int dtype, const float *x, const void *gain, void *out, int M, int d, float eps,
                     int row_stride_x, hipStream_t stream);
-// qkv fp32 [M][(h_q+2h_kv) d_h] -> rotated q (activation dtype), rotated k and v appended to the cache
+// qkv fp32 [M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended to the cache (model dtype)
 void launch_rope_append(int dtype, const float *qkv, void *q_out, void *k_cache, void *v_cache,
                         const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
                         float theta, hipStream_t stream);
-// h = silu(gu[:, :f]) * gu[:, f:], activation dtype
+// h = silu(gu[:, :f]) * gu[:, f:] (fp32)
 void launch_swiglu(int dtype, const float *gu, void *h, int M, int f, hipStream_t stream);
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream);
 void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B,

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float *gu, TA *h, int
     if (idx >= (size_t)M * f) return;
     const size_t m = idx / f, j = idx % f;
     const float g = gu[m * 2 * f + j], u = gu[m * 2 * f + f + j];
-    store_elem(h, idx, g / (1.0f + __expf(-g)) * u);
+    store_elem(h, idx, g / (1.0f + expf(-g)) * u);
 }
 
 __global__ void advance_lens_kernel(int32_t *lens, int B, int delta, int max_len) {
@@ -112,7 +112,7 @@ void launch_embed(int dtype, const void *embed, const int32_t *tokens, float *x,
 void launch_rmsnorm(int dtype, const float *x, const void *gain, void *out, int M, int d, float eps,
                     int row_stride_x, hipStream_t stream) {
     if (dtype == PSD_BF16)
-        rmsnorm_kernel<uint16_t, uint16_t><<<M, 256, 0, stream>>>(x, (const uint16_t *)gain, (uint16_t *)out, d, eps, row_stride_x);
+        rmsnorm_kernel<uint16_t, float><<<M, 256, 0, stream>>>(x, (const uint16_t *)gain, (float *)out, d, eps, row_stride_x);
     else
         rmsnorm_kernel<float, float><<<M, 256, 0, stream>>>(x, (const float *)gain, (float *)out, d, eps, row_stride_x);
 }
@@ -121,8 +121,8 @@ void launch_rope_append(int dtype, const float *qkv, void *q_out, void *k_cache,
                         const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
                         float theta, hipStream_t stream) {
     if (dtype == PSD_BF16)
-        rope_append_kernel<uint16_t, uint16_t><<<B * R, 64, 0, stream>>>(qkv, (uint16_t *)q_out, (uint16_t *)k_cache,
-                                                                         (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
+        rope_append_kernel<float, uint16_t><<<B * R, 64, 0, stream>>>(qkv, (float *)q_out, (uint16_t *)k_cache,
+                                                                      (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
     else
         rope_append_kernel<float, float><<<B * R, 64, 0, stream>>>(qkv, (float *)q_out, (float *)k_cache, (float *)v_cache,
                                                                    lens, R, h_q, h_kv, d_h, max_len, theta);
@@ -130,8 +130,8 @@ void launch_rope_append(int dtype, const float *qkv, void *q_out, void *k_cache,
 
 void launch_swiglu(int dtype, const float *gu, void *h, int M, int f, hipStream_t stream) {
     const unsigned blocks = (unsigned)(((size_t)M * f + 255) / 256);
-    if (dtype == PSD_BF16) swiglu_kernel<uint16_t><<<blocks, 256, 0, stream>>>(gu, (uint16_t *)h, M, f);
-    else swiglu_kernel<float><<<blocks, 256, 0, stream>>>(gu, (float *)h, M, f);
+    (void)dtype;
+    swiglu_kernel<float><<<blocks, 256, 0, stream>>>(gu, (float *)h, M, f);
 }
 
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream) {
