@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Bench of the verify path on one MI355X.
+
+A step is one pass of the whole hot path on the benchmark's configs[2] (the workload the
+metric is quoted on: LLaMA2-7B shape, bf16, batch 1, gamma = 8 new tokens against a
+1024-token KV cache): psd_model_forward over the 8 rows, psd_spec_accept of the 8 draft
+tokens against synthetic drafter logits, psd_kv_truncate to the accepted length (then the
+cache length is put back to 1024 so every step sees the same shape).  Inputs are synthetic
+and resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+
+
+def weight_stream_bytes(shape):
+    """Algorithmic bytes one forward pass must read for its projections: every weight matrix
+    once, 2 bytes per bf16 weight (embedding rows and norm gains excluded: kilobytes)."""
+    s = shape
+    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
+    per_layer = s.d_model * (hd + 2 * kvd) + hd * s.d_model + 3 * s.d_model * s.d_ffn
+    return 2 * (s.n_layers * per_layer + s.vocab * s.d_model)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--accept-iters", type=int, default=60)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2510_26527_amd as psd
+    from paper_2510_26527_amd import runtime, synth
+    if not os.path.exists(psd.LIB_PATH):
+        from paper_2510_26527_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs the GPU: no CPU fallback exists")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    shape, gamma, ctx, max_len, temperature = synth.LLAMA2_7B, 8, 1024, 1088, 1.0
+    w_cpu = synth.make_weights(shape, 3, torch.bfloat16)
+    model = runtime.Model(shape, w_cpu, dev)
+    kv = runtime.KVCache(model, 1, max_len)
+    ks, vs = synth.make_kv_fill(shape, 1, ctx, 4, torch.bfloat16)
+    kv.load(ks, vs, ctx)
+    tok_np = synth.make_tokens(shape.vocab, (1, gamma), 33)
+    tokens = torch.from_numpy(tok_np).to(dev)
+    p_buf = torch.empty((1, gamma, shape.vocab), dtype=torch.float32, device=dev)
+    base = torch.full((1,), ctx, dtype=torch.int32, device=dev)
+    acc = runtime.Acceptor(dev)
+    uniforms = synth.make_uniforms((1, gamma + 1), 6, dev)
+
+    # one forward outside the timed region fixes the synthetic drafter (q = p + N(0, 0.5^2))
+    runtime.forward(model, kv, tokens, logits_out=p_buf)
+    psd.psd_kv_truncate_to(kv.handle, ctx)
+    q_logits, draft = synth.make_draft_from_target(p_buf, 0.5, 7)
+    torch.cuda.synchronize()
+
+    out = {}
+
+    def step():
+        runtime.forward(model, kv, tokens, logits_out=p_buf)
+        n, tok, fl = acc(p_buf, q_logits, draft, uniforms, temperature)
+        psd.psd_kv_truncate(kv.handle, base, n, 1)
+        psd.psd_kv_truncate_to(kv.handle, ctx)          # back to the benchmark's cache length
+        out["n"] = n
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    accepted = int(out["n"].item())
+
+    # same steps again with every launch bracketed by HIP events on its stream
+    launches_per_step = 40 * shape.n_layers + 64
+    prof_steps = min(args.steps, 20)
+    psd.psd_profile_enable(launches_per_step * prof_steps)
+    for _ in range(prof_steps):
+        step()
+    prof = psd.psd_profile_collect()
+    psd.psd_profile_enable(0)
+    kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * ms / c, "ms_per_step": ms / prof_steps}
+               for k, (ms, c) in prof.items() if c}
+    sk_ms, sk_n = prof["gemm_skinny"]
+    w_bytes = weight_stream_bytes(shape)
+    achieved = w_bytes * prof_steps / (sk_ms * 1e-3) / 1e9
+    roofline = {"kernel": "gemm_bf16_skinny_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "bytes_per_launch": w_bytes * prof_steps / sk_n, "avg_launch_us": 1e3 * sk_ms / sk_n,
+                "launches_per_step": sk_n / prof_steps}
+    kv_bytes = 2 * shape.n_layers * shape.n_kv_heads * (ctx + gamma) * shape.d_head * 2
+    step_floor_ms = (w_bytes + kv_bytes) / (HBM_PEAK_GBS * 1e9) * 1e3
+
+    # ---- the isolated acceptance workload (configs[1]): 64 x 8 x 32000 bf16, cold HBM
+    sets = [synth.make_accept_inputs(64, 8, 32000, 100 + i, dtype=torch.bfloat16, device=dev) for i in range(6)]
+    acc2 = runtime.Acceptor(dev)
+    for s in sets:
+        acc2(s["p"], s["q"], s["tokens"], s["uniforms"], 1.0)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(args.accept_iters):
+        s = sets[i % len(sets)]
+        acc2(s["p"], s["q"], s["tokens"], s["uniforms"], 1.0)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    call_us = e0.elapsed_time(e1) * 1e3 / args.accept_iters
+    psd.psd_profile_enable(3 * args.accept_iters)
+    for i in range(args.accept_iters):
+        s = sets[i % len(sets)]
+        acc2(s["p"], s["q"], s["tokens"], s["uniforms"], 1.0)
+    aprof = psd.psd_profile_collect()
+    psd.psd_profile_enable(0)
+    a_bytes = 64 * 8 * 32000 * 2 * 2
+    stats_us = 1e3 * aprof["accept_stats"][0] / aprof["accept_stats"][1]
+    accept = {"workload": "configs[1]: 64 rows x gamma 8 x vocab 32000 bf16, 6 rotating input sets (393 MB)",
+              "algorithmic_bytes": a_bytes, "call_us": call_us, "GB/s": a_bytes / call_us / 1e3,
+              "frac_of_hbm_peak": a_bytes / call_us / 1e3 / HBM_PEAK_GBS,
+              "stats_kernel_us": stats_us, "stats_kernel_GB/s": a_bytes / stats_us / 1e3,
+              "emit_z_kernel_us": 1e3 * aprof["accept_emit_z"][0] / aprof["accept_emit_z"][1],
+              "emit_r_kernel_us": 1e3 * aprof["accept_emit_r"][0] / aprof["accept_emit_r"][1]}
+
+    # ---- the oracle on the host cores, one whole step of the same workload
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import accept as oacc
+        from oracle import forward as ofwd
+        from threadpoolctl import threadpool_info
+        cfg = ofwd.ModelConfig(**shape.asdict())
+        okv = ofwd.KVCache(cfg, 1, max_len, np.float32)
+        for l in range(shape.n_layers):
+            okv.k[l][:, :, :ctx] = ks[l].float().numpy()
+            okv.v[l][:, :, :ctx] = vs[l].float().numpy()
+        okv.lens[:] = ctx
+        c0 = time.perf_counter()
+        ref = ofwd.forward(cfg, w_cpu, tok_np, okv)
+        oacc.spec_accept(ref, q_logits.cpu().double().numpy(), draft.cpu().numpy(), uniforms.cpu().double().numpy(),
+                         temperature)
+        okv.truncate(ctx)
+        c1 = time.perf_counter()
+        threads = max([torch.get_num_threads()] + [p.get("num_threads", 1) for p in threadpool_info()])
+        cpu_baseline = {"value": gamma / (c1 - c0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                        "sample": "one whole step of the same workload (32 layers + lm_head forward in numpy fp64, "
+                                  "acceptance in C fp64, rollback), %.1f s" % (c1 - c0)}
+
+    line = {
+        "metric": "verify-step tokens/s (7B shape, γ=8, ctx 1k) + accept-kernel HBM GB/s",
+        "value": gamma * 1e3 / ms_per_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[2]: LLaMA2-7B-shaped random-init bf16, batch 1, gamma=8 new tokens on a "
+                               "1024-token N(0,1) bf16 KV cache, forward + acceptance + KV rollback",
+                   "gamma": gamma, "n_new": gamma, "kv_len": ctx, "batch": 1, "temperature": temperature},
+        "accepted_this_step": accepted,
+        "step_floor_ms_at_hbm_peak": step_floor_ms,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "accept_kernel": accept, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -162,6 +162,32 @@ psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32
  * upper bound to new_len. */
 psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 
+/* ---- measurement aid (not part of the decoding path) -------------------------------------
+ * Per-kernel timing with HIP events recorded on the launch stream, so that a bench can state
+ * each kernel's average duration against its roofline.  psd_profile_enable(n > 0) creates
+ * event pairs for up to n launches and starts recording; psd_profile_enable(0) stops and
+ * frees them.  psd_profile_collect waits for the recorded work, adds each launch's elapsed
+ * milliseconds into ms_by_kind[kind] and counts it in launches_by_kind[kind] (host arrays of
+ * PSD_KIND_COUNT entries, zeroed by the call), then rewinds.  Launches beyond n are not
+ * recorded.  Not thread-safe; one process-wide recorder. */
+#define PSD_KIND_EMBED 0
+#define PSD_KIND_RMSNORM 1
+#define PSD_KIND_GEMM_F32 2
+#define PSD_KIND_GEMM_SKINNY 3       /* bf16 weight-streaming GEMM, M <= 64 */
+#define PSD_KIND_GEMM_TILED 4        /* bf16 LDS-tiled GEMM, M > 64 */
+#define PSD_KIND_GEMM_REDUCE 5       /* split-K reduction */
+#define PSD_KIND_ROPE_APPEND 6
+#define PSD_KIND_ATTN 7
+#define PSD_KIND_ATTN_COMBINE 8
+#define PSD_KIND_SWIGLU 9
+#define PSD_KIND_LENS 10             /* length advance / truncate */
+#define PSD_KIND_ACCEPT_STATS 11
+#define PSD_KIND_ACCEPT_EMIT_Z 12
+#define PSD_KIND_ACCEPT_EMIT_R 13
+#define PSD_KIND_COUNT 14
+psd_status psd_profile_enable(int32_t max_launches);
+psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,7 +44,12 @@ _SIGNATURES = {
                                _vp, _vp, _sz, _vp]),
     "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _vp]),
     "psd_kv_truncate_to": (_i32, [_vp, _i32, _vp]),
+    "psd_profile_enable": (_i32, [_i32]),
+    "psd_profile_collect": (_i32, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]),
 }
+
+PSD_KIND_NAMES = ("embed", "rmsnorm", "gemm_f32", "gemm_skinny", "gemm_tiled", "gemm_reduce", "rope_append", "attn",
+                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_emit_z", "accept_emit_r")
 
 _lib = None
 
@@ -52,7 +57,8 @@ _lib = None
 class PsdError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        extra = f", hipError {lib().psd_last_hip_error()}" if status == PSD_ERR_HIP else ""
+        super().__init__(f"{where}: {status_string(status)} (status {status}{extra})")
 
 
 def lib():
@@ -62,6 +68,7 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2510_26527_amd.build`; "
                                "there is no CPU fallback")
+        import torch  # noqa: F401  loads the HIP runtime the library is linked against, before the library
         l = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(l, name)
@@ -158,3 +165,16 @@ def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, stream=None):
 
 def psd_kv_truncate_to(kv, new_len, stream=None):
     _check(lib().psd_kv_truncate_to(kv, new_len, _stream_ptr(stream)), "psd_kv_truncate_to")
+
+
+def psd_profile_enable(max_launches):
+    _check(lib().psd_profile_enable(max_launches), "psd_profile_enable")
+
+
+def psd_profile_collect():
+    """-> {kind name: (total milliseconds, launches)} for the launches recorded since the last call."""
+    n = len(PSD_KIND_NAMES)
+    ms = (ctypes.c_double * n)()
+    cnt = (_i64 * n)()
+    _check(lib().psd_profile_collect(ms, cnt), "psd_profile_collect")
+    return {PSD_KIND_NAMES[k]: (ms[k], cnt[k]) for k in range(n)}

@@ -14,6 +14,7 @@
 // All sums are taken in a fixed order, so results do not depend on block scheduling.
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 #include "../../include/psd.h"
 
 namespace psd {
@@ -23,6 +24,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kLoadsPerLane = 8;
 constexpr double kTieEps = 1e-5;
+constexpr int kMaxChunksE = 1024;     // draw-pass chunks per logits row (LDS table of the locating block)
 
 template <typename T>
 __device__ __forceinline__ const T *logits_row(const AcceptArgs &a, int b, bool is_q, int j) {
@@ -220,6 +222,7 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
     __shared__ double s_red[kThreads / 64];
     __shared__ double s_scan[kThreads / 64];
+    __shared__ double s_w[kMaxChunksE];          // per-chunk weights of this sequence (last block only)
     __shared__ int s_last, s_cstar, s_best, s_lastpos;
     __shared__ double s_base, s_t;
     const int b = blockIdx.x / a.n_chunksE, c = blockIdx.x % a.n_chunksE, tid = threadIdx.x;
@@ -263,12 +266,18 @@ __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
     // ---- last block of this sequence: locate the crossing of u * mass in index order
     const volatile double *rp = a.rpart + (size_t)b * nE;
     double mass = 0.0;
-    for (int k = tid; k < nE; k += kThreads) mass += rp[k];
+    for (int k = tid; k < nE; k += kThreads) {
+        const double wk = rp[k];
+        s_w[k] = wk;
+        mass += wk;
+    }
     mass = block_sum(mass, s_red);
     const bool fall_back_to_p = d.have_q && !(mass > 0.0);
     if (fall_back_to_p) {                  // residual mass 0: draw from p itself
         w.have_q = false;
         mass = 1.0;                        // sum of a_i / Z_p
+        for (int k = tid; k < nE; k += kThreads) s_w[k] = zp[k].x * w.inv_zp;
+        __syncthreads();
     }
     if (tid == 0) {
         const double u = (double)a.u[(size_t)b * (a.gamma + 1) + a.gamma];
@@ -276,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
         double base = 0.0;
         int cstar = -1, last_nonzero = -1;
         for (int k = 0; k < nE; ++k) {
-            const double wk = fall_back_to_p ? zp[k].x * w.inv_zp : rp[k];
+            const double wk = s_w[k];
             if (wk > 0.0) last_nonzero = k;
             if (base + wk > t) { cstar = k; break; }
             base += wk;
@@ -343,6 +352,7 @@ void accept_plan(int rows, int gamma, int n_p_rows, int V, int dtype, bool vec, 
     a->n_chunksA = (V + a->chunkA - 1) / a->chunkA;
     long want = ((long)V * (rows > 0 ? rows : 1) + 1023) / 1024;
     int ce = round_up((int)(want < 512 ? 512 : (want > 8192 ? 8192 : want)), 256);
+    while ((V + ce - 1) / ce > kMaxChunksE) ce *= 2;           // very large vocabularies: fewer, larger chunks
     a->chunkE = ce;
     a->n_chunksE = (V + ce - 1) / ce;
 }
@@ -375,12 +385,19 @@ static void launch_accept_t(const AcceptArgs &a, bool vec_ok, hipStream_t stream
     const int vecs = a.rows * (a.n_p_rows + a.gamma);
     if (vecs > 0) {
         dim3 grid((unsigned)vecs * a.n_chunksA);
+        ScopedProf sp(PSD_KIND_ACCEPT_STATS, stream);
         if (vec_ok) accept_stats_kernel<T, true><<<grid, kThreads, 0, stream>>>(a);
         else accept_stats_kernel<T, false><<<grid, kThreads, 0, stream>>>(a);
     }
     dim3 gridE((unsigned)a.rows * a.n_chunksE);
-    accept_emit_z_kernel<T><<<gridE, kThreads, 0, stream>>>(a);
-    accept_emit_r_kernel<T><<<gridE, kThreads, 0, stream>>>(a);
+    {
+        ScopedProf sp(PSD_KIND_ACCEPT_EMIT_Z, stream);
+        accept_emit_z_kernel<T><<<gridE, kThreads, 0, stream>>>(a);
+    }
+    {
+        ScopedProf sp(PSD_KIND_ACCEPT_EMIT_R, stream);
+        accept_emit_r_kernel<T><<<gridE, kThreads, 0, stream>>>(a);
+    }
 }
 
 void launch_accept(const AcceptArgs &a, bool vec_ok, hipStream_t stream) {

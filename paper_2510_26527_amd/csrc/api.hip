@@ -7,8 +7,35 @@
 
 #include "../../include/psd.h"
 #include "kernels.h"
+#include "prof.h"
 
 using namespace psd;
+
+// ------------------------------------------------------------------ launch recorder
+namespace {
+struct Recorder {
+    bool on = false;
+    std::vector<hipEvent_t> ev;      // 2 per launch
+    std::vector<int> kind;
+    size_t used = 0, cap = 0;
+    bool open = false;
+} g_rec;
+}  // namespace
+
+namespace psd {
+void prof_begin(int kind, hipStream_t stream) {
+    if (!g_rec.on || g_rec.used >= g_rec.cap) return;
+    g_rec.kind[g_rec.used] = kind;
+    (void)hipEventRecord(g_rec.ev[2 * g_rec.used], stream);
+    g_rec.open = true;
+}
+void prof_end(hipStream_t stream) {
+    if (!g_rec.open) return;
+    (void)hipEventRecord(g_rec.ev[2 * g_rec.used + 1], stream);
+    ++g_rec.used;
+    g_rec.open = false;
+}
+}  // namespace psd
 
 struct psd_model {
     psd_model_desc d;
@@ -331,6 +358,45 @@ psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32
     (void)hipGetLastError();
     launch_truncate(kv->lens, base_lens_dev, keep_dev, keep_offset, kv->batch, (hipStream_t)hip_stream);
     return check_launch();
+}
+
+psd_status psd_profile_enable(int32_t max_launches) {
+    for (hipEvent_t e : g_rec.ev) (void)hipEventDestroy(e);
+    g_rec.ev.clear(); g_rec.kind.clear();
+    g_rec.used = g_rec.cap = 0; g_rec.on = false; g_rec.open = false;
+    if (max_launches < 0) return PSD_ERR_SHAPE;
+    if (max_launches == 0) return PSD_OK;
+    g_rec.ev.resize(2 * (size_t)max_launches);
+    g_rec.kind.resize(max_launches);
+    for (size_t i = 0; i < g_rec.ev.size(); ++i) {
+        if (hipEventCreate(&g_rec.ev[i]) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(g_rec.ev[j]);
+            g_rec.ev.clear(); g_rec.kind.clear();
+            g_last_hip_error = (int32_t)hipGetLastError();
+            return PSD_ERR_HIP;
+        }
+    }
+    g_rec.cap = max_launches;
+    g_rec.on = true;
+    return PSD_OK;
+}
+
+psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind) {
+    if (!ms_by_kind || !launches_by_kind) return PSD_ERR_NULL;
+    for (int k = 0; k < PSD_KIND_COUNT; ++k) { ms_by_kind[k] = 0.0; launches_by_kind[k] = 0; }
+    if (g_rec.used == 0) return PSD_OK;
+    if (hipEventSynchronize(g_rec.ev[2 * g_rec.used - 1]) != hipSuccess) {
+        g_last_hip_error = (int32_t)hipGetLastError();
+        return PSD_ERR_HIP;
+    }
+    for (size_t i = 0; i < g_rec.used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_rec.ev[2 * i], g_rec.ev[2 * i + 1]) != hipSuccess) continue;
+        const int k = g_rec.kind[i];
+        if (k >= 0 && k < PSD_KIND_COUNT) { ms_by_kind[k] += ms; ++launches_by_kind[k]; }
+    }
+    g_rec.used = 0;
+    return PSD_OK;
 }
 
 psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream) {

@@ -21,6 +21,7 @@
 // of a lane are 8 consecutive keys).
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 #include "../../include/psd.h"
 
 namespace psd {
@@ -295,10 +296,16 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
     dim3 grid(a.splits, chunks, a.B * a.h_kv);
+    {
+    ScopedProf sp(PSD_KIND_ATTN, stream);
     if (QT == 1) attn_mfma_kernel<DH, 1><<<grid, 256, 0, stream>>>(a, scale_log2, range);
     else if (QT == 2) attn_mfma_kernel<DH, 2><<<grid, 256, 0, stream>>>(a, scale_log2, range);
     else if constexpr (DH <= 64) attn_mfma_kernel<DH, 4><<<grid, 256, 0, stream>>>(a, scale_log2, range);
-    if (a.splits > 1) attn_combine_kernel<<<a.B * a.R * a.h_q, DH, 0, stream>>>(a);
+    }
+    if (a.splits > 1) {
+        ScopedProf sp(PSD_KIND_ATTN_COMBINE, stream);
+        attn_combine_kernel<<<a.B * a.R * a.h_q, DH, 0, stream>>>(a);
+    }
 }
 
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream) {
@@ -310,6 +317,7 @@ void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream) {
     const float scale = 1.0f / sqrtf((float)a.d_h);
     dim3 grid(a.h_q, a.B * a.R);
     const size_t smem = (size_t)a.len_bound * sizeof(float);
+    ScopedProf sp(PSD_KIND_ATTN, stream);
     if (dtype == PSD_BF16) attn_simple_kernel<uint16_t><<<grid, 64, smem, stream>>>(a, scale);
     else attn_simple_kernel<float><<<grid, 64, smem, stream>>>(a, scale);
 }

@@ -16,6 +16,7 @@
 // so results are bit-reproducible.
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 #include "../../include/psd.h"
 
 namespace psd {
@@ -337,10 +338,12 @@ int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
 
 void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
     if (dtype != PSD_BF16) {
+        ScopedProf sp(PSD_KIND_GEMM_F32, stream);
         gemm_f32_kernel<<<(g.N + 3) / 4, 256, 0, stream>>>(g);
         return;
     }
     if (g.M <= 64) {
+        ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
         const int mt = (g.M + 15) / 16;
         if (mt == 1) gemm_bf16_skinny_kernel<1><<<grid, 256, 0, stream>>>(g);
@@ -348,11 +351,13 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         else if (mt == 3) gemm_bf16_skinny_kernel<3><<<grid, 256, 0, stream>>>(g);
         else gemm_bf16_skinny_kernel<4><<<grid, 256, 0, stream>>>(g);
     } else {
+        ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kBN) * ((g.M + kBM - 1) / kBM), g.splitk);
         gemm_bf16_tiled_kernel<<<grid, 256, 0, stream>>>(g);
     }
     if (g.splitk > 1) {
         const unsigned blocks = (unsigned)(((size_t)g.M * g.N + 255) / 256);
+        ScopedProf sp(PSD_KIND_GEMM_REDUCE, stream);
         gemm_splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(g);
     }
 }

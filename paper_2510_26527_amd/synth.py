@@ -146,6 +146,29 @@ def make_accept_inputs(rows, gamma, vocab, seed, n_p_rows=None, p_std=2.0, noise
     return {"p": p32.to(dtype), "q": q, "tokens": tokens, "uniforms": u}
 
 
+def make_draft_from_target(p_logits: torch.Tensor, noise_std: float, seed: int):
+    """Synthetic drafter for a verify step whose target logits p_logits [rows, gamma, V] (fp32)
+    are already known: drafter logits = p + N(0, noise_std^2) and draft tokens distributed as
+    softmax(drafter logits) (Gumbel-max).  Returns (q fp32 [rows, gamma, V], tokens int32)."""
+    gen = torch.Generator(device=p_logits.device)
+    gen.manual_seed(seed)
+    noise = torch.empty_like(p_logits, dtype=torch.float32)
+    noise.normal_(0.0, noise_std, generator=gen)
+    q = p_logits.float() + noise
+    g = torch.empty_like(q)
+    g.exponential_(1.0, generator=gen)
+    tokens = torch.argmax(q - torch.log(g), dim=-1).to(torch.int32)
+    return q, tokens
+
+
+def make_uniforms(shape, seed: int, device="cpu"):
+    """fp32 uniforms in [0, 1)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    u = torch.rand(shape, dtype=torch.float32, device=device, generator=gen)
+    return torch.clamp(u, max=float(np.nextafter(np.float32(1.0), np.float32(0.0))))
+
+
 def make_tape(seed: int, level: int, calls: int, width: int):
     """Uniform tape for one level of a chain: float32 [calls, width] in [0,1), counter-based
     (Philox keyed by seed and level) so both sides index the same numbers by (call, slot)."""
