@@ -43,6 +43,13 @@ class Model:
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._ws
 
+    def workspace_upto(self, batch, max_new, max_len):
+        """A workspace large enough for every n_new in 1..max_new."""
+        need = max(psd.psd_model_workspace_bytes(self.handle, batch, r, max_len) for r in range(1, max_new + 1))
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
     def close(self):
         if self.handle is not None:
             psd.psd_model_destroy(self.handle)
