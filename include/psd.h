@@ -87,6 +87,20 @@ psd_status psd_model_create(const psd_model_desc *desc, const void *const *weigh
                             int32_t n_ptrs, psd_model **out);
 psd_status psd_model_destroy(psd_model *m);
 
+/* Optional streaming copy of the projection weights for verify steps of up to 64 rows
+ * (batch * n_new <= 64), where the forward pass is bound by reading the weights once from HBM.
+ * psd_model_pack rewrites every projection matrix into caller memory in the order the
+ * wavefronts of the streaming GEMM load it (64-row x 128-column units of 16 KB, each stored
+ * as the 64 lanes' 16-byte operands, units of one projection contiguous), so that each
+ * wavefront reads one contiguous byte range.  packed_mem: device, 256-byte aligned, at least
+ * psd_model_packed_bytes() bytes (about the size of the weights), kept alive with the model;
+ * the row-major weights stay in use for larger steps and must stay alive too.  After a
+ * successful call, forwards with batch * n_new <= 64 read the packed copy; results are the same
+ * up to fp32 summation order.  Call it before sizing workspaces: the workspace need changes.
+ * PSD_BF16 models only (PSD_ERR_DTYPE otherwise); psd_model_packed_bytes returns 0 for others. */
+size_t psd_model_packed_bytes(const psd_model *m);
+psd_status psd_model_pack(psd_model *m, void *packed_mem, size_t packed_bytes, void *hip_stream);
+
 /* Bytes of workspace psd_model_forward needs for this batch / n_new / cache length
  * (0 on a bad argument).  The workspace must be 256-byte aligned. */
 size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_new, int32_t max_len);

@@ -34,6 +34,8 @@ _SIGNATURES = {
     "psd_model_create": (_i32, [ctypes.POINTER(psd_model_desc), ctypes.POINTER(_vp), _i32, ctypes.POINTER(_vp)]),
     "psd_model_destroy": (_i32, [_vp]),
     "psd_model_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32]),
+    "psd_model_packed_bytes": (_sz, [_vp]),
+    "psd_model_pack": (_i32, [_vp, _vp, _sz, _vp]),
     "psd_kv_bytes": (_sz, [_vp, _i32, _i32]),
     "psd_kv_create": (_i32, [_vp, _i32, _i32, _vp, _vp, _vp, _i32, ctypes.POINTER(_vp)]),
     "psd_kv_destroy": (_i32, [_vp]),
@@ -117,6 +119,15 @@ def psd_model_destroy(model):
 
 def psd_model_workspace_bytes(model, batch, n_new, max_len):
     return lib().psd_model_workspace_bytes(model, batch, n_new, max_len)
+
+
+def psd_model_packed_bytes(model):
+    return lib().psd_model_packed_bytes(model)
+
+
+def psd_model_pack(model, packed_mem, stream=None):
+    _check(lib().psd_model_pack(model, _ptr(packed_mem), packed_mem.numel() * packed_mem.element_size(),
+                                _stream_ptr(stream)), "psd_model_pack")
 
 
 def psd_kv_bytes(model, batch, max_len):

@@ -44,7 +44,13 @@ struct psd_model {
     const void *layer(int l, int which) const { return w[1 + 9 * l + which]; }
     const void *final_norm() const { return w[1 + 9 * d.n_layers]; }
     const void *lm_head() const { return w[2 + 9 * d.n_layers]; }
+    // repacked copies for the M <= 64 path (psd_model_pack): per layer qkv, o, gate|up, down; then lm_head
+    const char *packed = nullptr;
+    std::vector<size_t> pack_off;    // 4 * n_layers + 1 offsets into `packed`
+    const void *pack(int l, int which) const { return packed ? packed + pack_off[4 * l + which] : nullptr; }
+    const void *pack_head() const { return packed ? packed + pack_off[4 * d.n_layers] : nullptr; }
 };
+enum { P_QKV = 0, P_O, P_GU, P_DOWN };
 enum { W_ATTN_NORM = 0, W_Q, W_K, W_V, W_O, W_FFN_NORM, W_GATE, W_UP, W_DOWN };
 
 struct psd_kv {
@@ -99,6 +105,7 @@ psd_status psd_model_create(const psd_model_desc *desc, const void *const *weigh
     if (d.n_q_heads % d.n_kv_heads) return PSD_ERR_SHAPE;
     const int align = d.dtype == PSD_BF16 ? 128 : 32;      // the bf16 GEMMs step K by 128
     if (d.d_model % align || d.d_ffn % align || (d.n_q_heads * d.d_head) % align) return PSD_ERR_SHAPE;
+    if (d.d_model > 8192) return PSD_ERR_SHAPE;              // the row-wise kernels keep a row in registers
     if (d.dtype == PSD_BF16 && d.d_head == 32) return PSD_ERR_SHAPE;
     if (!(d.rope_theta > 0.f) || !(d.rms_eps >= 0.f)) return PSD_ERR_SHAPE;
     if (n_ptrs != 3 + 9 * d.n_layers) return PSD_ERR_SHAPE;
@@ -118,6 +125,66 @@ psd_status psd_model_destroy(psd_model *m) {
     if (!m) return PSD_ERR_NULL;
     delete m;
     return PSD_OK;
+}
+
+static void pack_layout(const psd_model *m, std::vector<size_t> *off, size_t *total) {
+    const psd_model_desc &d = m->d;
+    const int hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
+    const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
+    size_t at = 0;
+    off->clear();
+    for (int l = 0; l < d.n_layers; ++l) {
+        off->push_back(at); at += gemm_pack_bytes(n_qkv, 3, d.d_model);
+        off->push_back(at); at += gemm_pack_bytes(n_o, 1, hd);
+        off->push_back(at); at += gemm_pack_bytes(n_gu, 2, d.d_model);
+        off->push_back(at); at += gemm_pack_bytes(n_o, 1, d.d_ffn);
+    }
+    off->push_back(at); at += gemm_pack_bytes(n_v, 1, d.d_model);
+    *total = at;
+}
+
+size_t psd_model_packed_bytes(const psd_model *m) {
+    if (!m || m->d.dtype != PSD_BF16) return 0;
+    std::vector<size_t> off;
+    size_t total = 0;
+    pack_layout(m, &off, &total);
+    return total;
+}
+
+psd_status psd_model_pack(psd_model *m, void *packed_mem, size_t packed_bytes, void *hip_stream) {
+    if (!m || !packed_mem) return PSD_ERR_NULL;
+    if (m->d.dtype != PSD_BF16) return PSD_ERR_DTYPE;
+    std::vector<size_t> off;
+    size_t total = 0;
+    pack_layout(m, &off, &total);
+    if ((uintptr_t)packed_mem % 256 || packed_bytes < total) return PSD_ERR_WORKSPACE;
+    const psd_model_desc &d = m->d;
+    const int hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *base = (char *)packed_mem;
+    (void)hipGetLastError();
+    for (int l = 0; l < d.n_layers; ++l) {
+        const void *qkv[3] = {m->layer(l, W_Q), m->layer(l, W_K), m->layer(l, W_V)};
+        const int n_qkv[3] = {hd, kvd, kvd};
+        launch_gemm_pack(qkv, n_qkv, 3, d.d_model, base + off[4 * l + P_QKV], st);
+        const void *o[1] = {m->layer(l, W_O)};
+        const int n_o[1] = {d.d_model};
+        launch_gemm_pack(o, n_o, 1, hd, base + off[4 * l + P_O], st);
+        const void *gu[2] = {m->layer(l, W_GATE), m->layer(l, W_UP)};
+        const int n_gu[2] = {d.d_ffn, d.d_ffn};
+        launch_gemm_pack(gu, n_gu, 2, d.d_model, base + off[4 * l + P_GU], st);
+        const void *dn[1] = {m->layer(l, W_DOWN)};
+        launch_gemm_pack(dn, n_o, 1, d.d_ffn, base + off[4 * l + P_DOWN], st);
+    }
+    const void *hw[1] = {m->lm_head()};
+    const int n_v[1] = {d.vocab};
+    launch_gemm_pack(hw, n_v, 1, d.d_model, base + off[4 * d.n_layers], st);
+    const psd_status s = check_launch();
+    if (s == PSD_OK) {
+        m->packed = base;
+        m->pack_off = off;
+    }
+    return s;
 }
 
 size_t psd_kv_bytes(const psd_model *m, int32_t batch, int32_t max_len) {
@@ -156,37 +223,41 @@ namespace {
 struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
-    size_t off_x, off_xn, off_qkv, off_q, off_attn, off_gu, off_h, off_partial, off_po, off_pml, total;
+    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, total;
 };
 
-ForwardPlan plan_forward(const psd_model_desc &d, int batch, int n_new, int n_logit_rows, int len_bound) {
+ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound) {
+    const psd_model_desc &d = mdl->d;
     ForwardPlan p{};
     const int M = batch * n_new;
     p.M = M;
     const int hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
     p.width_qkv = hd + 2 * kvd;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
-    p.sk_qkv = gemm_pick_splitk(d.dtype, M, d.d_model, p.width_qkv, n_qkv, 3);
-    p.sk_o = gemm_pick_splitk(d.dtype, M, hd, d.d_model, n_o, 1);
-    p.sk_gu = gemm_pick_splitk(d.dtype, M, d.d_model, 2 * d.d_ffn, n_gu, 2);
-    p.sk_down = gemm_pick_splitk(d.dtype, M, d.d_ffn, d.d_model, n_o, 1);
     const int Ml = batch * n_logit_rows;
-    p.sk_head = Ml > 0 ? gemm_pick_splitk(d.dtype, Ml, d.d_model, d.vocab, n_v, 1) : 1;
+    auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
+        if (mdl->packed && rows <= 64) return gemm_packed_splits(rows, K, n, nseg);
+        return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
+    };
+    p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
+    p.sk_o = splits(M, hd, d.d_model, n_o, 1);
+    p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
+    p.sk_down = splits(M, d.d_ffn, d.d_model, n_o, 1);
+    p.sk_head = Ml > 0 ? splits(Ml, d.d_model, d.vocab, n_v, 1) : 1;
     p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
     const size_t act = 4;                                    // activations are fp32 for both dtypes
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += align256(bytes); return o; };
     p.off_x = take((size_t)M * d.d_model * 4);
     p.off_xn = take((size_t)M * d.d_model * act);
-    p.off_qkv = take((size_t)M * p.width_qkv * 4);
     p.off_q = take((size_t)M * hd * act);
     p.off_attn = take((size_t)M * hd * act);
-    p.off_gu = take((size_t)M * 2 * d.d_ffn * 4);
     p.off_h = take((size_t)M * d.d_ffn * act);
     size_t part = 0;
-    auto need = [&](int sk, int rows, int N) { if (sk > 1) { const size_t b = (size_t)sk * rows * N * 4; if (b > part) part = b; } };
+    auto need = [&](int sk, int rows, int N) { const size_t b = (size_t)sk * rows * N * 4; if (b > part) part = b; };
     need(p.sk_qkv, M, p.width_qkv); need(p.sk_o, M, d.d_model); need(p.sk_gu, M, 2 * d.d_ffn);
-    need(p.sk_down, M, d.d_model); need(p.sk_head, Ml, d.vocab);
+    need(p.sk_down, M, d.d_model);
+    if (p.sk_head > 1) need(p.sk_head, Ml, d.vocab);             // a single split writes the logits in place
     p.off_partial = take(part);
     p.off_po = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * d.d_head * 4 : 0);
     p.off_pml = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * 2 * 4 : 0);
@@ -211,8 +282,8 @@ size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_ne
     // take the largest need over all of them
     size_t worst = 0;
     for (int rows = 0; rows <= n_new; ++rows) {
-        const size_t a = plan_forward(m->d, batch, n_new, rows, max_len).total;
-        const size_t b = plan_forward(m->d, batch, n_new, rows, n_new).total;
+        const size_t a = plan_forward(m, batch, n_new, rows, max_len).total;
+        const size_t b = plan_forward(m, batch, n_new, rows, n_new).total;
         worst = a > worst ? a : worst;
         worst = b > worst ? b : worst;
     }
@@ -231,36 +302,38 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
     if (n_logit_rows > 0 && !logits_out_dev) return PSD_ERR_NULL;
     if (kv->len_ub + n_new > kv->max_len) return PSD_ERR_CAPACITY;
     const int len_bound = kv->len_ub + n_new;
-    const ForwardPlan p = plan_forward(d, B, n_new, n_logit_rows, len_bound);
+    const ForwardPlan p = plan_forward(m, B, n_new, n_logit_rows, len_bound);
     if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < p.total) return PSD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     float *x = (float *)(ws + p.off_x);
     float *xn = (float *)(ws + p.off_xn);
-    float *qkv = (float *)(ws + p.off_qkv);
     float *q = (float *)(ws + p.off_q);
     float *attn = (float *)(ws + p.off_attn);
-    float *gu = (float *)(ws + p.off_gu);
     float *h = (float *)(ws + p.off_h);
     float *partial = (float *)(ws + p.off_partial);
     const int M = p.M, hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
-    const size_t es = elem_size(d.dtype);
-    const size_t kv_layer = (size_t)B * d.n_kv_heads * kv->max_len * d.d_head * es;
+    const size_t kv_layer = (size_t)B * d.n_kv_heads * kv->max_len * d.d_head * elem_size(d.dtype);
 
     (void)hipGetLastError();
-    launch_embed(d.dtype, m->embed(), tokens_dev, x, M, d.d_model, d.vocab, st);
-    for (int l = 0; l < d.n_layers; ++l) {
-        launch_rmsnorm(d.dtype, x, m->layer(l, W_ATTN_NORM), xn, M, d.d_model, d.rms_eps, d.d_model, st);
+    auto norm_gain = [&](int l) { return l < d.n_layers ? m->layer(l, W_ATTN_NORM) : m->final_norm(); };
+    auto gemm = [&](const float *xin, int rows, int K, const void *w0, int n0, const void *w1, int n1,
+                    const void *w2, int n2, int sk, float *dst, const void *wpack) {
         GemmArgs g{};
-        g.x = xn; g.w[0] = m->layer(l, W_Q); g.w[1] = m->layer(l, W_K); g.w[2] = m->layer(l, W_V);
-        g.n[0] = hd; g.n[1] = kvd; g.n[2] = kvd; g.nseg = 3;
-        g.M = M; g.K = d.d_model; g.N = p.width_qkv; g.out = qkv; g.ldo = p.width_qkv; g.accumulate = 0;
-        g.partial = partial; g.splitk = p.sk_qkv;
+        g.wpack = rows <= 64 ? wpack : nullptr;
+        g.x = xin; g.x_rows_per_group = rows > 0 ? rows : 1; g.x_group_stride = 0; g.x_group_offset = 0;
+        g.w[0] = w0; g.w[1] = w1; g.w[2] = w2; g.n[0] = n0; g.n[1] = n1; g.n[2] = n2;
+        g.nseg = w2 ? 3 : (w1 ? 2 : 1);
+        g.M = rows; g.K = K; g.N = n0 + n1 + n2; g.partial = dst; g.splitk = sk; g.reduced = nullptr;
+        g.pack_tiles = gemm_pack_tiles(g.n, g.nseg);
         launch_gemm(d.dtype, g, st);
-
+    };
+    launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, M, d.d_model, d.vocab, d.rms_eps, st);
+    for (int l = 0; l < d.n_layers; ++l) {
+        gemm(xn, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial, m->pack(l, P_QKV));
         char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
-        launch_rope_append(d.dtype, qkv, q, kl, vl, kv->lens, B, n_new, d.n_q_heads, d.n_kv_heads, d.d_head,
-                           kv->max_len, d.rope_theta, st);
+        launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, q, kl, vl, kv->lens, B, n_new, d.n_q_heads, d.n_kv_heads,
+                                  d.d_head, kv->max_len, d.rope_theta, st);
         AttnArgs a{};
         a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn;
         a.B = B; a.R = n_new; a.h_q = d.n_q_heads; a.h_kv = d.n_kv_heads; a.d_h = d.d_head; a.max_len = kv->max_len;
@@ -268,41 +341,24 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         a.splits = p.attn_splits;
         launch_attention(d.dtype, a, st);
 
-        GemmArgs o{};
-        o.x = attn; o.w[0] = m->layer(l, W_O); o.n[0] = d.d_model; o.nseg = 1;
-        o.M = M; o.K = hd; o.N = d.d_model; o.out = x; o.ldo = d.d_model; o.accumulate = 1;
-        o.partial = partial; o.splitk = p.sk_o;
-        launch_gemm(d.dtype, o, st);
-
-        launch_rmsnorm(d.dtype, x, m->layer(l, W_FFN_NORM), xn, M, d.d_model, d.rms_eps, d.d_model, st);
-        GemmArgs u{};
-        u.x = xn; u.w[0] = m->layer(l, W_GATE); u.w[1] = m->layer(l, W_UP); u.n[0] = d.d_ffn; u.n[1] = d.d_ffn; u.nseg = 2;
-        u.M = M; u.K = d.d_model; u.N = 2 * d.d_ffn; u.out = gu; u.ldo = 2 * d.d_ffn; u.accumulate = 0;
-        u.partial = partial; u.splitk = p.sk_gu;
-        launch_gemm(d.dtype, u, st);
-        launch_swiglu(d.dtype, gu, h, M, d.d_ffn, st);
-
-        GemmArgs dn{};
-        dn.x = h; dn.w[0] = m->layer(l, W_DOWN); dn.n[0] = d.d_model; dn.nseg = 1;
-        dn.M = M; dn.K = d.d_ffn; dn.N = d.d_model; dn.out = x; dn.ldo = d.d_model; dn.accumulate = 1;
-        dn.partial = partial; dn.splitk = p.sk_down;
-        launch_gemm(d.dtype, dn, st);
+        gemm(attn, M, hd, m->layer(l, W_O), d.d_model, nullptr, 0, nullptr, 0, p.sk_o, partial, m->pack(l, P_O));
+        launch_reduce_residual_norm(d.dtype, partial, p.sk_o, x, m->layer(l, W_FFN_NORM), xn, M, d.d_model, d.rms_eps, st);
+        gemm(xn, M, d.d_model, m->layer(l, W_GATE), d.d_ffn, m->layer(l, W_UP), d.d_ffn, nullptr, 0, p.sk_gu, partial, m->pack(l, P_GU));
+        launch_reduce_swiglu(partial, p.sk_gu, h, M, d.d_ffn, st);
+        gemm(h, M, d.d_ffn, m->layer(l, W_DOWN), d.d_model, nullptr, 0, nullptr, 0, p.sk_down, partial, m->pack(l, P_DOWN));
+        launch_reduce_residual_norm(d.dtype, partial, p.sk_down, x, norm_gain(l + 1), xn, M, d.d_model, d.rms_eps, st);
     }
     if (n_logit_rows > 0) {
-        // final norm + lm_head on the last n_logit_rows rows of every sequence
-        const int Ml = B * n_logit_rows;
-        if (n_logit_rows == n_new) {
-            launch_rmsnorm(d.dtype, x, m->final_norm(), xn, M, d.d_model, d.rms_eps, d.d_model, st);
-        } else {
-            for (int b = 0; b < B; ++b)
-                launch_rmsnorm(d.dtype, x + ((size_t)b * n_new + (n_new - n_logit_rows)) * d.d_model, m->final_norm(),
-                               xn + (size_t)b * n_logit_rows * d.d_model, n_logit_rows, d.d_model,
-                               d.rms_eps, d.d_model, st);
-        }
+        // lm_head on the last n_logit_rows rows of every sequence: xn already holds the final norm
         GemmArgs hg{};
-        hg.x = xn; hg.w[0] = m->lm_head(); hg.n[0] = d.vocab; hg.nseg = 1;
-        hg.M = Ml; hg.K = d.d_model; hg.N = d.vocab; hg.out = logits_out_dev; hg.ldo = d.vocab; hg.accumulate = 0;
-        hg.partial = partial; hg.splitk = p.sk_head;
+        hg.x = xn; hg.x_rows_per_group = n_logit_rows; hg.x_group_stride = n_new; hg.x_group_offset = n_new - n_logit_rows;
+        hg.w[0] = m->lm_head(); hg.n[0] = d.vocab; hg.nseg = 1;
+        hg.M = B * n_logit_rows; hg.K = d.d_model; hg.N = d.vocab;
+        hg.wpack = hg.M <= 64 ? m->pack_head() : nullptr;
+        hg.pack_tiles = gemm_pack_tiles(hg.n, 1);
+        hg.splitk = p.sk_head;
+        hg.partial = p.sk_head > 1 ? partial : logits_out_dev;
+        hg.reduced = p.sk_head > 1 ? logits_out_dev : nullptr;
         launch_gemm(d.dtype, hg, st);
     }
     launch_advance_lens(kv->lens, B, n_new, kv->max_len, st);

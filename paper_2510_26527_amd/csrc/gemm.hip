@@ -7,13 +7,19 @@
 //                            global memory into MFMA A-operand registers with 16-byte loads
 //                            (no LDS), the few activation rows are the B operand, K is split
 //                            over the four wavefronts of a block and over blocks.
+//   gemm_bf16_stream_kernel  M <= 64 on weights repacked by gemm_pack_kernel: the same MFMA tiling,
+//                            but every 16 KB unit (64 rows x 128 k) is stored in exactly the order the
+//                            lanes load it, units of a GEMM are contiguous, and the grid is persistent:
+//                            each wavefront streams an equal, contiguous byte range of the weights
+//                            (stream-K) and writes one partial per tile it touches.
 //   gemm_bf16_tiled_kernel   M > 64.  128x128x64 LDS-staged tiles, 32x32x16 bf16 MFMA.
 // Activations are fp32 in memory in every case.  The bf16 kernels feed each activation to the
 // matrix cores as a pair of bf16 values hi + lo (two MFMAs against the same weight operand):
 // with plain bf16 activations the logits of the 7B-shaped random-init models are 3e-2 off the
 // fp64 result, above the 2e-2 bar; the weights, which are what streams from HBM, stay bf16.
-// Split-K partial sums are written to scratch and added in split order by a second kernel,
-// so results are bit-reproducible.
+// Every kernel writes its result as split-K partials [splitk][M][N] (splitk >= 1); the consumer
+// (the fused row-wise kernels, or gemm_splitk_reduce_kernel for the logits) adds them in split
+// order, so results are bit-reproducible.
 #include "common.h"
 #include "kernels.h"
 #include "prof.h"
@@ -21,6 +27,11 @@
 
 namespace psd {
 namespace {
+
+// source row of activation row m: rows may be a strided subset (the last rows of each sequence)
+__device__ __forceinline__ size_t x_row(const GemmArgs &g, int m) {
+    return (size_t)(m / g.x_rows_per_group) * g.x_group_stride + g.x_group_offset + (m % g.x_rows_per_group);
+}
 
 // ------------------------------------------------------------------------------ fp32
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
@@ -39,7 +50,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
             const float w = wrow[k];
 #pragma unroll
             for (int mm = 0; mm < 8; ++mm)
-                if (m0 + mm < g.M) acc[mm] += w * x[(size_t)(m0 + mm) * g.K + k];
+                if (m0 + mm < g.M) acc[mm] += w * x[x_row(g, m0 + mm) * g.K + k];
         }
 #pragma unroll
         for (int mm = 0; mm < 8; ++mm) acc[mm] = wave_sum(acc[mm]);
@@ -47,8 +58,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 #pragma unroll
             for (int mm = 0; mm < 8; ++mm)
                 if (m0 + mm < g.M) {
-                    float *o = g.out + (size_t)(m0 + mm) * g.ldo + n;
-                    *o = g.accumulate ? *o + acc[mm] : acc[mm];
+                    g.partial[(size_t)(m0 + mm) * g.N + n] = acc[mm];
                 }
         }
     }
@@ -76,13 +86,10 @@ __device__ __forceinline__ TileRef find_tile(const GemmArgs &g, int tile, int ti
 }
 
 __device__ __forceinline__ void store_out(const GemmArgs &g, int ks, int m, int col, float v) {
-    if (g.splitk > 1) {
-        g.partial[((size_t)ks * g.M + m) * g.N + col] = v;
-    } else {
-        float *o = g.out + (size_t)m * g.ldo + col;
-        *o = g.accumulate ? *o + v : v;
-    }
+    g.partial[((size_t)ks * g.M + m) * g.N + col] = v;
 }
+
+
 
 __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs g) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -90,8 +97,8 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs g) {
     const size_t m = idx / g.N, col = idx % g.N;
     float v = 0.f;
     for (int ks = 0; ks < g.splitk; ++ks) v += g.partial[(size_t)ks * g.M * g.N + idx];
-    float *o = g.out + m * g.ldo + col;
-    *o = g.accumulate ? *o + v : v;
+    (void)m; (void)col;
+    g.reduced[idx] = v;
 }
 
 // ------------------------------------------------------------------------------ bf16 skinny
@@ -103,8 +110,9 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs g) {
 // cover 2 x 128 contiguous bytes; the activation operand uses the same permutation.
 constexpr int kSkinnyRows = 64;
 constexpr int kSkinnyStepK = 128;
+constexpr int kStreamBlocks = 512;                 // persistent grid of the stream-K kernel: 2 blocks per CU
 
-template <int MT>
+template <int MT, bool PACKED>
 __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
@@ -130,7 +138,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
     for (int mt = 0; mt < MT; ++mt) {
         const int tok = mt * 16 + i;
         xvalid[mt] = tok < g.M;
-        xp[mt] = X + (size_t)min(tok, g.M - 1) * K + gq * 16;
+        xp[mt] = X + x_row(g, min(tok, g.M - 1)) * K + gq * 16;
     }
 
     f32x4 acc[4][MT];
@@ -140,13 +148,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
         for (int mt = 0; mt < MT; ++mt) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     bf16x8 a_cur[4][4], a_nxt[4][4];
+    // packed weights: unit (tile, step) is 16 slots of 1 KB, slot strip*4+q holds this lane's operand
+    const bf16x8 *pk = reinterpret_cast<const bf16x8 *>(g.wpack) + (size_t)blockIdx.x * nsteps * 1024 + lane;
     auto load_a = [&](bf16x8 (&dst)[4][4], int step) {
         const int kk = step * kSkinnyStepK;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                dst[s][q] = *reinterpret_cast<const bf16x8 *>(wp[s] + kk + (q >> 1) * 64 + (q & 1) * 8);
+            for (int q = 0; q < 4; ++q) {
+                if constexpr (PACKED) dst[s][q] = __builtin_nontemporal_load(pk + (size_t)step * 1024 + (s * 4 + q) * 64);
+                else dst[s][q] = *reinterpret_cast<const bf16x8 *>(wp[s] + kk + (q >> 1) * 64 + (q & 1) * 8);
+            }
     };
     if (s0 < s1) load_a(a_cur, s0);
     for (int step = s0; step < s1; ++step) {
@@ -201,6 +213,138 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
     }
 }
 
+// ------------------------------------------------------------------------------ bf16 stream-K on packed weights
+// Packed layout of one GEMM (all its weight matrices, in segment order): tiles of 64 rows, each
+// tile ns = K/128 units of 16 KB.  Unit = 16 slots of 1 KB; slot (strip, q) holds, for lane l =
+// (i = l & 15, gq = l >> 4), the 8 bf16 W[tile*64 + strip*16 + i][step*128 + (q>>1)*64 + gq*16 + (q&1)*8 ...].
+// Rows past the end of a matrix are stored as zeros.
+constexpr int kUnitBytes = kSkinnyRows * kSkinnyStepK * 2;
+constexpr int kUnitVec = kUnitBytes / 16;          // 16-byte vectors per unit
+
+__global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t *W, int N, int K, u32x4 *dst) {
+    // one thread per 16-byte vector of the packed copy
+    const size_t vec = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int ns = K / kSkinnyStepK;
+    const size_t n_units = (size_t)((N + kSkinnyRows - 1) / kSkinnyRows) * ns;
+    if (vec >= n_units * kUnitVec) return;
+    const size_t unit = vec / kUnitVec;
+    const int within = (int)(vec % kUnitVec), slot = within >> 6, lane = within & 63;
+    const int tile = (int)(unit / ns), step = (int)(unit % ns);
+    const int strip = slot >> 2, q = slot & 3, i = lane & 15, gq = lane >> 4;
+    const int row = tile * kSkinnyRows + strip * 16 + i;
+    const int k = step * kSkinnyStepK + (q >> 1) * 64 + gq * 16 + (q & 1) * 8;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (row < N) v = *reinterpret_cast<const u32x4 *>(W + (size_t)row * K + k);
+    dst[vec] = v;
+}
+
+// first unit of wavefront w when U units are dealt to P wavefronts in contiguous, near-equal ranges
+__host__ __device__ __forceinline__ long range_begin(long w, long U, long P) { return w * U / P; }
+// the wavefront whose range holds unit u
+__host__ __device__ __forceinline__ long range_owner(long u, long U, long P) { return ((u + 1) * P - 1) / U; }
+
+template <int MT>
+__global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, gq = lane >> 4;
+    const float *X = g.x;
+    const int K = g.K, ns = K / kSkinnyStepK;
+    const long U = (long)g.pack_tiles * ns, P = (long)gridDim.x * 4;
+    const long w = (long)blockIdx.x * 4 + wave;
+    const long u0 = range_begin(w, U, P), u1 = range_begin(w + 1, U, P);
+    if (u0 >= u1) return;
+
+    const float *xp[MT];
+    bool xvalid[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int tok = mt * 16 + i;
+        xvalid[mt] = tok < g.M;
+        xp[mt] = X + x_row(g, min(tok, g.M - 1)) * K + gq * 16;
+    }
+    f32x4 acc[4][MT];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const u32x4 *wbase = reinterpret_cast<const u32x4 *>(g.wpack) + lane;
+    u32x4 a_cur[16], a_nxt[16];
+    auto load_unit = [&](u32x4 (&dst)[16], long u) {
+        const u32x4 *p = wbase + u * kUnitVec;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) dst[j] = __builtin_nontemporal_load(p + j * 64);
+    };
+    __shared__ float red[4][kSkinnyRows][17];      // per-wavefront transpose buffer for the partial stores
+
+    load_unit(a_cur, u0);
+    for (long u = u0; u < u1; ++u) {
+        if (u + 1 < u1) load_unit(a_nxt, u + 1);
+        const int tile = (int)(u / ns), step = (int)(u % ns);
+        const int kk = step * kSkinnyStepK;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16x8 bh[MT], bl[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                f32x8 xv = load_f32x8(xp[mt] + kk + (q >> 1) * 64 + (q & 1) * 8);
+                if (!xvalid[mt]) xv = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                split_bf16(xv, &bh[mt], &bl[mt]);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[s * 4 + q]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh[mt], acc[s][mt], 0, 0, 0);
+                    acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl[mt], acc[s][mt], 0, 0, 0);
+                }
+            }
+        }
+        if (step == ns - 1 || u + 1 == u1) {
+            // ---- flush this wavefront's share of tile `tile` into its partial slot
+            const TileRef t = find_tile(g, tile, kSkinnyRows);
+            const int seg_rows = g.n[t.seg];
+            const long w_lo = range_owner((long)tile * ns, U, P);
+            const int slot = (int)(w - w_lo);
+            const int row = t.row0 + lane;                   // lane = row of the tile from here on
+            const bool row_ok = row < seg_rows;
+            const size_t col = (size_t)t.col0 + row;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][mt][v];
+                __builtin_amdgcn_wave_barrier();
+                if (row_ok) {
+                    for (int mm = 0; mm < 16; ++mm) {
+                        const int tok = mt * 16 + mm;
+                        if (tok < g.M) g.partial[((size_t)slot * g.M + tok) * g.N + col] = red[wave][lane][mm];
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int s = 0; s < 4; ++s) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            if (step == ns - 1 && row_ok) {
+                // the wavefront that finishes a tile zeroes the slots no wavefront writes
+                const long w_hi = w;
+                for (int j = 0; j < g.splitk; ++j) {
+                    const long wj = w_lo + j;
+                    const bool written = wj <= w_hi && range_begin(wj, U, P) < range_begin(wj + 1, U, P);
+                    if (!written)
+                        for (int tok = 0; tok < g.M; ++tok) g.partial[((size_t)j * g.M + tok) * g.N + col] = 0.f;
+                }
+            }
+        }
+        if (u + 1 < u1) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) a_cur[j] = a_nxt[j];
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------ bf16 tiled
 constexpr int kBM = 128, kBN = 128, kBK = 64, kLdsStride = 72;   // 72 elements = 144 B rows: no bank conflicts
 
@@ -229,7 +373,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(GemmArgs g) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
-        xg[c] = X + (size_t)min(m_base + row, g.M - 1) * K + col;
+        xg[c] = X + x_row(g, min(m_base + row, g.M - 1)) * K + col;
         wg[c] = W + (size_t)min(t.row0 + row, seg_rows - 1) * K + col;
         lds_off[c] = row * kLdsStride + col;
     }
@@ -314,6 +458,50 @@ int tiles_of(const int *n, int nseg, int rows) {
 
 }  // namespace
 
+// Stream-K pays off when there are many tiles: then few wavefronts share a tile.  With few tiles
+// (N = d_model projections) the K range of a tile is split over the four wavefronts of a block, added
+// through LDS, and over blocks (gemm_bf16_skinny_kernel), which keeps the partial slots few.
+bool gemm_use_stream(int tiles) { return tiles >= 128; }
+
+int gemm_stream_grid(int tiles, int K) {
+    const long U = (long)tiles * (K / kSkinnyStepK);
+    long blocks = U / 4;                              // every wavefront gets at least one unit
+    if (blocks > kStreamBlocks) blocks = kStreamBlocks;
+    return blocks < 1 ? 1 : (int)blocks;
+}
+
+// largest number of wavefronts that share one tile, i.e. partial slots per output element
+int gemm_stream_slots(int tiles, int K) {
+    const long ns = K / kSkinnyStepK, U = (long)tiles * ns, P = (long)gemm_stream_grid(tiles, K) * 4;
+    long worst = 1;
+    for (long t = 0; t < tiles; ++t) {
+        const long span = range_owner((t + 1) * ns - 1, U, P) - range_owner(t * ns, U, P) + 1;
+        if (span > worst) worst = span;
+    }
+    return (int)worst;
+}
+
+int gemm_pack_tiles(const int *n, int nseg) { return tiles_of(n, nseg, kSkinnyRows); }
+size_t gemm_pack_bytes(const int *n, int nseg, int K) {
+    return (size_t)tiles_of(n, nseg, kSkinnyRows) * (K / kSkinnyStepK) * kUnitBytes;
+}
+
+void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, hipStream_t stream) {
+    char *out = (char *)dst;
+    for (int s = 0; s < nseg; ++s) {
+        const size_t units = (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * (K / kSkinnyStepK);
+        const size_t vecs = units * kUnitVec;
+        gemm_pack_kernel<<<(unsigned)((vecs + 255) / 256), 256, 0, stream>>>((const uint16_t *)w[s], n[s], K, (u32x4 *)out);
+        out += units * kUnitBytes;
+    }
+}
+
+int gemm_packed_splits(int M, int K, const int *n, int nseg) {
+    const int tiles = tiles_of(n, nseg, kSkinnyRows);
+    if (gemm_use_stream(tiles)) return gemm_stream_slots(tiles, K);
+    return gemm_pick_splitk(PSD_BF16, M, K, 0, n, nseg);
+}
+
 int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
     (void)N;
     if (dtype != PSD_BF16) return 1;
@@ -342,20 +530,35 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         gemm_f32_kernel<<<(g.N + 3) / 4, 256, 0, stream>>>(g);
         return;
     }
-    if (g.M <= 64) {
+    if (g.M <= 64 && g.wpack && gemm_use_stream(g.pack_tiles)) {
+        ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
+        const int grid = gemm_stream_grid(g.pack_tiles, g.K);
+        const int mt = (g.M + 15) / 16;
+        if (mt == 1) gemm_bf16_stream_kernel<1><<<grid, 256, 0, stream>>>(g);
+        else if (mt == 2) gemm_bf16_stream_kernel<2><<<grid, 256, 0, stream>>>(g);
+        else if (mt == 3) gemm_bf16_stream_kernel<3><<<grid, 256, 0, stream>>>(g);
+        else gemm_bf16_stream_kernel<4><<<grid, 256, 0, stream>>>(g);
+    } else if (g.M <= 64) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
         const int mt = (g.M + 15) / 16;
-        if (mt == 1) gemm_bf16_skinny_kernel<1><<<grid, 256, 0, stream>>>(g);
-        else if (mt == 2) gemm_bf16_skinny_kernel<2><<<grid, 256, 0, stream>>>(g);
-        else if (mt == 3) gemm_bf16_skinny_kernel<3><<<grid, 256, 0, stream>>>(g);
-        else gemm_bf16_skinny_kernel<4><<<grid, 256, 0, stream>>>(g);
+        if (g.wpack) {
+            if (mt == 1) gemm_bf16_skinny_kernel<1, true><<<grid, 256, 0, stream>>>(g);
+            else if (mt == 2) gemm_bf16_skinny_kernel<2, true><<<grid, 256, 0, stream>>>(g);
+            else if (mt == 3) gemm_bf16_skinny_kernel<3, true><<<grid, 256, 0, stream>>>(g);
+            else gemm_bf16_skinny_kernel<4, true><<<grid, 256, 0, stream>>>(g);
+        } else {
+            if (mt == 1) gemm_bf16_skinny_kernel<1, false><<<grid, 256, 0, stream>>>(g);
+            else if (mt == 2) gemm_bf16_skinny_kernel<2, false><<<grid, 256, 0, stream>>>(g);
+            else if (mt == 3) gemm_bf16_skinny_kernel<3, false><<<grid, 256, 0, stream>>>(g);
+            else gemm_bf16_skinny_kernel<4, false><<<grid, 256, 0, stream>>>(g);
+        }
     } else {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kBN) * ((g.M + kBM - 1) / kBM), g.splitk);
         gemm_bf16_tiled_kernel<<<grid, 256, 0, stream>>>(g);
     }
-    if (g.splitk > 1) {
+    if (g.splitk > 1 && g.reduced) {
         const unsigned blocks = (unsigned)(((size_t)g.M * g.N + 255) / 256);
         ScopedProf sp(PSD_KIND_GEMM_REDUCE, stream);
         gemm_splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(g);

@@ -34,18 +34,28 @@ void launch_accept(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
 // y[m][n] = sum_k x[m][k] * W[n][k]; W is up to three row-major [n_i][K] matrices whose
 // outputs are concatenated along n (QKV, gate|up).
 struct GemmArgs {
-    const float *x;               // [M][K] fp32 activations
+    const float *x;               // fp32 activations, K contiguous; row m is read from source row
+                                  //   (m / x_rows_per_group) * x_group_stride + x_group_offset + m % x_rows_per_group
+    int x_rows_per_group, x_group_stride, x_group_offset;
     const void *w[3];
     int n[3];
     int nseg;
     int M, K, N;                  // N = sum n[i]
-    float *out;                   // [M][ldo] fp32
-    int ldo;
-    int accumulate;               // 0: out = y, 1: out += y (residual stream)
-    float *partial;               // split-K scratch [splitk][M][N] fp32 (bf16 kernels)
+    const void *wpack;            // optional repacked copy of all segments (bf16, M <= 64): see gemm.hip
+    int pack_tiles;               //   its number of 64-row tiles
+    float *partial;               // [splitk][M][N] fp32: split s holds its share of the K sum
     int splitk;
+    float *reduced;               // if non-NULL and splitk > 1: [M][N] <- sum over splits (logits)
 };
 int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg);
+// repacked weights for the M <= 64 path
+int gemm_pack_tiles(const int *n, int nseg);
+size_t gemm_pack_bytes(const int *n, int nseg, int K);
+int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots (the splitk to use) with packed weights
+bool gemm_use_stream(int tiles);
+int gemm_stream_grid(int tiles, int K);
+int gemm_stream_slots(int tiles, int K);
+void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, hipStream_t stream);
 void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention (attention.hip)
@@ -65,17 +75,19 @@ int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int le
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- row-wise kernels (rowwise.hip)
-void launch_embed(int dtype, const void *embed, const int32_t *tokens, float *x, int M, int d,
-                  int vocab, hipStream_t stream);
-// out = x * rsqrt(mean(x^2) + eps) * gain (fp32); gain has the model's dtype
-void launch_rmsnorm(int dtype, const float *x, const void *gain, void *out, int M, int d, float eps,
-                    int row_stride_x, hipStream_t stream);
-// qkv fp32 [M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended to the cache (model dtype)
-void launch_rope_append(int dtype, const float *qkv, void *q_out, void *k_cache, void *v_cache,
-                        const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
-                        float theta, hipStream_t stream);
-// h = silu(gu[:, :f]) * gu[:, f:] (fp32)
-void launch_swiglu(int dtype, const float *gu, void *h, int M, int f, hipStream_t stream);
+// x = embed[token]; xn = rmsnorm(x) * gain
+void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
+                       int M, int d, int vocab, float eps, hipStream_t stream);
+// qkv = sum over splits of partial [S][M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended
+// to the cache (model dtype)
+void launch_reduce_rope_append(int dtype, const float *partial, int S, float *q_out, void *k_cache, void *v_cache,
+                               const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
+                               float theta, hipStream_t stream);
+// x += sum over splits of partial [S][M][d]; xn = rmsnorm(x) * gain
+void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
+                                 int M, int d, float eps, hipStream_t stream);
+// h = silu(g) * u with [g | u] = sum over splits of partial [S][M][2f]
+void launch_reduce_swiglu(const float *partial, int S, float *h, int M, int f, hipStream_t stream);
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream);
 void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B,
                      hipStream_t stream);

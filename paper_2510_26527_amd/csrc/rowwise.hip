@@ -10,61 +10,140 @@
 namespace psd {
 namespace {
 
-template <typename T>
-__global__ __launch_bounds__(256) void embed_kernel(const T *embed, const int32_t *tokens, float *x,
-                                                    int d, int vocab) {
-    const int m = blockIdx.x;
-    int tok = tokens[m];
-    tok = min(max(tok, 0), vocab - 1);
-    const T *row = embed + (size_t)tok * d;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = load_elem(row, i);
+constexpr int kRowThreads = 256;
+constexpr int kMaxV4 = 8;              // float4 per thread kept in registers: rows up to 8192 wide
+
+// fixed-order block sum: butterfly inside each wavefront, then the four totals left to right
+__device__ __forceinline__ float block_sum4(float v, float *red) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return ((red[0] + red[1]) + red[2]) + red[3];
 }
 
-// One block per row.  The sum of squares is taken in fp32 in a fixed order: per-thread strided
-// partial, butterfly inside the wavefront, then the four wavefront totals left to right.
-template <typename TW, typename TA>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const TW *gain, TA *out, int d,
-                                                      float eps, int row_stride_x) {
-    const int m = blockIdx.x, tid = threadIdx.x;
-    const float *row = x + (size_t)m * row_stride_x;
-    float ss = 0.f;
-    for (int i = tid; i < d; i += 256) { const float v = row[i]; ss += v * v; }
+__device__ __forceinline__ f32x4 load_gain4(const float *g, int i4) { return reinterpret_cast<const f32x4 *>(g)[i4]; }
+__device__ __forceinline__ f32x4 load_gain4(const uint16_t *g, int i4) {
+    const uint2 raw = reinterpret_cast<const uint2 *>(g)[i4];
+    return f32x4{bf16_bits_to_f32(raw.x & 0xffffu), __uint_as_float(raw.x & 0xffff0000u),
+                 bf16_bits_to_f32(raw.y & 0xffffu), __uint_as_float(raw.y & 0xffff0000u)};
+}
+__device__ __forceinline__ f32x4 load_row4(const float *row, int i4) { return reinterpret_cast<const f32x4 *>(row)[i4]; }
+__device__ __forceinline__ f32x4 load_row4(const uint16_t *row, int i4) { return load_gain4(row, i4); }
+
+// One block per row: x (+)= source, then xn = x * rsqrt(mean(x^2) + eps) * gain.  The source is either
+// an embedding row (EMBED) or the split-K partial sums of the projection that feeds the residual
+// stream, added in split order.  All loads of a row are issued before the first use.
+template <typename TW, bool EMBED>
+__global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *embed, const int32_t *tokens, int vocab,
+                                                                    const float *partial, int S, size_t split_stride,
+                                                                    float *x, const TW *gain, float *xn, int d, float eps) {
     __shared__ float red[4];
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    const float tot = ((red[0] + red[1]) + red[2]) + red[3];
+    const int m = blockIdx.x, tid = threadIdx.x, n4 = d >> 2;
+    f32x4 v[kMaxV4];
+    float ss = 0.f;
+    f32x4 *__restrict__ xrow = reinterpret_cast<f32x4 *>(x + (size_t)m * d);
+    const TW *erow = nullptr;
+    if constexpr (EMBED) {
+        int tok = tokens[m];
+        tok = min(max(tok, 0), vocab - 1);
+        erow = embed + (size_t)tok * d;
+    }
+    // issue every load of the row first (x or the embedding row, then the partials four splits at a
+    // time), add in split order, store afterwards
+    const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < kMaxV4; ++j) {
+        const int i4 = tid + j * kRowThreads;
+        v[j] = zero;
+        if (i4 < n4) {
+            if constexpr (EMBED) v[j] = load_row4(erow, i4);
+            else v[j] = xrow[i4];
+        }
+    }
+    if constexpr (!EMBED) {
+        const f32x4 *prow = reinterpret_cast<const f32x4 *>(partial + (size_t)m * d);
+        const size_t stride4 = split_stride >> 2;
+        int sp = 0;
+        for (; sp + 4 <= S; sp += 4) {
+            f32x4 t[4][kMaxV4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int j = 0; j < kMaxV4; ++j) {
+                    const int i4 = tid + j * kRowThreads;
+                    t[u][j] = i4 < n4 ? prow[(sp + u) * stride4 + i4] : zero;
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int j = 0; j < kMaxV4; ++j) v[j] += t[u][j];
+        }
+        for (; sp < S; ++sp) {
+#pragma unroll
+            for (int j = 0; j < kMaxV4; ++j) {
+                const int i4 = tid + j * kRowThreads;
+                if (i4 < n4) v[j] += prow[sp * stride4 + i4];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxV4; ++j) {
+        const int i4 = tid + j * kRowThreads;
+        if (i4 < n4) {
+            const f32x4 a = v[j];
+            xrow[i4] = a;
+            ss += a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
+        }
+    }
+    const float tot = block_sum4(ss, red);
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = tid; i < d; i += 256) store_elem(out, (size_t)m * d + i, row[i] * scale * load_elem(gain, i));
+    f32x4 *orow = reinterpret_cast<f32x4 *>(xn + (size_t)m * d);
+#pragma unroll
+    for (int j = 0; j < kMaxV4; ++j) {
+        const int i4 = tid + j * kRowThreads;
+        if (i4 < n4) orow[i4] = v[j] * scale * load_gain4(gain, i4);
+    }
 }
 
 // One block per (new row, head slot): slots 0..h_q-1 rotate a query head, the next h_kv rotate a
-// key head into the cache, the last h_kv copy a value head into the transposed V cache.  Thread
-// i < d_h/2 owns the rotation pair (i, i + d_h/2); the angle position * theta^(-2i/d_h) is
-// evaluated in fp64.
-template <typename TA, typename TC>
-__global__ __launch_bounds__(64) void rope_append_kernel(const float *qkv, TA *q_out, TC *k_cache, TC *v_cache,
-                                                         const int32_t *lens, int R, int h_q, int h_kv, int d_h,
-                                                         int max_len, float theta) {
+// key head into the cache, the last h_kv copy a value head into the transposed V cache.  The
+// projection arrives as split-K partials and is summed here, in split order.  Thread i < d_h/2
+// owns the rotation pair (i, i + d_h/2); the angle position * theta^(-2i/d_h) is evaluated in fp64.
+template <typename TC>
+__global__ __launch_bounds__(64) void reduce_rope_append_kernel(const float *partial, int S, size_t split_stride,
+                                                                float *q_out, TC *k_cache, TC *v_cache,
+                                                                const int32_t *lens, int R, int h_q, int h_kv, int d_h,
+                                                                int max_len, float theta) {
     const int m = blockIdx.x, slot = blockIdx.y, b = m / R, r = m % R;
     const int pos = lens[b] + r;
     if (pos >= max_len) return;            // capacity was checked on the host; never write outside
     const int half = d_h / 2;
     const int width = (h_q + 2 * h_kv) * d_h;
-    const float *src = qkv + (size_t)m * width + (size_t)slot * d_h;
+    const float *src = partial + (size_t)m * width + (size_t)slot * d_h;
     const int i = threadIdx.x;
+    auto value = [&](int e) {                  // loads four splits at a time, adds in split order
+        float a = 0.f;
+        int sp = 0;
+        for (; sp + 4 <= S; sp += 4) {
+            const float t0 = src[sp * split_stride + e], t1 = src[(sp + 1) * split_stride + e];
+            const float t2 = src[(sp + 2) * split_stride + e], t3 = src[(sp + 3) * split_stride + e];
+            a += t0; a += t1; a += t2; a += t3;
+        }
+        for (; sp < S; ++sp) a += src[sp * split_stride + e];
+        return a;
+    };
     if (slot < h_q + h_kv) {
         if (i >= half) return;
         const double inv_freq = exp2(-2.0 * (double)i / (double)d_h * log2((double)theta));
         double sn, cs;
         sincos((double)pos * inv_freq, &sn, &cs);
         const float c = (float)cs, s = (float)sn;
-        const float x1 = src[i], x2 = src[half + i];
+        const float x1 = value(i), x2 = value(half + i);
         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
         if (slot < h_q) {
-            TA *dst = q_out + ((size_t)m * h_q + slot) * d_h;
-            store_elem(dst, i, y1);
-            store_elem(dst, half + i, y2);
+            float *dst = q_out + ((size_t)m * h_q + slot) * d_h;
+            dst[i] = y1;
+            dst[half + i] = y2;
         } else {
             TC *dst = k_cache + (((size_t)b * h_kv + (slot - h_q)) * max_len + pos) * d_h;
             store_elem(dst, i, y1);
@@ -74,17 +153,27 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float *qkv, TA *q
         // V is stored transposed: v_cache[b][h][d][pos]
         const int h = slot - h_q - h_kv;
         for (int dd = i; dd < d_h; dd += 64)
-            store_elem(v_cache, (((size_t)b * h_kv + h) * d_h + dd) * max_len + pos, src[dd]);
+            store_elem(v_cache, (((size_t)b * h_kv + h) * d_h + dd) * max_len + pos, value(dd));
     }
 }
 
-template <typename TA>
-__global__ __launch_bounds__(256) void swiglu_kernel(const float *gu, TA *h, int M, int f) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)M * f) return;
-    const size_t m = idx / f, j = idx % f;
-    const float g = gu[m * 2 * f + j], u = gu[m * 2 * f + f + j];
-    store_elem(h, idx, g / (1.0f + expf(-g)) * u);
+// h = silu(g) * u, four columns per thread; [g | u] arrive as split-K partials of the gate|up projection
+__global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float *partial, int S, size_t split_stride, float *h,
+                                                            int M, int f) {
+    const size_t idx4 = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int f4 = f >> 2;
+    if (idx4 >= (size_t)M * f4) return;
+    const size_t m = idx4 / f4, j4 = idx4 % f4;
+    f32x4 g = f32x4{0.f, 0.f, 0.f, 0.f}, u = g;
+    for (int sp = 0; sp < S; ++sp) {
+        const f32x4 *row = reinterpret_cast<const f32x4 *>(partial + sp * split_stride + m * 2 * f);
+        g += row[j4];
+        u += row[f4 + j4];
+    }
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+    reinterpret_cast<f32x4 *>(h)[idx4] = o;
 }
 
 __global__ void advance_lens_kernel(int32_t *lens, int B, int delta, int max_len) {
@@ -104,39 +193,47 @@ __global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
 
 }  // namespace
 
-void launch_embed(int dtype, const void *embed, const int32_t *tokens, float *x, int M, int d, int vocab,
-                  hipStream_t stream) {
+void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
+                       int M, int d, int vocab, float eps, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_EMBED, stream);
-    if (dtype == PSD_BF16) embed_kernel<uint16_t><<<M, 256, 0, stream>>>((const uint16_t *)embed, tokens, x, d, vocab);
-    else embed_kernel<float><<<M, 256, 0, stream>>>((const float *)embed, tokens, x, d, vocab);
+    if (dtype == PSD_BF16)
+        residual_norm_kernel<uint16_t, true><<<M, kRowThreads, 0, stream>>>((const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
+                                                                           x, (const uint16_t *)gain, xn, d, eps);
+    else
+        residual_norm_kernel<float, true><<<M, kRowThreads, 0, stream>>>((const float *)embed, tokens, vocab, nullptr, 0, 0, x,
+                                                                        (const float *)gain, xn, d, eps);
 }
 
-void launch_rmsnorm(int dtype, const float *x, const void *gain, void *out, int M, int d, float eps,
-                    int row_stride_x, hipStream_t stream) {
+void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
+                                 int M, int d, float eps, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_RMSNORM, stream);
+    const size_t stride = (size_t)M * d;
     if (dtype == PSD_BF16)
-        rmsnorm_kernel<uint16_t, float><<<M, 256, 0, stream>>>(x, (const uint16_t *)gain, (float *)out, d, eps, row_stride_x);
+        residual_norm_kernel<uint16_t, false><<<M, kRowThreads, 0, stream>>>(nullptr, nullptr, 0, partial, S, stride, x,
+                                                                            (const uint16_t *)gain, xn, d, eps);
     else
-        rmsnorm_kernel<float, float><<<M, 256, 0, stream>>>(x, (const float *)gain, (float *)out, d, eps, row_stride_x);
+        residual_norm_kernel<float, false><<<M, kRowThreads, 0, stream>>>(nullptr, nullptr, 0, partial, S, stride, x,
+                                                                         (const float *)gain, xn, d, eps);
 }
 
-void launch_rope_append(int dtype, const float *qkv, void *q_out, void *k_cache, void *v_cache,
-                        const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
-                        float theta, hipStream_t stream) {
+void launch_reduce_rope_append(int dtype, const float *partial, int S, float *q_out, void *k_cache, void *v_cache,
+                               const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
+                               float theta, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_ROPE_APPEND, stream);
+    const size_t stride = (size_t)B * R * (h_q + 2 * h_kv) * d_h;
+    const dim3 grid(B * R, h_q + 2 * h_kv);
     if (dtype == PSD_BF16)
-        rope_append_kernel<float, uint16_t><<<dim3(B * R, h_q + 2 * h_kv), 64, 0, stream>>>(qkv, (float *)q_out, (uint16_t *)k_cache,
-                                                                      (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
+        reduce_rope_append_kernel<uint16_t><<<grid, 64, 0, stream>>>(partial, S, stride, q_out, (uint16_t *)k_cache,
+                                                                     (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
     else
-        rope_append_kernel<float, float><<<dim3(B * R, h_q + 2 * h_kv), 64, 0, stream>>>(qkv, (float *)q_out, (float *)k_cache, (float *)v_cache,
-                                                                   lens, R, h_q, h_kv, d_h, max_len, theta);
+        reduce_rope_append_kernel<float><<<grid, 64, 0, stream>>>(partial, S, stride, q_out, (float *)k_cache, (float *)v_cache,
+                                                                  lens, R, h_q, h_kv, d_h, max_len, theta);
 }
 
-void launch_swiglu(int dtype, const float *gu, void *h, int M, int f, hipStream_t stream) {
+void launch_reduce_swiglu(const float *partial, int S, float *h, int M, int f, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_SWIGLU, stream);
-    const unsigned blocks = (unsigned)(((size_t)M * f + 255) / 256);
-    (void)dtype;
-    swiglu_kernel<float><<<blocks, 256, 0, stream>>>(gu, (float *)h, M, f);
+    const unsigned blocks = (unsigned)(((size_t)M * (f / 4) + 255) / 256);
+    reduce_swiglu_kernel<<<blocks, 256, 0, stream>>>(partial, S, (size_t)M * 2 * f, h, M, f);
 }
 
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream) {

@@ -34,6 +34,17 @@ class Model:
         ptrs = [self.weights[n].data_ptr() for n in weight_order(shape.n_layers)]
         self.handle = psd.psd_model_create(self.desc, ptrs)
         self._ws = None
+        self.packed = None
+
+    def pack(self):
+        """Build the streaming copy of the projection weights (bf16 models) for steps of <= 64 rows."""
+        need = psd.psd_model_packed_bytes(self.handle)
+        if need == 0:
+            return self
+        self.packed = torch.empty(need, dtype=torch.uint8, device=self.device)
+        psd.psd_model_pack(self.handle, self.packed)
+        self._ws = None
+        return self
 
     def workspace(self, batch, n_new, max_len):
         need = psd.psd_model_workspace_bytes(self.handle, batch, n_new, max_len)

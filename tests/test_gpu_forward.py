@@ -43,10 +43,12 @@ class Pair:
     """The same model, cache contents and lengths on both sides."""
 
     def __init__(self, shape, dtype, batch, max_len, seed=0, ctx=None, lens=None, std=0.02, oracle_kv_dtype=np.float64,
-                 oracle_rows=None):
+                 oracle_rows=None, pack=False):
         self.shape, self.dtype, self.batch = shape, dtype, batch
         self.w = synth.make_weights(shape, seed, dtype, std=std)
         self.model = runtime.Model(shape, self.w)
+        if pack:
+            self.model.pack()
         self.kv = runtime.KVCache(self.model, batch, max_len, fill_garbage=True)
         self.cfg = ofwd.ModelConfig(**shape.asdict())
         self.rows = list(range(batch)) if oracle_rows is None else oracle_rows   # sequences the oracle follows
@@ -123,12 +125,14 @@ SMALL_G7 = synth.Shape(1, 896, 7, 1, 128, 1152, 2048, 1.0e6)          # Qwen2-li
     (SMALL_MHA, 8, 1024), (SMALL_MHA, 11, 77), (SMALL_MHA, 70, 200), (SMALL_MHA, 130, 0),
     (SMALL_G7, 16, 520), (SMALL_G7, 17, 4096), (SMALL_G7, 3, 5),
 ])
-def test_bf16_small_models(shape, n_new, ctx):
-    """Covers the skinny GEMM at 1-3 row tiles, the tiled GEMM (70, 130 rows), ragged N and M,
+@pytest.mark.parametrize("pack", [False, True], ids=["rowmajor", "packed"])
+def test_bf16_small_models(shape, n_new, ctx, pack):
+    """Both weight layouts of the M <= 64 path (row-major split-K kernel, packed stream-K kernel).
+    Covers the skinny GEMM at 1-3 row tiles, the tiled GEMM (70, 130 rows), ragged N and M,
     attention with 1, 2 and 4 query tiles, several query chunks (7 x 17 rows), split counts from
     1 to 17 and a prefill with an empty cache.  std 0.05 keeps the signal above bf16 noise."""
     max_len = (ctx + n_new + 70 + 63) // 64 * 64
-    p = Pair(shape, torch.bfloat16, 1, max_len, seed=n_new, ctx=ctx or None, std=0.05)
+    p = Pair(shape, torch.bfloat16, 1, max_len, seed=n_new, ctx=ctx or None, std=0.05, pack=pack)
     toks = synth.make_tokens(shape.vocab, (1, n_new + 6), n_new + ctx)
     e1 = p.step(toks[:, :n_new], what="first step")
     e2 = p.step(toks[:, n_new:], n_logit_rows=4, what="second step, last 4 rows")
@@ -138,7 +142,7 @@ def test_bf16_small_models(shape, n_new, ctx):
 
 def test_bf16_batch_ragged_lengths_truncate():
     shape = SMALL_GQA
-    p = Pair(shape, torch.bfloat16, 4, 640, seed=21, ctx=512, lens=[512, 100, 333, 1], std=0.05)
+    p = Pair(shape, torch.bfloat16, 4, 640, seed=21, ctx=512, lens=[512, 100, 333, 1], std=0.05, pack=True)
     toks = synth.make_tokens(shape.vocab, (4, 33), 2)
     p.step(toks[:, :16], what="16 rows x 4 sequences")
     base = torch.tensor([512, 100, 333, 1], dtype=torch.int32, device="cuda")
@@ -154,7 +158,7 @@ def test_bf16_batch_ragged_lengths_truncate():
 def test_forward_is_deterministic():
     shape = SMALL_MHA
     w = synth.make_weights(shape, 3, torch.bfloat16, std=0.05)
-    model = runtime.Model(shape, w)
+    model = runtime.Model(shape, w).pack()
     toks = torch.from_numpy(synth.make_tokens(shape.vocab, (2, 9), 1)).cuda()
     outs = []
     for _ in range(3):
@@ -184,7 +188,7 @@ def test_workload3_llama2_7b_full_size():
     Then the 9-row variant after a rollback to 1024 + 3 accepted."""
     shape = synth.LLAMA2_7B
     _progress("w3: generating 7B weights")
-    p = Pair(shape, torch.bfloat16, 1, 1088, seed=3, ctx=1024, oracle_kv_dtype=np.float32)
+    p = Pair(shape, torch.bfloat16, 1, 1088, seed=3, ctx=1024, oracle_kv_dtype=np.float32, pack=True)
     toks = synth.make_tokens(shape.vocab, (1, 17), 33)
     _progress("w3: forward 8 rows, both sides")
     e1 = p.step(toks[:, :8], what="8 rows")
