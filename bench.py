@@ -29,6 +29,19 @@ def weight_stream_bytes(shape):
     return 2 * (s.n_layers * per_layer + s.vocab * s.d_model)
 
 
+def measured_traffic_bytes():
+    """HBM bytes per launch of the M <= 64 GEMM kernels as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE (the committed summary under profiles/ records the commands); None if it is not there."""
+    path = os.path.join(ROOT, "profiles", "bench_verify_step_llama2_7b_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_MB_PER_LAUNCH gemm_m_le_64"):
+                return float(line.split("=")[1]) * 1e6
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,6 +49,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--accept-iters", type=int, default=60)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run ten plain 1 GiB device-to-device copies (a kernel of known traffic, for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
@@ -53,6 +69,14 @@ def main():
         raise SystemExit("bench.py needs the GPU: no CPU fallback exists")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": "10 x copy of 1 GiB (reads 1 GiB, writes 1 GiB each)"}))
+        return
 
     shape, gamma, ctx, max_len, temperature = synth.LLAMA2_7B, 8, 1024, 1088, 1.0
     w_cpu = synth.make_weights(shape, 3, torch.bfloat16)
@@ -107,7 +131,7 @@ def main():
     w_bytes = weight_stream_bytes(shape)
     achieved = w_bytes * prof_steps / (sk_ms * 1e-3) / 1e9
     roofline = {"kernel": "gemm_bf16_stream_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
                 "bytes_per_launch": w_bytes * prof_steps / sk_n, "avg_launch_us": 1e3 * sk_ms / sk_n,
                 "launches_per_step": sk_n / prof_steps}
     kv_bytes = 2 * shape.n_layers * shape.n_kv_heads * (ctx + gamma) * shape.d_head * 2
