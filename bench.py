@@ -152,7 +152,7 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     call_us = e0.elapsed_time(e1) * 1e3 / args.accept_iters
-    psd.psd_profile_enable(3 * args.accept_iters)
+    psd.psd_profile_enable(4 * args.accept_iters)
     for i in range(args.accept_iters):
         s = sets[i % len(sets)]
         acc2(s["p"], s["q"], s["tokens"], s["uniforms"], 1.0)
@@ -165,7 +165,8 @@ def main():
               "frac_of_hbm_peak": a_bytes / call_us / 1e3 / HBM_PEAK_GBS,
               "stats_kernel_us": stats_us, "stats_kernel_GB/s": a_bytes / stats_us / 1e3,
               "emit_z_kernel_us": 1e3 * aprof["accept_emit_z"][0] / aprof["accept_emit_z"][1],
-              "emit_r_kernel_us": 1e3 * aprof["accept_emit_r"][0] / aprof["accept_emit_r"][1]}
+              "emit_r_kernel_us": 1e3 * aprof["accept_emit_r"][0] / aprof["accept_emit_r"][1],
+              "locate_kernel_us": 1e3 * aprof["accept_locate"][0] / aprof["accept_locate"][1]}
 
     # ---- the oracle on the host cores, one whole step of the same workload
     cpu_baseline = None

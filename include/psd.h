@@ -177,8 +177,9 @@ psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32
 psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 
 /* ---- measurement aid (not part of the decoding path) -------------------------------------
- * Per-kernel timing with HIP events recorded on the launch stream, so that a bench can state
- * each kernel's average duration against its roofline.  psd_profile_enable(n > 0) creates
+ * Per-kernel timing with a start and a stop HIP event attached to each kernel dispatch (they
+ * time the kernel itself, on the stream it is launched on), so that a bench can state each
+ * kernel's average duration against its roofline.  psd_profile_enable(n > 0) creates
  * event pairs for up to n launches and starts recording; psd_profile_enable(0) stops and
  * frees them.  psd_profile_collect waits for the recorded work, adds each launch's elapsed
  * milliseconds into ms_by_kind[kind] and counts it in launches_by_kind[kind] (host arrays of
@@ -198,7 +199,8 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_ACCEPT_STATS 11
 #define PSD_KIND_ACCEPT_EMIT_Z 12
 #define PSD_KIND_ACCEPT_EMIT_R 13
-#define PSD_KIND_COUNT 14
+#define PSD_KIND_ACCEPT_LOCATE 14
+#define PSD_KIND_COUNT 15
 psd_status psd_profile_enable(int32_t max_launches);
 psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind);
 

@@ -1,7 +1,8 @@
 // Speculative-sampling acceptance on gfx950 (the VERIFY loop of Algorithm 1 and the residual
 // draw that keeps the verifier's distribution, Sec. 3.1).
 //
-// Three launches per call, no host round trip:
+// Four launches per call, no host round trip (kernel boundaries are the cross-block
+// synchronisation: device-scope fences plus a last-block counter measured several times slower):
 //   1. accept_stats_kernel  one pass over every logits row of p and q (the HBM-bound part):
 //      per (row, chunk) the max raw logit and sum exp((l - max)/T), fp32, wavefront
 //      reductions, 8 x 16-byte loads in flight per lane.
@@ -9,8 +10,9 @@
 //      the statistics (ratio test against the supplied uniforms, prefix scan over <= 64
 //      flags) and accumulates, in fp64, the softmax denominators of the ONE position the
 //      draw needs.
-//   3. accept_emit_r_kernel fp64 residual mass per chunk; the last block to arrive for a
-//      sequence locates the inverse-CDF crossing (chunk, then element) in index order.
+//   3. accept_emit_r_kernel fp64 residual mass per chunk.
+//   4. accept_locate_kernel one block per sequence locates the inverse-CDF crossing (chunk, then
+//      element) in index order.
 // All sums are taken in a fixed order, so results do not depend on block scheduling.
 #include "common.h"
 #include "kernels.h"
@@ -25,11 +27,37 @@ constexpr int kThreads = 256;
 constexpr int kLoadsPerLane = 8;
 constexpr double kTieEps = 1e-5;
 constexpr int kMaxChunksE = 1024;     // draw-pass chunks per logits row (LDS table of the locating block)
+constexpr int kMaxChunkE = 8192;      // elements per draw-pass chunk
+constexpr int kMaxPer = kMaxChunkE / 256;   // elements per thread of the locating block
 
 template <typename T>
 __device__ __forceinline__ const T *logits_row(const AcceptArgs &a, int b, bool is_q, int j) {
     const T *base = is_q ? (const T *)a.q + (int64_t)b * a.q_stride : (const T *)a.p + (int64_t)b * a.p_stride;
     return base + (int64_t)j * a.V;
+}
+
+// exp(x) for x <= 0 in fp64, a few ulp: x = k ln2 + r with |r| <= ln2/2, degree-13 Taylor polynomial
+// of exp(r) evaluated pairwise (short dependency chains), scaled by 2^k.  The draw only needs both
+// sides to agree to ~1e-15 relative, which leaves the flip probability at V * 1e-15.
+__device__ __forceinline__ double exp_nonpos(double x) {
+    if (!(x > -745.0)) return 0.0;
+    const double kf = rint(x * 1.4426950408889634074);
+    double r = fma(-kf, 6.93147180369123816490e-01, x);
+    r = fma(-kf, 1.90821492927058770002e-10, r);
+    const double r2 = r * r, r4 = r2 * r2, r8 = r4 * r4;
+    const double p01 = 1.0 + r;
+    const double p23 = fma(r, 1.0 / 6.0, 0.5);
+    const double p45 = fma(r, 1.0 / 120.0, 1.0 / 24.0);
+    const double p67 = fma(r, 1.0 / 5040.0, 1.0 / 720.0);
+    const double p89 = fma(r, 1.0 / 362880.0, 1.0 / 40320.0);
+    const double pab = fma(r, 1.0 / 39916800.0, 1.0 / 3628800.0);
+    const double pcd = fma(r, 1.0 / 6227020800.0, 1.0 / 479001600.0);
+    const double q0 = fma(r2, p23, p01);          // degree 0..3
+    const double q1 = fma(r2, p67, p45);          // degree 4..7 (times r^4)
+    const double q2 = fma(r2, pab, p89);          // degree 8..11 (times r^8)
+    const double lo = fma(r4, q1, q0);
+    const double hi = fma(r4, pcd, q2);           // degree 8..13 (times r^8)
+    return ldexp(fma(r8, hi, lo), (int)kf);
 }
 
 // block-wide fixed-order sum of one double per thread; result valid in every thread
@@ -56,36 +84,34 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(AcceptArgs a) {
     const int e0 = c * a.chunkA;
     const int e1 = min(a.V, e0 + a.chunkA);
 
-    float v[kLoadsPerLane][EPL];
+    // keep the loaded 16-byte vectors as they are (32 registers) and unpack them twice, once for
+    // the max and once for the exponentials: the small footprint keeps 8 blocks resident per CU
+    u32x4 raw[kLoadsPerLane];
+    float sc[kLoadsPerLane];               // scalar path
+    bool have[kLoadsPerLane];
 #pragma unroll
     for (int i = 0; i < kLoadsPerLane; ++i) {
         const int idx = e0 + (i * kThreads + tid) * EPL;
+        have[i] = idx < e1;                // chunk bounds and V are multiples of EPL: a vector load is whole
         if constexpr (VEC) {
-            if (idx < e1) {   // chunk bounds and V are multiples of EPL: the load is whole
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(row + idx);
-                if constexpr (sizeof(T) == 2) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[i][2 * e] = bf16_bits_to_f32(raw[e] & 0xffffu);
-                        v[i][2 * e + 1] = __uint_as_float(raw[e] & 0xffff0000u);
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[i][e] = __uint_as_float(raw[e]);
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) v[i][e] = -INFINITY;
-            }
+            raw[i] = have[i] ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + idx)) : u32x4{0u, 0u, 0u, 0u};
         } else {
-            v[i][0] = idx < e1 ? load_elem(row, idx) : -INFINITY;
+            sc[i] = have[i] ? load_elem(row, idx) : -INFINITY;
         }
     }
+    auto elem = [&](int i, int e) -> float {
+        if constexpr (!VEC) return sc[i];
+        else if constexpr (sizeof(T) == 2)
+            return (e & 1) ? __uint_as_float(raw[i][e >> 1] & 0xffff0000u) : __uint_as_float(raw[i][e >> 1] << 16);
+        else return __uint_as_float(raw[i][e]);
+    };
     float m = -INFINITY;
 #pragma unroll
     for (int i = 0; i < kLoadsPerLane; ++i)
+        if (have[i]) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) m = fmaxf(m, v[i][e]);
+            for (int e = 0; e < EPL; ++e) m = fmaxf(m, elem(i, e));
+        }
     __shared__ float sm[kThreads / 64];
     __shared__ float ss[kThreads / 64];
     m = wave_max(m);
@@ -97,8 +123,10 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(AcceptArgs a) {
         const float k2 = 1.4426950408889634f / a.temperature;
 #pragma unroll
         for (int i = 0; i < kLoadsPerLane; ++i)
+            if (have[i]) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) s += __builtin_amdgcn_exp2f((v[i][e] - m) * k2);
+                for (int e = 0; e < EPL; ++e) s += __builtin_amdgcn_exp2f((elem(i, e) - m) * k2);
+            }
     }
     s = wave_sum(s);
     if ((tid & 63) == 0) ss[tid >> 6] = s;
@@ -180,7 +208,6 @@ __global__ __launch_bounds__(kThreads) void accept_emit_z_kernel(AcceptArgs a) {
     if (c == 0 && tid == 0) {
         a.out_n[b] = n;
         a.flags[b] = flags;
-        a.counters[b] = 0;
         if (d.p_row < 0) a.out_tok[b] = -1;
     }
     if (d.p_row < 0) return;
@@ -189,14 +216,23 @@ __global__ __launch_bounds__(kThreads) void accept_emit_z_kernel(AcceptArgs a) {
     combine_stats(a, b, d.p_row, &Mp, &Z_unused);
     if (d.have_q) combine_stats(a, b, a.n_p_rows + n, &Mq, &Z_unused);
     const double temp = (double)a.temperature;
-    const double mp = (double)Mp / temp, mq = (double)Mq / temp;
+    const double mp = (double)Mp * (1.0 / temp), mq = (double)Mq * (1.0 / temp);
     const T *prow = logits_row<T>(a, b, false, d.p_row);
     const T *qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
     const int e0 = c * a.chunkE, e1 = min(a.V, e0 + a.chunkE);
+    const double inv_t = 1.0 / temp;
     double sa = 0.0, sb = 0.0;
-    for (int i = e0 + tid; i < e1; i += kThreads) {
-        sa += exp((double)load_elem(prow, i) / temp - mp);
-        if (d.have_q) sb += exp((double)load_elem(qrow, i) / temp - mq);
+    for (int i0 = e0 + tid; i0 < e1; i0 += 4 * kThreads) {
+        double ea[4], eb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {          // four independent elements in flight per thread
+            const int i = i0 + u * kThreads;
+            const bool in = i < e1;
+            ea[u] = in ? exp_nonpos(fma((double)load_elem(prow, in ? i : e0), inv_t, -mp)) : 0.0;
+            eb[u] = (in && d.have_q) ? exp_nonpos(fma((double)load_elem(qrow, in ? i : e0), inv_t, -mq)) : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { sa += ea[u]; sb += eb[u]; }
     }
     sa = block_sum(sa, s_red);
     sb = block_sum(sb, s_red);
@@ -207,12 +243,12 @@ __global__ __launch_bounds__(kThreads) void accept_emit_z_kernel(AcceptArgs a) {
 template <typename T>
 struct DrawWeights {
     const T *prow, *qrow;
-    double T_, mp, mq, inv_zp, inv_zq;
+    double inv_t, mp, mq, inv_zp, inv_zq;
     bool have_q;
     __device__ __forceinline__ double operator()(int i) const {
-        const double pi = exp((double)load_elem(prow, i) / T_ - mp) * inv_zp;
+        const double pi = exp_nonpos(fma((double)load_elem(prow, i), inv_t, -mp)) * inv_zp;
         if (!have_q) return pi;
-        const double qi = exp((double)load_elem(qrow, i) / T_ - mq) * inv_zq;
+        const double qi = exp_nonpos(fma((double)load_elem(qrow, i), inv_t, -mq)) * inv_zq;
         const double r = pi - qi;
         return r > 0.0 ? r : 0.0;
     }
@@ -221,10 +257,6 @@ struct DrawWeights {
 template <typename T>
 __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
     __shared__ double s_red[kThreads / 64];
-    __shared__ double s_scan[kThreads / 64];
-    __shared__ double s_w[kMaxChunksE];          // per-chunk weights of this sequence (last block only)
-    __shared__ int s_last, s_cstar, s_best, s_lastpos;
-    __shared__ double s_base, s_t;
     const int b = blockIdx.x / a.n_chunksE, c = blockIdx.x % a.n_chunksE, tid = threadIdx.x;
     const int n = a.out_n[b];
     const DrawRows d = draw_rows(a, n);
@@ -242,29 +274,64 @@ __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
     DrawWeights<T> w;
     w.prow = logits_row<T>(a, b, false, d.p_row);
     w.qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
-    w.T_ = (double)a.temperature;
-    w.mp = (double)Mp / w.T_;
-    w.mq = (double)Mq / w.T_;
+    w.inv_t = 1.0 / (double)a.temperature;
+    w.mp = (double)Mp * w.inv_t;
+    w.mq = (double)Mq * w.inv_t;
     w.inv_zp = 1.0 / za;
     w.inv_zq = d.have_q ? 1.0 / zb : 0.0;
     w.have_q = d.have_q;
 
     const int e0 = c * a.chunkE, e1 = min(a.V, e0 + a.chunkE);
     double rs = 0.0;
-    for (int i = e0 + tid; i < e1; i += kThreads) rs += w(i);
-    rs = block_sum(rs, s_red);
-    if (tid == 0) {
-        a.rpart[(size_t)b * nE + c] = rs;
-        __threadfence();
-        const uint32_t old = __hip_atomic_fetch_add(&a.counters[b], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (old == (uint32_t)nE - 1u) ? 1 : 0;
+    for (int i0 = e0 + tid; i0 < e1; i0 += 4 * kThreads) {
+        double t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kThreads;
+            t[u] = i < e1 ? w(i) : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rs += t[u];
     }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
+    rs = block_sum(rs, s_red);
+    if (tid == 0) a.rpart[(size_t)b * nE + c] = rs;
+}
+
+// One block per sequence: locate the inverse-CDF crossing of u * mass, first among the chunk sums
+// (index order), then among the elements of that chunk.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void accept_locate_kernel(AcceptArgs a) {
+    __shared__ double s_red[kThreads / 64];
+    __shared__ double s_scan[kThreads / 64];
+    __shared__ double s_w[kMaxChunksE];          // per-chunk weights of this sequence
+    __shared__ int s_cstar, s_best, s_lastpos;
+    __shared__ double s_base, s_t;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n = a.out_n[b];
+    const DrawRows d = draw_rows(a, n);
+    if (d.p_row < 0) return;
+    const int nE = a.n_chunksE;
+    const double2 *zp = a.zpart + (size_t)b * nE;
+    double za = 0.0, zb = 0.0;
+    for (int k = tid; k < nE; k += kThreads) { za += zp[k].x; zb += zp[k].y; }
+    za = block_sum(za, s_red);
+    zb = block_sum(zb, s_red);
+    float Mp, Mq = 0.f;
+    double Z_unused;
+    combine_stats(a, b, d.p_row, &Mp, &Z_unused);
+    if (d.have_q) combine_stats(a, b, a.n_p_rows + n, &Mq, &Z_unused);
+    DrawWeights<T> w;
+    w.prow = logits_row<T>(a, b, false, d.p_row);
+    w.qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
+    w.inv_t = 1.0 / (double)a.temperature;
+    w.mp = (double)Mp * w.inv_t;
+    w.mq = (double)Mq * w.inv_t;
+    w.inv_zp = 1.0 / za;
+    w.inv_zq = d.have_q ? 1.0 / zb : 0.0;
+    w.have_q = d.have_q;
 
     // ---- last block of this sequence: locate the crossing of u * mass in index order
-    const volatile double *rp = a.rpart + (size_t)b * nE;
+    const double *rp = a.rpart + (size_t)b * nE;
     double mass = 0.0;
     for (int k = tid; k < nE; k += kThreads) {
         const double wk = rp[k];
@@ -306,10 +373,16 @@ __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
     const int cs = s_cstar;
     const double t = s_t;
     const int f0 = cs * a.chunkE, f1 = min(a.V, f0 + a.chunkE);
-    const int per = (f1 - f0 + kThreads - 1) / kThreads;       // consecutive elements per thread
+    const int per = (f1 - f0 + kThreads - 1) / kThreads;       // consecutive elements per thread (<= kMaxPer)
     const int i0 = min(f1, f0 + tid * per), i1 = min(f1, i0 + per);
+    double wv[kMaxPer];
     double local = 0.0;
-    for (int i = i0; i < i1; ++i) local += w(i);
+#pragma unroll
+    for (int j = 0; j < kMaxPer; ++j) {
+        wv[j] = (j < per && i0 + j < i1) ? w(i0 + j) : 0.0;
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxPer; ++j) local += wv[j];
     // exclusive prefix of `local` over threads, in thread order
     double incl = local;
 #pragma unroll
@@ -320,14 +393,16 @@ __global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
     if ((tid & 63) == 63) s_scan[tid >> 6] = incl;
     __syncthreads();
     double run = s_base;
-    for (int wv = 0; wv < (tid >> 6); ++wv) run += s_scan[wv];
+    for (int wvi = 0; wvi < (tid >> 6); ++wvi) run += s_scan[wvi];
     run += incl - local;
     int found = 0x7fffffff, lastpos = -1;
-    for (int i = i0; i < i1; ++i) {
-        const double wi = w(i);
-        if (wi > 0.0) lastpos = i;
-        run += wi;
-        if (run > t && found == 0x7fffffff) found = i;
+#pragma unroll
+    for (int j = 0; j < kMaxPer; ++j) {
+        if (i0 + j < i1) {
+            if (wv[j] > 0.0) lastpos = i0 + j;
+            run += wv[j];
+            if (run > t && found == 0x7fffffff) found = i0 + j;
+        }
     }
     if (found != 0x7fffffff) atomicMin(&s_best, found);
     if (lastpos >= 0) atomicMax(&s_lastpos, lastpos);
@@ -352,7 +427,7 @@ void accept_plan(int rows, int gamma, int n_p_rows, int V, int dtype, bool vec, 
     a->n_chunksA = (V + a->chunkA - 1) / a->chunkA;
     long want = ((long)V * (rows > 0 ? rows : 1) + 1023) / 1024;
     int ce = round_up((int)(want < 512 ? 512 : (want > 8192 ? 8192 : want)), 256);
-    while ((V + ce - 1) / ce > kMaxChunksE) ce *= 2;           // very large vocabularies: fewer, larger chunks
+    if ((V + ce - 1) / ce > kMaxChunksE) ce = kMaxChunkE;
     a->chunkE = ce;
     a->n_chunksE = (V + ce - 1) / ce;
 }
@@ -386,17 +461,21 @@ static void launch_accept_t(const AcceptArgs &a, bool vec_ok, hipStream_t stream
     if (vecs > 0) {
         dim3 grid((unsigned)vecs * a.n_chunksA);
         ScopedProf sp(PSD_KIND_ACCEPT_STATS, stream);
-        if (vec_ok) accept_stats_kernel<T, true><<<grid, kThreads, 0, stream>>>(a);
-        else accept_stats_kernel<T, false><<<grid, kThreads, 0, stream>>>(a);
+        if (vec_ok) launch_kernel(accept_stats_kernel<T, true>, grid, kThreads, 0, stream, a);
+        else launch_kernel(accept_stats_kernel<T, false>, grid, kThreads, 0, stream, a);
     }
     dim3 gridE((unsigned)a.rows * a.n_chunksE);
     {
         ScopedProf sp(PSD_KIND_ACCEPT_EMIT_Z, stream);
-        accept_emit_z_kernel<T><<<gridE, kThreads, 0, stream>>>(a);
+        launch_kernel(accept_emit_z_kernel<T>, gridE, kThreads, 0, stream, a);
     }
     {
         ScopedProf sp(PSD_KIND_ACCEPT_EMIT_R, stream);
-        accept_emit_r_kernel<T><<<gridE, kThreads, 0, stream>>>(a);
+        launch_kernel(accept_emit_r_kernel<T>, gridE, kThreads, 0, stream, a);
+    }
+    {
+        ScopedProf sp(PSD_KIND_ACCEPT_LOCATE, stream);
+        launch_kernel(accept_locate_kernel<T>, a.rows, kThreads, 0, stream, a);
     }
 }
 

@@ -18,22 +18,19 @@ struct Recorder {
     std::vector<hipEvent_t> ev;      // 2 per launch
     std::vector<int> kind;
     size_t used = 0, cap = 0;
-    bool open = false;
 } g_rec;
 }  // namespace
 
 namespace psd {
-void prof_begin(int kind, hipStream_t stream) {
-    if (!g_rec.on || g_rec.used >= g_rec.cap) return;
-    g_rec.kind[g_rec.used] = kind;
-    (void)hipEventRecord(g_rec.ev[2 * g_rec.used], stream);
-    g_rec.open = true;
-}
-void prof_end(hipStream_t stream) {
-    if (!g_rec.open) return;
-    (void)hipEventRecord(g_rec.ev[2 * g_rec.used + 1], stream);
+static thread_local int g_kind = -1;
+void prof_set_kind(int kind) { g_kind = kind; }
+bool prof_acquire(hipEvent_t *start, hipEvent_t *stop) {
+    if (!g_rec.on || g_rec.used >= g_rec.cap || g_kind < 0) return false;
+    g_rec.kind[g_rec.used] = g_kind;
+    *start = g_rec.ev[2 * g_rec.used];
+    *stop = g_rec.ev[2 * g_rec.used + 1];
     ++g_rec.used;
-    g_rec.open = false;
+    return true;
 }
 }  // namespace psd
 
@@ -381,7 +378,7 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
                            int64_t q_seq_stride, int32_t *out_flags, void *workspace, size_t ws_bytes,
                            void *hip_stream) {
     if (dtype != PSD_F32 && dtype != PSD_BF16) return PSD_ERR_DTYPE;
-    if (rows < 0 || gamma < 0 || gamma > 64 || vocab <= 0) return PSD_ERR_SHAPE;
+    if (rows < 0 || gamma < 0 || gamma > 64 || vocab <= 0 || vocab > (1 << 23)) return PSD_ERR_SHAPE;
     if (n_p_rows != gamma && n_p_rows != gamma + 1) return PSD_ERR_SHAPE;
     if (gamma == 0 && n_p_rows == 0) return PSD_ERR_SHAPE;
     if ((long)rows * (n_p_rows + gamma) > (1L << 24)) return PSD_ERR_SHAPE;
@@ -419,7 +416,7 @@ psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32
 psd_status psd_profile_enable(int32_t max_launches) {
     for (hipEvent_t e : g_rec.ev) (void)hipEventDestroy(e);
     g_rec.ev.clear(); g_rec.kind.clear();
-    g_rec.used = g_rec.cap = 0; g_rec.on = false; g_rec.open = false;
+    g_rec.used = g_rec.cap = 0; g_rec.on = false;
     if (max_launches < 0) return PSD_ERR_SHAPE;
     if (max_launches == 0) return PSD_OK;
     g_rec.ev.resize(2 * (size_t)max_launches);

@@ -113,34 +113,42 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
     }
 
     for (int kt = kb0 + wave * kKeysPerWaveIter; kt < kb1; kt += kKeysPerBlockIter) {
+        // issue every K and V^T load of this 64-key tile before the first MFMA (two 32-key halves)
+        bf16x8 ka[2][2][KS];
+        bf16x8 va[2][DT];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
-            const int kb = kt + sub * 32;
-            if (kb >= kb1) break;
+            // a half that starts at or beyond kb1 is fully masked; clamp its address into the tile's first half
+            const int kb = (kt + sub * 32 < kb1) ? kt + sub * 32 : kt;
             // K rows of the two 16-key score tiles: row i of tile t is key kb + 8*(i/4) + 4*t + i%4
-            bf16x8 ka[2][KS];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int key = kb + 8 * (i >> 2) + 4 * t + (i & 3);     // < max_len: kb + 32 <= max_len
                 const uint16_t *kp = Kc + (size_t)key * DH + g * (DH / 4);
 #pragma unroll
-                for (int s = 0; s < KS; ++s) ka[t][s] = *reinterpret_cast<const bf16x8 *>(kp + 8 * s);
+                for (int s = 0; s < KS; ++s) ka[sub][t][s] = *reinterpret_cast<const bf16x8 *>(kp + 8 * s);
             }
             // V^T rows d = dt*16 + i, keys kb + 8g .. kb + 8g + 7
-            bf16x8 va[DT];
-            const bool tail = kb + 32 > n_keys;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + (size_t)(dt * 16 + i) * max_len + kb + 8 * g);
-                if (tail) {          // stale cache rows may hold anything, even NaN: zero them
+            for (int dt = 0; dt < DT; ++dt)
+                va[sub][dt] = *reinterpret_cast<const bf16x8 *>(Vt + (size_t)(dt * 16 + i) * max_len + kb + 8 * g);
+        }
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int kb = kt + sub * 32;
+            if (kb >= kb1) break;
+            if (kb + 32 > n_keys) {          // stale cache rows may hold anything, even NaN: zero them
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    u32x4 raw = __builtin_bit_cast(u32x4, va[sub][dt]);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int key = kb + 8 * g + 2 * e;
                         if (key >= n_keys) raw[e] = 0u;
                         else if (key + 1 >= n_keys) raw[e] &= 0xffffu;
                     }
+                    va[sub][dt] = __builtin_bit_cast(bf16x8, raw);
                 }
-                va[dt] = __builtin_bit_cast(bf16x8, raw);
             }
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
@@ -150,8 +158,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                     c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s = 0; s < KS; ++s) {
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[t], 0, 0, 0);
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[t], 0, 0, 0);
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], qh[qt][s], c[t], 0, 0, 0);
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], ql[qt][s], c[t], 0, 0, 0);
                     }
                 }
                 // lane (query column i, group g): c[t][v] is key kb + 8g + 4t + v
@@ -190,8 +198,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                 for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph, o[qt][dt], 0, 0, 0);
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl, o[qt][dt], 0, 0, 0);
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], ph, o[qt][dt], 0, 0, 0);
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], pl, o[qt][dt], 0, 0, 0);
                 }
             }
         }
@@ -298,13 +306,13 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     dim3 grid(a.splits, chunks, a.B * a.h_kv);
     {
     ScopedProf sp(PSD_KIND_ATTN, stream);
-    if (QT == 1) attn_mfma_kernel<DH, 1><<<grid, 256, 0, stream>>>(a, scale_log2, range);
-    else if (QT == 2) attn_mfma_kernel<DH, 2><<<grid, 256, 0, stream>>>(a, scale_log2, range);
-    else if constexpr (DH <= 64) attn_mfma_kernel<DH, 4><<<grid, 256, 0, stream>>>(a, scale_log2, range);
+    if (QT == 1) launch_kernel(attn_mfma_kernel<DH, 1>, grid, 256, 0, stream, a, scale_log2, range);
+    else if (QT == 2) launch_kernel(attn_mfma_kernel<DH, 2>, grid, 256, 0, stream, a, scale_log2, range);
+    else if constexpr (DH <= 64) launch_kernel(attn_mfma_kernel<DH, 4>, grid, 256, 0, stream, a, scale_log2, range);
     }
     if (a.splits > 1) {
         ScopedProf sp(PSD_KIND_ATTN_COMBINE, stream);
-        attn_combine_kernel<<<a.B * a.R * a.h_q, DH, 0, stream>>>(a);
+        launch_kernel(attn_combine_kernel, a.B * a.R * a.h_q, DH, 0, stream, a);
     }
 }
 
@@ -318,8 +326,8 @@ void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream) {
     dim3 grid(a.h_q, a.B * a.R);
     const size_t smem = (size_t)a.len_bound * sizeof(float);
     ScopedProf sp(PSD_KIND_ATTN, stream);
-    if (dtype == PSD_BF16) attn_simple_kernel<uint16_t><<<grid, 64, smem, stream>>>(a, scale);
-    else attn_simple_kernel<float><<<grid, 64, smem, stream>>>(a, scale);
+    if (dtype == PSD_BF16) launch_kernel(attn_simple_kernel<uint16_t>, grid, 64, smem, stream, a, scale);
+    else launch_kernel(attn_simple_kernel<float>, grid, 64, smem, stream, a, scale);
 }
 
 }  // namespace psd

@@ -491,7 +491,7 @@ void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void 
     for (int s = 0; s < nseg; ++s) {
         const size_t units = (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * (K / kSkinnyStepK);
         const size_t vecs = units * kUnitVec;
-        gemm_pack_kernel<<<(unsigned)((vecs + 255) / 256), 256, 0, stream>>>((const uint16_t *)w[s], n[s], K, (u32x4 *)out);
+        launch_kernel(gemm_pack_kernel, (unsigned)((vecs + 255) / 256), 256, 0, stream, (const uint16_t *)w[s], n[s], K, (u32x4 *)out);
         out += units * kUnitBytes;
     }
 }
@@ -527,41 +527,41 @@ int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
 void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
     if (dtype != PSD_BF16) {
         ScopedProf sp(PSD_KIND_GEMM_F32, stream);
-        gemm_f32_kernel<<<(g.N + 3) / 4, 256, 0, stream>>>(g);
+        launch_kernel(gemm_f32_kernel, (g.N + 3) / 4, 256, 0, stream, g);
         return;
     }
     if (g.M <= 64 && g.wpack && gemm_use_stream(g.pack_tiles)) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         const int grid = gemm_stream_grid(g.pack_tiles, g.K);
         const int mt = (g.M + 15) / 16;
-        if (mt == 1) gemm_bf16_stream_kernel<1><<<grid, 256, 0, stream>>>(g);
-        else if (mt == 2) gemm_bf16_stream_kernel<2><<<grid, 256, 0, stream>>>(g);
-        else if (mt == 3) gemm_bf16_stream_kernel<3><<<grid, 256, 0, stream>>>(g);
-        else gemm_bf16_stream_kernel<4><<<grid, 256, 0, stream>>>(g);
+        if (mt == 1) launch_kernel(gemm_bf16_stream_kernel<1>, grid, 256, 0, stream, g);
+        else if (mt == 2) launch_kernel(gemm_bf16_stream_kernel<2>, grid, 256, 0, stream, g);
+        else if (mt == 3) launch_kernel(gemm_bf16_stream_kernel<3>, grid, 256, 0, stream, g);
+        else launch_kernel(gemm_bf16_stream_kernel<4>, grid, 256, 0, stream, g);
     } else if (g.M <= 64) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
         const int mt = (g.M + 15) / 16;
         if (g.wpack) {
-            if (mt == 1) gemm_bf16_skinny_kernel<1, true><<<grid, 256, 0, stream>>>(g);
-            else if (mt == 2) gemm_bf16_skinny_kernel<2, true><<<grid, 256, 0, stream>>>(g);
-            else if (mt == 3) gemm_bf16_skinny_kernel<3, true><<<grid, 256, 0, stream>>>(g);
-            else gemm_bf16_skinny_kernel<4, true><<<grid, 256, 0, stream>>>(g);
+            if (mt == 1) launch_kernel(gemm_bf16_skinny_kernel<1, true>, grid, 256, 0, stream, g);
+            else if (mt == 2) launch_kernel(gemm_bf16_skinny_kernel<2, true>, grid, 256, 0, stream, g);
+            else if (mt == 3) launch_kernel(gemm_bf16_skinny_kernel<3, true>, grid, 256, 0, stream, g);
+            else launch_kernel(gemm_bf16_skinny_kernel<4, true>, grid, 256, 0, stream, g);
         } else {
-            if (mt == 1) gemm_bf16_skinny_kernel<1, false><<<grid, 256, 0, stream>>>(g);
-            else if (mt == 2) gemm_bf16_skinny_kernel<2, false><<<grid, 256, 0, stream>>>(g);
-            else if (mt == 3) gemm_bf16_skinny_kernel<3, false><<<grid, 256, 0, stream>>>(g);
-            else gemm_bf16_skinny_kernel<4, false><<<grid, 256, 0, stream>>>(g);
+            if (mt == 1) launch_kernel(gemm_bf16_skinny_kernel<1, false>, grid, 256, 0, stream, g);
+            else if (mt == 2) launch_kernel(gemm_bf16_skinny_kernel<2, false>, grid, 256, 0, stream, g);
+            else if (mt == 3) launch_kernel(gemm_bf16_skinny_kernel<3, false>, grid, 256, 0, stream, g);
+            else launch_kernel(gemm_bf16_skinny_kernel<4, false>, grid, 256, 0, stream, g);
         }
     } else {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kBN) * ((g.M + kBM - 1) / kBM), g.splitk);
-        gemm_bf16_tiled_kernel<<<grid, 256, 0, stream>>>(g);
+        launch_kernel(gemm_bf16_tiled_kernel, grid, 256, 0, stream, g);
     }
     if (g.splitk > 1 && g.reduced) {
         const unsigned blocks = (unsigned)(((size_t)g.M * g.N + 255) / 256);
         ScopedProf sp(PSD_KIND_GEMM_REDUCE, stream);
-        gemm_splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(g);
+        launch_kernel(gemm_splitk_reduce_kernel, blocks, 256, 0, stream, g);
     }
 }
 

@@ -197,10 +197,10 @@ void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, floa
                        int M, int d, int vocab, float eps, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_EMBED, stream);
     if (dtype == PSD_BF16)
-        residual_norm_kernel<uint16_t, true><<<M, kRowThreads, 0, stream>>>((const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
+        launch_kernel(residual_norm_kernel<uint16_t, true>, M, kRowThreads, 0, stream, (const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
                                                                            x, (const uint16_t *)gain, xn, d, eps);
     else
-        residual_norm_kernel<float, true><<<M, kRowThreads, 0, stream>>>((const float *)embed, tokens, vocab, nullptr, 0, 0, x,
+        launch_kernel(residual_norm_kernel<float, true>, M, kRowThreads, 0, stream, (const float *)embed, tokens, vocab, nullptr, 0, 0, x,
                                                                         (const float *)gain, xn, d, eps);
 }
 
@@ -209,10 +209,10 @@ void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *
     ScopedProf sp(PSD_KIND_RMSNORM, stream);
     const size_t stride = (size_t)M * d;
     if (dtype == PSD_BF16)
-        residual_norm_kernel<uint16_t, false><<<M, kRowThreads, 0, stream>>>(nullptr, nullptr, 0, partial, S, stride, x,
+        launch_kernel(residual_norm_kernel<uint16_t, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
                                                                             (const uint16_t *)gain, xn, d, eps);
     else
-        residual_norm_kernel<float, false><<<M, kRowThreads, 0, stream>>>(nullptr, nullptr, 0, partial, S, stride, x,
+        launch_kernel(residual_norm_kernel<float, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
                                                                          (const float *)gain, xn, d, eps);
 }
 
@@ -223,30 +223,30 @@ void launch_reduce_rope_append(int dtype, const float *partial, int S, float *q_
     const size_t stride = (size_t)B * R * (h_q + 2 * h_kv) * d_h;
     const dim3 grid(B * R, h_q + 2 * h_kv);
     if (dtype == PSD_BF16)
-        reduce_rope_append_kernel<uint16_t><<<grid, 64, 0, stream>>>(partial, S, stride, q_out, (uint16_t *)k_cache,
+        launch_kernel(reduce_rope_append_kernel<uint16_t>, grid, 64, 0, stream, partial, S, stride, q_out, (uint16_t *)k_cache,
                                                                      (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
     else
-        reduce_rope_append_kernel<float><<<grid, 64, 0, stream>>>(partial, S, stride, q_out, (float *)k_cache, (float *)v_cache,
+        launch_kernel(reduce_rope_append_kernel<float>, grid, 64, 0, stream, partial, S, stride, q_out, (float *)k_cache, (float *)v_cache,
                                                                   lens, R, h_q, h_kv, d_h, max_len, theta);
 }
 
 void launch_reduce_swiglu(const float *partial, int S, float *h, int M, int f, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_SWIGLU, stream);
     const unsigned blocks = (unsigned)(((size_t)M * (f / 4) + 255) / 256);
-    reduce_swiglu_kernel<<<blocks, 256, 0, stream>>>(partial, S, (size_t)M * 2 * f, h, M, f);
+    launch_kernel(reduce_swiglu_kernel, blocks, 256, 0, stream, partial, S, (size_t)M * 2 * f, h, M, f);
 }
 
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_LENS, stream);
-    advance_lens_kernel<<<(B + 63) / 64, 64, 0, stream>>>(lens, B, delta, max_len);
+    launch_kernel(advance_lens_kernel, (B + 63) / 64, 64, 0, stream, lens, B, delta, max_len);
 }
 void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_LENS, stream);
-    truncate_kernel<<<(B + 63) / 64, 64, 0, stream>>>(lens, base, keep, offset, B);
+    launch_kernel(truncate_kernel, (B + 63) / 64, 64, 0, stream, lens, base, keep, offset, B);
 }
 void launch_truncate_to(int32_t *lens, int new_len, int B, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_LENS, stream);
-    truncate_to_kernel<<<(B + 63) / 64, 64, 0, stream>>>(lens, new_len, B);
+    launch_kernel(truncate_to_kernel, (B + 63) / 64, 64, 0, stream, lens, new_len, B);
 }
 
 }  // namespace psd
