@@ -260,6 +260,199 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
     }
 }
 
+// Many query rows per KV head (grouped-query verify at batch, prefill): the four wavefronts of a
+// block own different 16-row query tiles and all walk the same keys, so K and V^T tiles are staged in
+// LDS once per block (16-byte global loads, next tile prefetched into registers during the MFMAs) and
+// read from there as MFMA operands; K/V leave HBM once for up to 128 query rows.  No cross-wavefront
+// merge is needed: each wavefront finishes its own query rows.
+template <int DH, int QW>
+__global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float scale_log2, int range) {
+    constexpr int KS = DH / 32, DT = DH / 16;
+    constexpr int KSTRIDE = DH + 8;            // bf16 elements per staged K row (+16 B: conflict-free reads)
+    constexpr int VSTRIDE = 64 + 8;            // bf16 elements per staged V^T row
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * KSTRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[DH * VSTRIDE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int split = blockIdx.x, qchunk = blockIdx.y;
+    const int b = blockIdx.z / a.h_kv, hk = blockIdx.z % a.h_kv;
+    const int group = a.h_q / a.h_kv;
+    const int NQ = group * a.R;
+    const int S_b = a.lens[b];
+    const int n_keys = min(S_b + a.R, a.max_len);
+    const int kb0 = split * range, kb1 = min(n_keys, kb0 + range);
+    const size_t max_len = a.max_len;
+    const uint16_t *Kc = (const uint16_t *)a.k + ((size_t)b * a.h_kv + hk) * max_len * DH;
+    const uint16_t *Vt = (const uint16_t *)a.v + ((size_t)b * a.h_kv + hk) * DH * max_len;
+
+    bf16x8 qh[QW][KS], ql[QW][KS];
+    int limit[QW];
+    size_t out_row[QW];
+#pragma unroll
+    for (int qt = 0; qt < QW; ++qt) {
+        const int qi = ((qchunk * 4 + wave) * QW + qt) * 16 + i;
+        const bool valid = qi < NQ;
+        const int hl = valid ? qi / a.R : 0, r = valid ? qi % a.R : 0;
+        limit[qt] = valid ? S_b + r : -1;
+        out_row[qt] = ((size_t)(b * a.R + r)) * a.h_q + hk * group + hl;
+        const float *qp = a.q + out_row[qt] * DH + g * (DH / 4);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            f32x8 v = load_f32x8(qp + 8 * s);
+            if (!valid) v = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            split_bf16(v, &qh[qt][s], &ql[qt][s]);
+        }
+    }
+    f32x4 o[QW][DT];
+    float mrun[QW], lrun[QW];
+#pragma unroll
+    for (int qt = 0; qt < QW; ++qt) {
+        mrun[qt] = -INFINITY;
+        lrun[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // staging: K tile 64 keys x DH (DH/8 chunks of 16 B per key), V^T tile DH rows x 64 keys (8 chunks per row)
+    constexpr int KCH = 64 * DH / 8 / 256, VCH = DH * 8 / 256;
+    u32x4 kreg[KCH], vreg[VCH];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) {
+            const int chunk = tid + c * 256, key = chunk / (DH / 8), col = (chunk % (DH / 8)) * 8;
+            kreg[c] = *reinterpret_cast<const u32x4 *>(Kc + (size_t)(kt + key) * DH + col);     // kt + 64 <= max_len
+        }
+#pragma unroll
+        for (int c = 0; c < VCH; ++c) {
+            const int chunk = tid + c * 256, d = chunk >> 3, col = (chunk & 7) * 8;
+            u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + (size_t)d * max_len + kt + col);
+            if (kt + 64 > n_keys) {          // stale cache columns may hold anything, even NaN: zero them
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = kt + col + 2 * e;
+                    if (key >= n_keys) raw[e] = 0u;
+                    else if (key + 1 >= n_keys) raw[e] &= 0xffffu;
+                }
+            }
+            vreg[c] = raw;
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) {
+            const int chunk = tid + c * 256, key = chunk / (DH / 8), col = (chunk % (DH / 8)) * 8;
+            *reinterpret_cast<u32x4 *>(&Ks[key * KSTRIDE + col]) = kreg[c];
+        }
+#pragma unroll
+        for (int c = 0; c < VCH; ++c) {
+            const int chunk = tid + c * 256, d = chunk >> 3, col = (chunk & 7) * 8;
+            *reinterpret_cast<u32x4 *>(&Vs[d * VSTRIDE + col]) = vreg[c];
+        }
+    };
+
+    if (kb0 < kb1) {
+        load_tile(kb0);
+        store_tile();
+    }
+    __syncthreads();
+    for (int kt = kb0; kt < kb1; kt += 64) {
+        if (kt + 64 < kb1) load_tile(kt + 64);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int kb = kt + sub * 32;
+            if (kb >= kb1) break;
+            bf16x8 ka[2][KS], va[DT];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int key = sub * 32 + 8 * (i >> 2) + 4 * t + (i & 3);
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    ka[t][s] = *reinterpret_cast<const bf16x8 *>(&Ks[key * KSTRIDE + g * (DH / 4) + 8 * s]);
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                va[dt] = *reinterpret_cast<const bf16x8 *>(&Vs[(dt * 16 + i) * VSTRIDE + sub * 32 + 8 * g]);
+#pragma unroll
+            for (int qt = 0; qt < QW; ++qt) {
+                f32x4 c[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) {
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[t], 0, 0, 0);
+                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[t], 0, 0, 0);
+                    }
+                }
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int key = kb + 8 * g + 4 * t + v;
+                        const float sc = key <= limit[qt] ? c[t][v] * scale_log2 : -INFINITY;
+                        c[t][v] = sc;
+                        tmax = fmaxf(tmax, sc);
+                    }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                const float mnew = fmaxf(mrun[qt], tmax);
+                float alpha = 1.f;
+                float p[8];
+                if (mnew > -INFINITY) {
+                    alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+                    float ps = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        p[e] = __builtin_amdgcn_exp2f(c[e >> 2][e & 3] - mnew);
+                        ps += p[e];
+                    }
+                    lrun[qt] = lrun[qt] * alpha + ps;
+                    mrun[qt] = mnew;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p[e] = 0.f;
+                }
+                bf16x8 ph, pl;
+                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph, &pl);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph, o[qt][dt], 0, 0, 0);
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl, o[qt][dt], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+        if (kt + 64 < kb1) store_tile();
+        __syncthreads();
+    }
+
+    // each wavefront writes its own query rows: lane (query i, group g) holds d = dt*16 + 4g + v
+#pragma unroll
+    for (int qt = 0; qt < QW; ++qt) {
+        float L = lrun[qt];
+        L += __shfl_xor(L, 16, 64);
+        L += __shfl_xor(L, 32, 64);
+        if (limit[qt] < 0) continue;
+        if (a.splits == 1) {
+            const float inv = 1.0f / L;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                *reinterpret_cast<f32x4 *>(a.out + out_row[qt] * DH + dt * 16 + 4 * g) = o[qt][dt] * inv;
+        } else {
+            float *po = a.part_o + (out_row[qt] * a.splits + split) * DH;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4 *>(po + dt * 16 + 4 * g) = o[qt][dt];
+            if (g == 0) {
+                a.part_ml[(out_row[qt] * a.splits + split) * 2] = mrun[qt];
+                a.part_ml[(out_row[qt] * a.splits + split) * 2 + 1] = L;
+            }
+        }
+    }
+}
+
 // one block per (sequence, row, head); thread d merges the splits in split order
 __global__ void attn_combine_kernel(AttnArgs a) {
     const size_t row = blockIdx.x;
@@ -283,11 +476,15 @@ inline int q_tiles(int NQ, int d_h) { return NQ <= 16 ? 1 : ((NQ <= 32 || d_h > 
 
 }  // namespace
 
+// more than 32 query rows per KV head: the LDS-staged kernel, 64 or 128 rows per block
+inline bool use_wide(int NQ) { return NQ > 32; }
+inline int wide_rows(int NQ) { return NQ <= 64 ? 64 : 128; }
+
 int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound) {
     if (dtype != PSD_BF16) return 1;
     const int NQ = (h_q / h_kv) * R;
     const int QT = q_tiles(NQ, d_h);
-    const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
+    const int chunks = use_wide(NQ) ? (NQ + wide_rows(NQ) - 1) / wide_rows(NQ) : (NQ + QT * 16 - 1) / (QT * 16);
     const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
     int by_grid = 1024 / (B * h_kv * chunks);
     if (by_grid < 1) by_grid = 1;
@@ -303,6 +500,20 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     int range = (a.len_bound + a.splits - 1) / a.splits;
     range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+    if (use_wide(NQ)) {
+        const int rows = wide_rows(NQ);
+        dim3 wgrid(a.splits, (NQ + rows - 1) / rows, a.B * a.h_kv);
+        {
+            ScopedProf sp(PSD_KIND_ATTN, stream);
+            if (rows == 64) launch_kernel(attn_mfma_wide_kernel<DH, 1>, wgrid, 256, 0, stream, a, scale_log2, range);
+            else launch_kernel(attn_mfma_wide_kernel<DH, 2>, wgrid, 256, 0, stream, a, scale_log2, range);
+        }
+        if (a.splits > 1) {
+            ScopedProf sp(PSD_KIND_ATTN_COMBINE, stream);
+            launch_kernel(attn_combine_kernel, a.B * a.R * a.h_q, DH, 0, stream, a);
+        }
+        return;
+    }
     dim3 grid(a.splits, chunks, a.B * a.h_kv);
     {
     ScopedProf sp(PSD_KIND_ATTN, stream);

@@ -12,7 +12,7 @@
 //                            lanes load it, units of a GEMM are contiguous, and the grid is persistent:
 //                            each wavefront streams an equal, contiguous byte range of the weights
 //                            (stream-K) and writes one partial per tile it touches.
-//   gemm_bf16_tiled_kernel   M > 64.  128x128x64 LDS-staged tiles, 32x32x16 bf16 MFMA.
+//   gemm_bf16_tiled_kernel   M > 64.  128x256x64 LDS-staged tiles, 32x32x16 bf16 MFMA.
 // Activations are fp32 in memory in every case.  The bf16 kernels feed each activation to the
 // matrix cores as a pair of bf16 values hi + lo (two MFMAs against the same weight operand):
 // with plain bf16 activations the logits of the 7B-shaped random-init models are 3e-2 off the
@@ -346,12 +346,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g) {
 }
 
 // ------------------------------------------------------------------------------ bf16 tiled
-constexpr int kBM = 128, kBN = 128, kBK = 64, kLdsStride = 72;   // 72 elements = 144 B rows: no bank conflicts
+// Block tile 128 rows of activations x 256 rows of W x 64 of K; four wavefronts in a 2 x 2 grid, each
+// 64 x 128 = 2 x 4 tiles of the 32x32x16 MFMA.  The activation tile is staged in LDS twice (hi and lo
+// bf16 parts), so the wide side of the wavefront tile is the weight side: per 16-wide K step a wavefront
+// reads 4 + 4 operands for 16 MFMAs.  Rows are padded to 72 elements (144 B): conflict-free 16-byte reads.
+// LDS is dynamic (73.7 KB per block, two blocks per CU).
+constexpr int kBM = 128, kBN = 256, kBK = 64, kLdsStride = 72;
+constexpr size_t kTiledLds = (size_t)(2 * kBM + kBN) * kLdsStride * sizeof(uint16_t);
 
-__global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) uint16_t Xh[kBM * kLdsStride];   // activation tile, hi parts
-    __shared__ __attribute__((aligned(16))) uint16_t Xl[kBM * kLdsStride];   // activation tile, lo parts
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[kBN * kLdsStride];
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds_tiled[];
+    uint16_t *Xh = lds_tiled;                               // activation tile, hi parts
+    uint16_t *Xl = Xh + kBM * kLdsStride;                   // activation tile, lo parts
+    uint16_t *Ws = Xl + kBM * kLdsStride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
     const int m_tiles = (g.M + kBM - 1) / kBM;
@@ -364,44 +371,49 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(GemmArgs g) {
     const int nk = K / kBK;
     const int k0 = (int)((long)blockIdx.y * nk / g.splitk), k1 = (int)((long)(blockIdx.y + 1) * nk / g.splitk);
     const int m_base = mt * kBM;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;   // this wavefront's 64x64 sub-tile
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;   // this wavefront's 64 x 128 sub-tile
 
-    // global -> register staging: 4 x 8 elements of X (fp32) and of W (bf16) per thread and K tile
+    // global -> register staging per K tile: 4 x 8 fp32 of X and 8 x 8 bf16 of W per thread
     const float *xg[4];
-    const uint16_t *wg[4];
-    int lds_off[4];
+    const uint16_t *wg[8];
+    int xoff[4], woff[8];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
         xg[c] = X + x_row(g, min(m_base + row, g.M - 1)) * K + col;
+        xoff[c] = row * kLdsStride + col;
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
         wg[c] = W + (size_t)min(t.row0 + row, seg_rows - 1) * K + col;
-        lds_off[c] = row * kLdsStride + col;
+        woff[c] = row * kLdsStride + col;
     }
     f32x8 xr[4];
-    u32x4 wr[4];
+    u32x4 wr[8];
     auto load_tiles = [&](int kt) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            xr[c] = load_f32x8(xg[c] + (size_t)kt * kBK);
-            wr[c] = *reinterpret_cast<const u32x4 *>(wg[c] + (size_t)kt * kBK);
-        }
+        for (int c = 0; c < 4; ++c) xr[c] = load_f32x8(xg[c] + (size_t)kt * kBK);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) wr[c] = *reinterpret_cast<const u32x4 *>(wg[c] + (size_t)kt * kBK);
     };
     auto store_tiles = [&]() {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             bf16x8 hi, lo;
             split_bf16(xr[c], &hi, &lo);
-            *reinterpret_cast<bf16x8 *>(&Xh[lds_off[c]]) = hi;
-            *reinterpret_cast<bf16x8 *>(&Xl[lds_off[c]]) = lo;
-            *reinterpret_cast<u32x4 *>(&Ws[lds_off[c]]) = wr[c];
+            *reinterpret_cast<bf16x8 *>(&Xh[xoff[c]]) = hi;
+            *reinterpret_cast<bf16x8 *>(&Xl[xoff[c]]) = lo;
         }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = wr[c];
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][4];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -414,19 +426,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(GemmArgs g) {
         if (kt + 1 < k1) load_tiles(kt + 1);
 #pragma unroll
         for (int ks = 0; ks < kBK / 16; ++ks) {
-            bf16x8 fa[2], fl[2], fb[2];
+            bf16x8 fa[2], fl[2], fb[4];
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
                 fa[a] = *reinterpret_cast<const bf16x8 *>(&Xh[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
                 fl[a] = *reinterpret_cast<const bf16x8 *>(&Xl[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
             }
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < 4; ++b)
                 fb[b] = *reinterpret_cast<const bf16x8 *>(&Ws[(wn + b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                for (int b = 0; b < 4; ++b) {
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[a], fb[b], acc[a][b], 0, 0, 0);
                 }
@@ -439,7 +451,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_kernel(GemmArgs g) {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int b = 0; b < 4; ++b) {
             const int row = t.row0 + wn + b * 32 + li;
             if (row >= seg_rows) continue;
 #pragma unroll
@@ -516,11 +528,12 @@ int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
         return want < 1 ? 1 : want;
     }
     const int tiles = tiles_of(n, nseg, kBN) * ((M + kBM - 1) / kBM);
-    int want = (256 + tiles - 1) / tiles;
+    if (tiles >= 200) return 1;
+    int want = (256 + tiles / 2) / tiles;                 // about one block per CU
     int cap = K / kBK / 4;
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
-    if (want > 8) want = 8;
+    if (want > 16) want = 16;
     return want < 1 ? 1 : want;
 }
 
@@ -556,7 +569,13 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
     } else {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kBN) * ((g.M + kBM - 1) / kBM), g.splitk);
-        launch_kernel(gemm_bf16_tiled_kernel, grid, 256, 0, stream, g);
+        static bool lds_ok = false;                      // opt in once to more than 64 KB of dynamic LDS
+        if (!lds_ok) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_tiled_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTiledLds);
+            lds_ok = true;
+        }
+        launch_kernel(gemm_bf16_tiled_kernel, grid, 256, kTiledLds, stream, g);
     }
     if (g.splitk > 1 && g.reduced) {
         const unsigned blocks = (unsigned)(((size_t)g.M * g.N + 255) / 256);
