@@ -164,8 +164,7 @@ def main():
               "algorithmic_bytes": a_bytes, "call_us": call_us, "GB/s": a_bytes / call_us / 1e3,
               "frac_of_hbm_peak": a_bytes / call_us / 1e3 / HBM_PEAK_GBS,
               "stats_kernel_us": stats_us, "stats_kernel_GB/s": a_bytes / stats_us / 1e3,
-              "emit_z_kernel_us": 1e3 * aprof["accept_emit_z"][0] / aprof["accept_emit_z"][1],
-              "emit_r_kernel_us": 1e3 * aprof["accept_emit_r"][0] / aprof["accept_emit_r"][1],
+              "emit_kernel_us": 1e3 * aprof["accept_emit"][0] / aprof["accept_emit"][1],
               "locate_kernel_us": 1e3 * aprof["accept_locate"][0] / aprof["accept_locate"][1]}
 
     # ---- the oracle on the host cores, one whole step of the same workload

@@ -1,18 +1,17 @@
 // Speculative-sampling acceptance on gfx950 (the VERIFY loop of Algorithm 1 and the residual
 // draw that keeps the verifier's distribution, Sec. 3.1).
 //
-// Four launches per call, no host round trip (kernel boundaries are the cross-block
+// Three launches per call, no host round trip (kernel boundaries are the cross-block
 // synchronisation: device-scope fences plus a last-block counter measured several times slower):
 //   1. accept_stats_kernel  one pass over every logits row of p and q (the HBM-bound part):
 //      per (row, chunk) the max raw logit and sum exp((l - max)/T), fp32, wavefront
 //      reductions, 8 x 16-byte loads in flight per lane.
-//   2. accept_emit_z_kernel each block re-derives the first rejection n of its sequence from
+//   2. accept_emit_kernel   each block re-derives the first rejection n of its sequence from
 //      the statistics (ratio test against the supplied uniforms, prefix scan over <= 64
-//      flags) and accumulates, in fp64, the softmax denominators of the ONE position the
-//      draw needs.
-//   3. accept_emit_r_kernel fp64 residual mass per chunk.
-//   4. accept_locate_kernel one block per sequence locates the inverse-CDF crossing (chunk, then
-//      element) in index order.
+//      flags) and accumulates, in fp64 and for the ONE position the draw needs, the softmax
+//      denominators and the residual mass of its chunk.
+//   3. accept_locate_kernel one block per sequence locates the inverse-CDF crossing (chunk, then
+//      entry) in index order.
 // All sums are taken in a fixed order, so results do not depend on block scheduling.
 #include "common.h"
 #include "kernels.h"
@@ -41,6 +40,7 @@ __device__ __forceinline__ const T *logits_row(const AcceptArgs &a, int b, bool 
 // sides to agree to ~1e-15 relative, which leaves the flip probability at V * 1e-15.
 __device__ __forceinline__ double exp_nonpos(double x) {
     if (!(x > -745.0)) return 0.0;
+    if (x > 709.0) return INFINITY;          // callers with x > 0 (the acceptance ratio) saturate
     const double kf = rint(x * 1.4426950408889634074);
     double r = fma(-kf, 6.93147180369123816490e-01, x);
     r = fma(-kf, 1.90821492927058770002e-10, r);
@@ -58,18 +58,6 @@ __device__ __forceinline__ double exp_nonpos(double x) {
     const double lo = fma(r4, q1, q0);
     const double hi = fma(r4, pcd, q2);           // degree 8..13 (times r^8)
     return ldexp(fma(r8, hi, lo), (int)kf);
-}
-
-// block-wide fixed-order sum of one double per thread; result valid in every thread
-__device__ __forceinline__ double block_sum(double v, double *smem) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double t = 0.0;
-#pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) t += smem[w];
-    return t;
 }
 
 template <typename T, bool VEC>
@@ -134,15 +122,16 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(AcceptArgs a) {
     if (tid == 0) a.stats[(size_t)vec * a.n_chunksA + c] = make_float2(m, ((ss[0] + ss[1]) + ss[2]) + ss[3]);
 }
 
-// (max raw logit, sum exp((l - max)/T)) of one logits row from its per-chunk statistics
+// (max raw logit, sum exp((l - max)/T)) of one logits row from its per-chunk statistics.  The chunk
+// sums are fp32 quantities; rescaling them with the fp32 exponential loses nothing.
 __device__ __forceinline__ void combine_stats(const AcceptArgs &a, int b, int r, float *M, double *Z) {
     const float2 *st = a.stats + ((size_t)b * (a.n_p_rows + a.gamma) + r) * a.n_chunksA;
     float m = -INFINITY;
     for (int c = 0; c < a.n_chunksA; ++c) m = fmaxf(m, st[c].x);
     double z = 0.0;
-    const double invT = 1.0 / (double)a.temperature;
+    const float k2 = 1.4426950408889634f / a.temperature;
     for (int c = 0; c < a.n_chunksA; ++c)
-        if (st[c].x > -INFINITY) z += (double)st[c].y * exp(((double)st[c].x - (double)m) * invT);
+        if (st[c].x > -INFINITY) z += (double)(st[c].y * __builtin_amdgcn_exp2f((st[c].x - m) * k2));
     *M = m;
     *Z = z;
 }
@@ -153,21 +142,22 @@ template <typename T>
 __device__ __forceinline__ void decide(const AcceptArgs &a, int b, int *s_bits, int *n_out, int *flags_out) {
     const int j = threadIdx.x;
     if (j < a.gamma) {
+        // the token load heads the only dependent chain (token -> its two logits): start it first
+        int x = a.x[(size_t)b * a.gamma + j];
+        const double u = (double)a.u[(size_t)b * (a.gamma + 1) + j];
+        x = min(max(x, 0), a.V - 1);
+        const double lpx = load_elem(logits_row<T>(a, b, false, j), x);
+        const double lqx = load_elem(logits_row<T>(a, b, true, j), x);
         float Mp, Mq;
         double Zp, Zq;
         combine_stats(a, b, j, &Mp, &Zp);
         combine_stats(a, b, a.n_p_rows + j, &Mq, &Zq);
-        int x = a.x[(size_t)b * a.gamma + j];
-        x = min(max(x, 0), a.V - 1);
-        const double lpx = load_elem(logits_row<T>(a, b, false, j), x);
-        const double lqx = load_elem(logits_row<T>(a, b, true, j), x);
         double rho;
         if (lqx == -INFINITY) {
             rho = INFINITY;             // q[x] = 0: the token could not have been drafted; accept
         } else {
-            rho = exp(((lpx - (double)Mp) - (lqx - (double)Mq)) / (double)a.temperature) * (Zq / Zp);
+            rho = exp_nonpos(((lpx - (double)Mp) - (lqx - (double)Mq)) / (double)a.temperature) * (Zq / Zp);
         }
-        const double u = (double)a.u[(size_t)b * (a.gamma + 1) + j];
         const int acc = u < fmin(1.0, rho) ? 1 : 0;
         const int tie = fabs(u - rho) < kTieEps ? 2 : 0;
         s_bits[j] = acc | tie;
@@ -197,10 +187,55 @@ __device__ __forceinline__ DrawRows draw_rows(const AcceptArgs &a, int n) {
     return d;
 }
 
+// The draw position of one sequence, as both draw kernels see it.  With a = exp(lp/T - mp),
+// b = exp(lq/T - mq) (fp64), the residual weight of entry i is a_i/Zp - b_i/Zq where that is positive.
+// Whether it is positive is decided in the log domain against the fp32 statistics of the first pass,
+// xa - xb > log(Zp32/Zq32): a fixed rule both kernels share, which lets ONE pass accumulate sum(a),
+// sum(b) and the sums over the positive set without knowing the fp64 Zp, Zq yet.  It differs from the
+// sign of the fp64 residual only for entries with |p_i - q_i| < ~1e-6 q_i, whose weight is that small.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void accept_emit_z_kernel(AcceptArgs a) {
+struct DrawPos {
+    const T *prow, *qrow;
+    double inv_t, mp, mq, delta;
+    bool have_q;
+    __device__ __forceinline__ void init(const AcceptArgs &a, int b, int n, const DrawRows &d) {
+        float Mp, Mq = 0.f;
+        double Zp32, Zq32 = 1.0;
+        combine_stats(a, b, d.p_row, &Mp, &Zp32);
+        if (d.have_q) combine_stats(a, b, a.n_p_rows + n, &Mq, &Zq32);
+        prow = logits_row<T>(a, b, false, d.p_row);
+        qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
+        inv_t = 1.0 / (double)a.temperature;
+        mp = (double)Mp * inv_t;
+        mq = (double)Mq * inv_t;
+        delta = (double)logf((float)(Zp32 / Zq32));
+        have_q = d.have_q;
+    }
+    // raw logits of entry i (q's is 0 when there is no q row): plain loads, so callers can issue many
+    __device__ __forceinline__ void load(int i, float *lp, float *lq) const {
+        *lp = load_elem(prow, i);
+        *lq = have_q ? load_elem(qrow, i) : 0.f;
+    }
+    // (a_i, b_i, positive?) from the raw logits
+    __device__ __forceinline__ void eval(float lp, float lq, double *ea, double *eb, bool *pos) const {
+        const double xa = fma((double)lp, inv_t, -mp);
+        *ea = exp_nonpos(xa);
+        if (have_q) {
+            const double xb = fma((double)lq, inv_t, -mq);
+            *eb = exp_nonpos(xb);
+            *pos = xa - xb > delta;
+        } else {
+            *eb = 0.0;
+            *pos = true;
+        }
+    }
+};
+
+// Per chunk of the draw position: sum a, sum b, and both sums over the positive set (fp64).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void accept_emit_kernel(AcceptArgs a) {
     __shared__ int s_bits[64];
-    __shared__ double s_red[kThreads / 64];
+    __shared__ double s_red[4][kThreads / 64];
     const int b = blockIdx.x / a.n_chunksE, c = blockIdx.x % a.n_chunksE, tid = threadIdx.x;
     int n, flags;
     decide<T>(a, b, s_bits, &n, &flags);
@@ -211,97 +246,48 @@ __global__ __launch_bounds__(kThreads) void accept_emit_z_kernel(AcceptArgs a) {
         if (d.p_row < 0) a.out_tok[b] = -1;
     }
     if (d.p_row < 0) return;
-    float Mp, Mq = 0.f;
-    double Z_unused;
-    combine_stats(a, b, d.p_row, &Mp, &Z_unused);
-    if (d.have_q) combine_stats(a, b, a.n_p_rows + n, &Mq, &Z_unused);
-    const double temp = (double)a.temperature;
-    const double mp = (double)Mp * (1.0 / temp), mq = (double)Mq * (1.0 / temp);
-    const T *prow = logits_row<T>(a, b, false, d.p_row);
-    const T *qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
+    DrawPos<T> w;
+    w.init(a, b, n, d);
     const int e0 = c * a.chunkE, e1 = min(a.V, e0 + a.chunkE);
-    const double inv_t = 1.0 / temp;
-    double sa = 0.0, sb = 0.0;
+    double sa = 0.0, sb = 0.0, pa = 0.0, pb = 0.0;
     for (int i0 = e0 + tid; i0 < e1; i0 += 4 * kThreads) {
+        float lp[4], lq[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)            // all loads first (out-of-range lanes re-read entry e0)
+            w.load(i0 + u * kThreads < e1 ? i0 + u * kThreads : e0, &lp[u], &lq[u]);
         double ea[4], eb[4];
+        bool pos[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {          // four independent elements in flight per thread
-            const int i = i0 + u * kThreads;
-            const bool in = i < e1;
-            ea[u] = in ? exp_nonpos(fma((double)load_elem(prow, in ? i : e0), inv_t, -mp)) : 0.0;
-            eb[u] = (in && d.have_q) ? exp_nonpos(fma((double)load_elem(qrow, in ? i : e0), inv_t, -mq)) : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { sa += ea[u]; sb += eb[u]; }
-    }
-    sa = block_sum(sa, s_red);
-    sb = block_sum(sb, s_red);
-    if (tid == 0) a.zpart[(size_t)b * a.n_chunksE + c] = make_double2(sa, sb);
-}
-
-// residual weight of element i of the draw position (unnormalised by the residual mass)
-template <typename T>
-struct DrawWeights {
-    const T *prow, *qrow;
-    double inv_t, mp, mq, inv_zp, inv_zq;
-    bool have_q;
-    __device__ __forceinline__ double operator()(int i) const {
-        const double pi = exp_nonpos(fma((double)load_elem(prow, i), inv_t, -mp)) * inv_zp;
-        if (!have_q) return pi;
-        const double qi = exp_nonpos(fma((double)load_elem(qrow, i), inv_t, -mq)) * inv_zq;
-        const double r = pi - qi;
-        return r > 0.0 ? r : 0.0;
-    }
-};
-
-template <typename T>
-__global__ __launch_bounds__(kThreads) void accept_emit_r_kernel(AcceptArgs a) {
-    __shared__ double s_red[kThreads / 64];
-    const int b = blockIdx.x / a.n_chunksE, c = blockIdx.x % a.n_chunksE, tid = threadIdx.x;
-    const int n = a.out_n[b];
-    const DrawRows d = draw_rows(a, n);
-    if (d.p_row < 0) return;
-    const int nE = a.n_chunksE;
-    const double2 *zp = a.zpart + (size_t)b * nE;
-    double za = 0.0, zb = 0.0;
-    for (int k = tid; k < nE; k += kThreads) { za += zp[k].x; zb += zp[k].y; }
-    za = block_sum(za, s_red);
-    zb = block_sum(zb, s_red);
-    float Mp, Mq = 0.f;
-    double Z_unused;
-    combine_stats(a, b, d.p_row, &Mp, &Z_unused);
-    if (d.have_q) combine_stats(a, b, a.n_p_rows + n, &Mq, &Z_unused);
-    DrawWeights<T> w;
-    w.prow = logits_row<T>(a, b, false, d.p_row);
-    w.qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
-    w.inv_t = 1.0 / (double)a.temperature;
-    w.mp = (double)Mp * w.inv_t;
-    w.mq = (double)Mq * w.inv_t;
-    w.inv_zp = 1.0 / za;
-    w.inv_zq = d.have_q ? 1.0 / zb : 0.0;
-    w.have_q = d.have_q;
-
-    const int e0 = c * a.chunkE, e1 = min(a.V, e0 + a.chunkE);
-    double rs = 0.0;
-    for (int i0 = e0 + tid; i0 < e1; i0 += 4 * kThreads) {
-        double t[4];
+        for (int u = 0; u < 4; ++u) w.eval(lp[u], lq[u], &ea[u], &eb[u], &pos[u]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * kThreads;
-            t[u] = i < e1 ? w(i) : 0.0;
+            if (i0 + u * kThreads < e1) {
+                sa += ea[u];
+                sb += eb[u];
+                if (pos[u]) { pa += ea[u]; pb += eb[u]; }
+            }
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) rs += t[u];
     }
-    rs = block_sum(rs, s_red);
-    if (tid == 0) a.rpart[(size_t)b * nE + c] = rs;
+    sa = wave_sum(sa); sb = wave_sum(sb); pa = wave_sum(pa); pb = wave_sum(pb);
+    if ((tid & 63) == 0) {
+        const int wv = tid >> 6;
+        s_red[0][wv] = sa; s_red[1][wv] = sb; s_red[2][wv] = pa; s_red[3][wv] = pb;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double t[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) t[k] = ((s_red[k][0] + s_red[k][1]) + s_red[k][2]) + s_red[k][3];
+        a.zpart[(size_t)b * a.n_chunksE + c] = make_double2(t[0], t[1]);
+        a.ppart[(size_t)b * a.n_chunksE + c] = make_double2(t[2], t[3]);
+    }
 }
 
-// One block per sequence: locate the inverse-CDF crossing of u * mass, first among the chunk sums
-// (index order), then among the elements of that chunk.
+// One block per sequence: fp64 Zp, Zq from the chunk sums, chunk weights, then the inverse-CDF
+// crossing of u * mass, first among the chunks (index order), then among the entries of that chunk.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void accept_locate_kernel(AcceptArgs a) {
-    __shared__ double s_red[kThreads / 64];
+    __shared__ double s_red[2][kThreads / 64];
     __shared__ double s_scan[kThreads / 64];
     __shared__ double s_w[kMaxChunksE];          // per-chunk weights of this sequence
     __shared__ int s_cstar, s_best, s_lastpos;
@@ -312,74 +298,109 @@ __global__ __launch_bounds__(kThreads) void accept_locate_kernel(AcceptArgs a) {
     if (d.p_row < 0) return;
     const int nE = a.n_chunksE;
     const double2 *zp = a.zpart + (size_t)b * nE;
+    const double2 *pp = a.ppart + (size_t)b * nE;
+    const double u = (double)a.u[(size_t)b * (a.gamma + 1) + a.gamma];
+    DrawPos<T> w;
+    w.init(a, b, n, d);
     double za = 0.0, zb = 0.0;
     for (int k = tid; k < nE; k += kThreads) { za += zp[k].x; zb += zp[k].y; }
-    za = block_sum(za, s_red);
-    zb = block_sum(zb, s_red);
-    float Mp, Mq = 0.f;
-    double Z_unused;
-    combine_stats(a, b, d.p_row, &Mp, &Z_unused);
-    if (d.have_q) combine_stats(a, b, a.n_p_rows + n, &Mq, &Z_unused);
-    DrawWeights<T> w;
-    w.prow = logits_row<T>(a, b, false, d.p_row);
-    w.qrow = logits_row<T>(a, b, true, d.have_q ? n : 0);
-    w.inv_t = 1.0 / (double)a.temperature;
-    w.mp = (double)Mp * w.inv_t;
-    w.mq = (double)Mq * w.inv_t;
-    w.inv_zp = 1.0 / za;
-    w.inv_zq = d.have_q ? 1.0 / zb : 0.0;
-    w.have_q = d.have_q;
-
-    // ---- last block of this sequence: locate the crossing of u * mass in index order
-    const double *rp = a.rpart + (size_t)b * nE;
+    za = wave_sum(za); zb = wave_sum(zb);
+    if ((tid & 63) == 0) { s_red[0][tid >> 6] = za; s_red[1][tid >> 6] = zb; }
+    __syncthreads();
+    za = ((s_red[0][0] + s_red[0][1]) + s_red[0][2]) + s_red[0][3];
+    zb = ((s_red[1][0] + s_red[1][1]) + s_red[1][2]) + s_red[1][3];
+    const double inv_zp = 1.0 / za, inv_zq = d.have_q ? 1.0 / zb : 0.0;
     double mass = 0.0;
     for (int k = tid; k < nE; k += kThreads) {
-        const double wk = rp[k];
+        const double wk = pp[k].x * inv_zp - pp[k].y * inv_zq;
         s_w[k] = wk;
         mass += wk;
     }
-    mass = block_sum(mass, s_red);
+    __syncthreads();                              // s_red reuse, s_w complete
+    mass = wave_sum(mass);
+    if ((tid & 63) == 0) s_red[0][tid >> 6] = mass;
+    __syncthreads();
+    mass = ((s_red[0][0] + s_red[0][1]) + s_red[0][2]) + s_red[0][3];
     const bool fall_back_to_p = d.have_q && !(mass > 0.0);
-    if (fall_back_to_p) {                  // residual mass 0: draw from p itself
-        w.have_q = false;
-        mass = 1.0;                        // sum of a_i / Z_p
-        for (int k = tid; k < nE; k += kThreads) s_w[k] = zp[k].x * w.inv_zp;
+    if (fall_back_to_p) {                         // residual mass 0: draw from p itself
+        mass = 1.0;                               // sum of a_i / Zp
+        for (int k = tid; k < nE; k += kThreads) s_w[k] = zp[k].x * inv_zp;
         __syncthreads();
     }
-    if (tid == 0) {
-        const double u = (double)a.u[(size_t)b * (a.gamma + 1) + a.gamma];
+    // first chunk whose inclusive prefix exceeds t: each thread owns kMaxChunksE/256 consecutive chunks
+    {
+        constexpr int CPT = kMaxChunksE / kThreads;
         const double t = u * mass;
+        double cw[CPT], lsum = 0.0;
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int k = tid * CPT + j;
+            cw[j] = k < nE ? s_w[k] : 0.0;
+            lsum += cw[j];
+        }
+        double incl = lsum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double up = __shfl_up(incl, o, 64);
+            if ((tid & 63) >= o) incl += up;
+        }
+        if (tid == 0) { s_best = 0x7fffffff; s_lastpos = -1; s_cstar = 0x7fffffff; }
+        if ((tid & 63) == 63) s_scan[tid >> 6] = incl;
+        __syncthreads();
         double base = 0.0;
-        int cstar = -1, last_nonzero = -1;
-        for (int k = 0; k < nE; ++k) {
-            const double wk = s_w[k];
-            if (wk > 0.0) last_nonzero = k;
-            if (base + wk > t) { cstar = k; break; }
-            base += wk;
+        for (int wvi = 0; wvi < (tid >> 6); ++wvi) base += s_scan[wvi];
+        base += incl - lsum;
+        int mine = 0x7fffffff, last_nonzero = -1;
+        double mybase = 0.0;
+#pragma unroll
+        for (int j = 0; j < CPT; ++j) {
+            const int k = tid * CPT + j;
+            if (k < nE) {
+                if (cw[j] > 0.0) last_nonzero = k;
+                if (mine == 0x7fffffff && base + cw[j] > t) { mine = k; mybase = base; }
+                base += cw[j];
+            }
         }
-        if (cstar < 0) {                   // rounding left no crossing: last element with weight
-            cstar = max(last_nonzero, 0);
-            s_t = INFINITY;
-        } else {
+        if (mine != 0x7fffffff) atomicMin(&s_cstar, mine);
+        if (last_nonzero >= 0) atomicMax(&s_lastpos, last_nonzero);
+        __syncthreads();
+        const int cstar = s_cstar;
+        if (cstar == 0x7fffffff) {                    // rounding left no crossing: last entry with weight
+            if (tid == 0) { s_cstar = max(s_lastpos, 0); s_t = INFINITY; s_base = 0.0; }
+        } else if (mine == cstar) {                   // exactly one thread owns the crossing chunk
             s_t = t;
+            s_base = mybase;
         }
-        s_cstar = cstar;
-        s_base = base;
-        s_best = 0x7fffffff;
-        s_lastpos = -1;
-        if (fall_back_to_p) a.flags[b] |= PSD_FLAG_ZERO_RESIDUAL;
+        __syncthreads();
+        if (tid == 0) {
+            s_lastpos = -1;
+            if (fall_back_to_p) a.flags[b] |= PSD_FLAG_ZERO_RESIDUAL;
+        }
     }
     __syncthreads();
     const int cs = s_cstar;
     const double t = s_t;
     const int f0 = cs * a.chunkE, f1 = min(a.V, f0 + a.chunkE);
-    const int per = (f1 - f0 + kThreads - 1) / kThreads;       // consecutive elements per thread (<= kMaxPer)
+    const int per = (f1 - f0 + kThreads - 1) / kThreads;       // consecutive entries per thread (<= kMaxPer)
     const int i0 = min(f1, f0 + tid * per), i1 = min(f1, i0 + per);
     double wv[kMaxPer];
     double local = 0.0;
+    float lp[kMaxPer], lq[kMaxPer];
+#pragma unroll
+    for (int j = 0; j < kMaxPer; ++j)            // all loads first (idle slots re-read entry f0)
+        if (j < per) w.load(i0 + j < i1 ? i0 + j : f0, &lp[j], &lq[j]);
 #pragma unroll
     for (int j = 0; j < kMaxPer; ++j) {
-        wv[j] = (j < per && i0 + j < i1) ? w(i0 + j) : 0.0;
+        wv[j] = 0.0;
+        if (j < per) {
+            double ea, eb;
+            bool pos;
+            w.eval(lp[j], lq[j], &ea, &eb, &pos);
+            if (i0 + j < i1) {
+                if (fall_back_to_p) wv[j] = ea * inv_zp;
+                else if (pos) wv[j] = ea * inv_zp - eb * inv_zq;
+            }
+        }
     }
 #pragma unroll
     for (int j = 0; j < kMaxPer; ++j) local += wv[j];
@@ -439,8 +460,7 @@ size_t accept_workspace_bytes(const AcceptArgs &a) {
     size_t b = 0;
     b += align256(rows * (a.n_p_rows + a.gamma) * a.n_chunksA * sizeof(float2));
     b += align256(rows * a.n_chunksE * sizeof(double2));
-    b += align256(rows * a.n_chunksE * sizeof(double));
-    b += align256(rows * sizeof(uint32_t));
+    b += align256(rows * a.n_chunksE * sizeof(double2));
     b += align256(rows * sizeof(int32_t));
     return b;
 }
@@ -450,8 +470,7 @@ void accept_bind_workspace(AcceptArgs *a, void *ws, int32_t *out_flags) {
     char *p = (char *)ws;
     a->stats = (float2 *)p;   p += align256(rows * (a->n_p_rows + a->gamma) * a->n_chunksA * sizeof(float2));
     a->zpart = (double2 *)p;  p += align256(rows * a->n_chunksE * sizeof(double2));
-    a->rpart = (double *)p;   p += align256(rows * a->n_chunksE * sizeof(double));
-    a->counters = (uint32_t *)p; p += align256(rows * sizeof(uint32_t));
+    a->ppart = (double2 *)p;  p += align256(rows * a->n_chunksE * sizeof(double2));
     a->flags = out_flags ? out_flags : (int32_t *)p;
 }
 
@@ -466,12 +485,8 @@ static void launch_accept_t(const AcceptArgs &a, bool vec_ok, hipStream_t stream
     }
     dim3 gridE((unsigned)a.rows * a.n_chunksE);
     {
-        ScopedProf sp(PSD_KIND_ACCEPT_EMIT_Z, stream);
-        launch_kernel(accept_emit_z_kernel<T>, gridE, kThreads, 0, stream, a);
-    }
-    {
-        ScopedProf sp(PSD_KIND_ACCEPT_EMIT_R, stream);
-        launch_kernel(accept_emit_r_kernel<T>, gridE, kThreads, 0, stream, a);
+        ScopedProf sp(PSD_KIND_ACCEPT_EMIT, stream);
+        launch_kernel(accept_emit_kernel<T>, gridE, kThreads, 0, stream, a);
     }
     {
         ScopedProf sp(PSD_KIND_ACCEPT_LOCATE, stream);

@@ -19,6 +19,7 @@
 // load, and the score accumulator of S^T = K Q^T already holds P^T in exactly the operand layout
 // the second MFMA needs (keys are numbered kb + 8g + 4t + v so that the two 16-key score tiles
 // of a lane are 8 consecutive keys).
+#include <cstdlib>
 #include "common.h"
 #include "kernels.h"
 #include "prof.h"
@@ -150,58 +151,75 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                     va[sub][dt] = __builtin_bit_cast(bf16x8, raw);
                 }
             }
+            // scores of every query tile first, MFMAs interleaved over independent accumulators
+            f32x4 c[QT][2];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) c[qt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], qh[qt][s], c[qt][t], 0, 0, 0);
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], ql[qt][s], c[qt][t], 0, 0, 0);
+            }
+            bf16x8 ph[QT], pl[QT];
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
-                f32x4 c[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], qh[qt][s], c[t], 0, 0, 0);
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], ql[qt][s], c[t], 0, 0, 0);
-                    }
-                }
-                // lane (query column i, group g): c[t][v] is key kb + 8g + 4t + v
+                // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
                 float tmax = -INFINITY;
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int key = kb + 8 * g + 4 * t + v;
-                        const float s = key <= limit[qt] ? c[t][v] * scale_log2 : -INFINITY;
-                        c[t][v] = s;
-                        tmax = fmaxf(tmax, s);
+                        const float sc = key <= limit[qt] ? c[qt][t][v] * scale_log2 : -INFINITY;
+                        c[qt][t][v] = sc;
+                        tmax = fmaxf(tmax, sc);
                     }
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
                 const float mnew = fmaxf(mrun[qt], tmax);
-                float alpha = 1.f;
                 float p[8];
                 if (mnew > -INFINITY) {
-                    alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+                    const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
                     float ps = 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        p[e] = __builtin_amdgcn_exp2f(c[e >> 2][e & 3] - mnew);
+                        p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
                         ps += p[e];
                     }
                     lrun[qt] = lrun[qt] * alpha + ps;
+                    if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                    }
                     mrun[qt] = mnew;
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) p[e] = 0.f;
                 }
-                bf16x8 ph, pl;
-                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph, &pl);
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], ph, o[qt][dt], 0, 0, 0);
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], pl, o[qt][dt], 0, 0, 0);
-                }
+                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph[qt], &pl[qt]);
             }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], ph[qt], o[qt][dt], 0, 0, 0);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], pl[qt], o[qt][dt], 0, 0, 0);
         }
     }
 
@@ -372,57 +390,75 @@ __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float s
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
                 va[dt] = *reinterpret_cast<const bf16x8 *>(&Vs[(dt * 16 + i) * VSTRIDE + sub * 32 + 8 * g]);
+            // scores of every query tile first, MFMAs interleaved over independent accumulators
+            f32x4 c[QW][2];
+#pragma unroll
+            for (int qt = 0; qt < QW; ++qt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) c[qt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                for (int qt = 0; qt < QW; ++qt)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[qt][t], 0, 0, 0);
+#pragma unroll
+                for (int qt = 0; qt < QW; ++qt)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[qt][t], 0, 0, 0);
+            }
+            bf16x8 ph[QW], pl[QW];
 #pragma unroll
             for (int qt = 0; qt < QW; ++qt) {
-                f32x4 c[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[t], 0, 0, 0);
-                        c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[t], 0, 0, 0);
-                    }
-                }
+                // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
                 float tmax = -INFINITY;
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int key = kb + 8 * g + 4 * t + v;
-                        const float sc = key <= limit[qt] ? c[t][v] * scale_log2 : -INFINITY;
-                        c[t][v] = sc;
+                        const float sc = key <= limit[qt] ? c[qt][t][v] * scale_log2 : -INFINITY;
+                        c[qt][t][v] = sc;
                         tmax = fmaxf(tmax, sc);
                     }
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
                 const float mnew = fmaxf(mrun[qt], tmax);
-                float alpha = 1.f;
                 float p[8];
                 if (mnew > -INFINITY) {
-                    alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+                    const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
                     float ps = 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        p[e] = __builtin_amdgcn_exp2f(c[e >> 2][e & 3] - mnew);
+                        p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
                         ps += p[e];
                     }
                     lrun[qt] = lrun[qt] * alpha + ps;
+                    if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                    }
                     mrun[qt] = mnew;
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) p[e] = 0.f;
                 }
-                bf16x8 ph, pl;
-                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph, &pl);
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph, o[qt][dt], 0, 0, 0);
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl, o[qt][dt], 0, 0, 0);
-                }
+                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph[qt], &pl[qt]);
             }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int qt = 0; qt < QW; ++qt)
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph[qt], o[qt][dt], 0, 0, 0);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int qt = 0; qt < QW; ++qt)
+                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl[qt], o[qt][dt], 0, 0, 0);
         }
         __syncthreads();
         if (kt + 64 < kb1) store_tile();

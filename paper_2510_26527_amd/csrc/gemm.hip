@@ -173,13 +173,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
                 if (!xvalid[mt]) xv = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 split_bf16(xv, &bh[mt], &bl[mt]);
             }
+            // hi parts over all accumulators, then lo parts: no back-to-back MFMAs on one accumulator
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
+                for (int mt = 0; mt < MT; ++mt)
                     acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_cur[s][q], bh[mt], acc[s][mt], 0, 0, 0);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
                     acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_cur[s][q], bl[mt], acc[s][mt], 0, 0, 0);
-                }
         }
         if (step + 1 < s1) {
 #pragma unroll
@@ -295,10 +299,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g) {
             for (int s = 0; s < 4; ++s) {
                 const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[s * 4 + q]);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
+                for (int mt = 0; mt < MT; ++mt)
                     acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh[mt], acc[s][mt], 0, 0, 0);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[s * 4 + q]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
                     acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl[mt], acc[s][mt], 0, 0, 0);
-                }
             }
         }
         if (step == ns - 1 || u + 1 == u1) {
@@ -438,10 +447,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
+                for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[a], fb[b], acc[a][b], 0, 0, 0);
-                }
         }
         __syncthreads();
         if (kt + 1 < k1) store_tiles();

@@ -20,8 +20,7 @@ struct AcceptArgs {
     int chunkE, n_chunksE;        // draw pass chunking
     float2 *stats;                // [rows][n_p_rows+gamma][n_chunksA] (max raw logit, sum exp)
     double2 *zpart;               // [rows][n_chunksE] fp64 partial softmax denominators (p, q)
-    double *rpart;                // [rows][n_chunksE] fp64 partial residual mass
-    uint32_t *counters;           // [rows] arrival counters of the draw pass
+    double2 *ppart;               // [rows][n_chunksE] the same sums over the entries with positive residual
     int32_t *out_n, *out_tok, *flags;
 };
 // vec: rows are 16-byte aligned and V is a multiple of the elements per 16-byte load
