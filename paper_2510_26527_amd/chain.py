@@ -43,9 +43,11 @@ class Level:
 
 
 class Chain:
-    def __init__(self, levels, gammas, tapes, temperature=1.0, max_len=None, trace=False, timed=False):
+    def __init__(self, levels, gammas, tapes, temperature=1.0, max_len=None, trace=False, timed=False, sink=None):
         """levels[0] is the target; gammas[i] (i >= 1) the block size level i hands to level i-1;
-        tapes[i] float32 [calls, >= gamma+1] for verifying levels, flat for the draft."""
+        tapes[i] float32 [calls, >= gamma+1] for verifying levels, flat for the draft.
+        trace: record every forward / sample / accept with its tensors, into self.events or, if
+        given, by calling sink(event) at once (a long run then keeps no copies)."""
         self.levels = levels
         self.n = len(levels)
         self.gammas = gammas
@@ -61,6 +63,7 @@ class Chain:
         self.trace = trace
         self.timed = timed
         self.events = []
+        self._emit = sink if sink is not None else self.events.append
         self.accept_lens = [[] for _ in range(self.n)]
         self.block_lens = [[] for _ in range(self.n)]
         self.accept_ms = 0.0
@@ -82,10 +85,14 @@ class Chain:
             lvl._pending.append((e0, e1))
         lvl.kv_len = self.seq_len
         lvl.forwards += 1
+        self._rows_ready(i, dst, n_logit_rows)
         if self.trace:
-            self.events.append(("forward", i, start, toks.cpu().tolist(),
+            self._emit(("forward", i, start, toks.cpu().tolist(),
                                 None if dst is None else dst.detach().clone()))
         return dst
+
+    def _rows_ready(self, i, dst, n_logit_rows):
+        """Called after level i's forward has been enqueued, before anything reads its rows."""
 
     def _rollback(self, i, new_len):
         for j in range(i, self.n):
@@ -114,7 +121,7 @@ class Chain:
                                     row.shape[-1], 0, None, a._ws)
                 self.seq_len += 1
                 if self.trace:
-                    self.events.append(("sample", i, float(u.item()), int(slot.item()), row.detach().cpu().clone()))
+                    self._emit(("sample", i, float(u.item()), int(slot.item()), row.detach().cpu().clone()))
             return
         have = 0
         below = self.levels[i + 1]
@@ -140,7 +147,7 @@ class Chain:
             self.accept_lens[i].append(n)
             self.block_lens[i].append(k)
             if self.trace:
-                self.events.append(("accept", i, k, x.cpu().numpy()[0].copy(), u.cpu().numpy()[0].copy(), n, tok, flags,
+                self._emit(("accept", i, k, x.cpu().numpy()[0].copy(), u.cpu().numpy()[0].copy(), n, tok, flags,
                                     p.detach().cpu().clone(), below.rows[0:k].detach().cpu().clone()))
             self.seq_len = base + n
             self._rollback(i, base + n)

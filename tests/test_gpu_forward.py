@@ -43,9 +43,9 @@ class Pair:
     """The same model, cache contents and lengths on both sides."""
 
     def __init__(self, shape, dtype, batch, max_len, seed=0, ctx=None, lens=None, std=0.02, oracle_kv_dtype=np.float64,
-                 oracle_rows=None, pack=False):
+                 oracle_rows=None, pack=False, share=None):
         self.shape, self.dtype, self.batch = shape, dtype, batch
-        self.w = synth.make_weights(shape, seed, dtype, std=std)
+        self.w = synth.make_weights(shape, seed, dtype, std=std, share=share)
         self.model = runtime.Model(shape, self.w)
         if pack:
             self.model.pack()
@@ -212,3 +212,31 @@ def test_workload5_qwen2_7b_full_size_sampled_sequences():
     e = p.step(toks, n_logit_rows=16, what="16x16 rows")
     _progress(f"w5: rel err {e:.3e}")
     p.close()
+
+
+def test_workload4_chain_models_full_size():
+    """Workload 4's three models at full size, each at the row count its verify step has in the
+    chain (gamma_intermediate + 1 = 11 rows for the LLaMA3-8B-shaped target: 44 query rows per KV
+    head; gamma_draft + 1 = 7 rows for the intermediate with d_head 64; 1 and 2 rows for the
+    one-layer draft that shares the target's embedding and lm_head), against 300-token caches."""
+    _progress("w4: generating LLaMA3-8B-shaped target")
+    tgt = Pair(synth.LLAMA3_8B, torch.bfloat16, 1, 384, seed=41, ctx=300, oracle_kv_dtype=np.float32, pack=True)
+    toks = synth.make_tokens(synth.LLAMA3_8B.vocab, (1, 14), 44)
+    _progress("w4: target forward 11 rows, both sides")
+    e = tgt.step(toks[:, :11], what="target 11 rows")
+    _progress(f"w4: target rel err {e:.3e}")
+    share = {"embed": tgt.w["embed"], "lm_head": tgt.w["lm_head"]}
+    drf = Pair(synth.CHAIN_DRAFT, torch.bfloat16, 1, 384, seed=43, ctx=300, oracle_kv_dtype=np.float32, pack=True,
+               share=share)
+    assert drf.model.weights["lm_head"].data_ptr() != 0
+    e1 = drf.step(toks[:, :1], what="draft 1 row")
+    e2 = drf.step(toks[:, 1:3], what="draft 2 rows")
+    _progress(f"w4: draft rel err {e1:.3e} {e2:.3e}")
+    drf.close()
+    tgt.close()
+    del drf, tgt, share
+    mid = Pair(synth.CHAIN_INTERMEDIATE, torch.bfloat16, 1, 384, seed=42, ctx=300, oracle_kv_dtype=np.float32,
+               pack=True)
+    e = mid.step(toks[:, :7], what="intermediate 7 rows")
+    _progress(f"w4: intermediate rel err {e:.3e}")
+    mid.close()
