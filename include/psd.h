@@ -60,10 +60,12 @@ typedef struct psd_kv psd_kv;
  * (element i pairs with i + d_head/2, angle = position * rope_theta^(-2i/d_head)),
  * grouped-query causal attention, SwiGLU MLP, no biases, untied lm_head.
  * dtype is the storage type of every weight and of the KV cache; PSD_BF16 models
- * multiply on the bf16 matrix cores with fp32 accumulation and keep the residual
- * stream in fp32, PSD_F32 models compute in fp32 throughout.
- * Limits: d_head in {32, 64, 128}; n_q_heads a multiple of n_kv_heads;
- * d_model, d_ffn and every projection width multiples of 32. */
+ * multiply on the bf16 matrix cores with fp32 accumulation; every activation stays
+ * fp32 and enters the matrix cores as a bf16 high part plus a bf16 remainder (two
+ * products per weight operand), PSD_F32 models compute in fp32 throughout.
+ * Limits: d_head in {32, 64, 128} (PSD_BF16: 64 or 128); n_q_heads a multiple of
+ * n_kv_heads; d_model <= 8192; d_model, d_ffn and n_q_heads*d_head multiples of 32
+ * (PSD_BF16: of 128).  Anything else: PSD_ERR_SHAPE from psd_model_create. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, d_head, d_ffn, vocab;
     float rope_theta, rms_eps;
