@@ -149,3 +149,37 @@ int oracle_spec_accept(const double *lp, const double *lq, const int32_t *x, con
     free(p); free(q); free(r);
     return 0;
 }
+
+/*
+ * Greedy verification (the verification rule the paper lists beside speculative
+ * sampling in Sec. 3.1 and compares against in its ablation on acceptance-length
+ * variance): a draft token is kept iff it is the verifier's most likely token,
+ * argmax_v lp_j[v], the lowest index among equal maxima; the first mismatch is
+ * replaced by that argmax; if every draft token matches and the verifier has one
+ * more row, its argmax is the bonus token, else -1.  No temperature, no uniforms,
+ * no drafter distribution.
+ *   lp [rows][n_p_rows][V], x [rows][gamma], out_n / out_tok [rows].
+ */
+int oracle_greedy_accept(const double *lp, const int32_t *x, int rows, int gamma, int n_p_rows, int V,
+                         int32_t *out_n, int32_t *out_tok)
+{
+    if (rows < 0 || gamma < 0 || V <= 0) return -1;
+    if (n_p_rows != gamma && n_p_rows != gamma + 1) return -1;
+    for (int b = 0; b < rows; ++b) {
+        const double *l = lp + (size_t)b * n_p_rows * V;
+        int n = gamma;
+        int32_t tok = -1;
+        for (int j = 0; j < n_p_rows; ++j) {
+            int best = 0;
+            for (int v = 1; v < V; ++v)
+                if (l[(size_t)j * V + v] > l[(size_t)j * V + best]) best = v;
+            if (j < gamma && x[(size_t)b * gamma + j] == best) continue;
+            n = j;            /* j < gamma: first mismatch; j == gamma: the bonus row */
+            tok = best;
+            break;
+        }
+        out_n[b] = n;
+        out_tok[b] = tok;
+    }
+    return 0;
+}

@@ -27,6 +27,9 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_double, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_greedy_accept.restype = ctypes.c_int
+        lib.oracle_greedy_accept.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -79,3 +82,21 @@ def sample(logits, uniforms, temperature=1.0):
                             np.empty((rows, 0), np.int32),
                             np.asarray(uniforms, np.float64).reshape(rows, 1), temperature)
     return tok
+
+
+def greedy_accept(p_logits, draft_tokens):
+    """Greedy verification: p_logits [rows, n_p_rows, V], draft_tokens int [rows, gamma] with
+    n_p_rows in {gamma, gamma+1} -> (accept_len int32[rows], token int32[rows])."""
+    lp = np.ascontiguousarray(p_logits, dtype=np.float64)
+    x = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    rows, n_p_rows, V = lp.shape
+    gamma = x.shape[1]
+    if x.shape[0] != rows:
+        raise ValueError("p and draft_tokens disagree on rows")
+    out_n = np.empty(rows, np.int32)
+    out_tok = np.empty(rows, np.int32)
+    rc = _load().oracle_greedy_accept(lp.ctypes.data, x.ctypes.data, rows, gamma, n_p_rows, V,
+                                      out_n.ctypes.data, out_tok.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_greedy_accept rejected its arguments")
+    return out_n, out_tok
