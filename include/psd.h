@@ -41,7 +41,7 @@ typedef int32_t psd_status;
 #define PSD_ERR_SHAPE (-2)         /* a size is out of the supported range               */
 #define PSD_ERR_DTYPE (-3)         /* dtype is neither PSD_F32 nor PSD_BF16              */
 #define PSD_ERR_CAPACITY (-4)      /* the KV cache cannot take n_new more positions      */
-#define PSD_ERR_TEMPERATURE (-5)   /* temperature is not a finite number > 0             */
+#define PSD_ERR_TEMPERATURE (-5)   /* temperature is not a finite number >= 0            */
 #define PSD_ERR_WORKSPACE (-6)     /* workspace is NULL, misaligned or too small         */
 #define PSD_ERR_HIP (-7)           /* a HIP launch failed (see psd_last_hip_error)       */
 #define PSD_ERR_UNIMPLEMENTED (-8)
@@ -158,6 +158,12 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
  * The ratio test runs in fp32 (softmax statistics by wavefront reductions); the draw runs
  * in fp64 in a fixed summation order, so it is reproducible bit for bit.
  * gamma = 0 with n_p_rows = 1 is plain sampling from softmax(p_0 / temperature).
+ * temperature = 0 selects greedy verification (the other rule Sec. 3.1 names, compared with
+ * sampling in the paper's ablation on acceptance-length variance): x_j is kept iff it equals
+ * argmax_v p_logits[j][v] (lowest index among equal maxima, values compared as stored), the
+ * first mismatch is replaced by that argmax, a fully matching block emits the argmax of the
+ * bonus row or -1; q_logits and uniforms are not read and may be NULL, flags are 0, the
+ * result is exact.  gamma = 0 with n_p_rows = 1 is then the argmax of p_0.
  * Limits: 0 <= gamma <= 64, vocab >= 1, rows >= 0 (rows = 0 is a no-op). */
 size_t psd_spec_accept_workspace_bytes(int32_t rows, int32_t gamma, int32_t n_p_rows, int32_t vocab);
 psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int32_t *draft_tokens,

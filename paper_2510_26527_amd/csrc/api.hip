@@ -382,11 +382,14 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
     if (n_p_rows != gamma && n_p_rows != gamma + 1) return PSD_ERR_SHAPE;
     if (gamma == 0 && n_p_rows == 0) return PSD_ERR_SHAPE;
     if ((long)rows * (n_p_rows + gamma) > (1L << 24)) return PSD_ERR_SHAPE;
-    if (!(temperature > 0.f) || !std::isfinite(temperature)) return PSD_ERR_TEMPERATURE;
+    if (!(temperature >= 0.f) || !std::isfinite(temperature)) return PSD_ERR_TEMPERATURE;
+    const bool greedy = temperature == 0.f;              // reads neither q nor the uniforms
     if (rows == 0) return PSD_OK;
-    if (!p_logits || !uniforms || !out_accept_len || !out_token) return PSD_ERR_NULL;
-    if (gamma > 0 && (!q_logits || !draft_tokens)) return PSD_ERR_NULL;
-    if (p_seq_stride < (int64_t)n_p_rows * vocab || (gamma > 0 && q_seq_stride < (int64_t)gamma * vocab))
+    if (!p_logits || !out_accept_len || !out_token) return PSD_ERR_NULL;
+    if (!greedy && !uniforms) return PSD_ERR_NULL;
+    if (gamma > 0 && (!draft_tokens || (!greedy && !q_logits))) return PSD_ERR_NULL;
+    if (greedy) { q_logits = nullptr; q_seq_stride = 0; }
+    if (p_seq_stride < (int64_t)n_p_rows * vocab || (gamma > 0 && !greedy && q_seq_stride < (int64_t)gamma * vocab))
         return PSD_ERR_SHAPE;
     const size_t es = elem_size(dtype);
     if ((uintptr_t)p_logits % es || (uintptr_t)q_logits % es) return PSD_ERR_SHAPE;
@@ -401,7 +404,8 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
     a.p_stride = p_seq_stride; a.q_stride = q_seq_stride; a.temperature = temperature;
     a.out_n = out_accept_len; a.out_tok = out_token;
     (void)hipGetLastError();
-    launch_accept(a, vec, (hipStream_t)hip_stream);
+    if (greedy) launch_accept_greedy(a, vec, (hipStream_t)hip_stream);
+    else launch_accept(a, vec, (hipStream_t)hip_stream);
     return check_launch();
 }
 

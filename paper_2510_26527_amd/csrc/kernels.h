@@ -28,6 +28,8 @@ void accept_plan(int rows, int gamma, int n_p_rows, int V, int dtype, bool vec, 
 size_t accept_workspace_bytes(const AcceptArgs &a);
 void accept_bind_workspace(AcceptArgs *a, void *ws, int32_t *out_flags);
 void launch_accept(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
+// temperature 0: greedy verification (greedy.hip); reads p and x only, same workspace
+void launch_accept_greedy(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
 
 // ---------------------------------------------------------------- GEMMs (gemm.hip)
 // y[m][n] = sum_k x[m][k] * W[n][k]; W is up to three row-major [n_i][K] matrices whose

@@ -104,7 +104,8 @@ def test_spec_accept_validation(lib):
         qs = gamma * V if qs is None else qs
         return a(p, q, x, gamma, u, temp, n, t, rows, n_p, V, dtype, ps, qs, 0, w, wb, 0)
 
-    assert call(temp=0.0) == psd.PSD_ERR_TEMPERATURE
+    assert call(temp=-1.0) == psd.PSD_ERR_TEMPERATURE
+    assert call(temp=0.0, x=0) == psd.PSD_ERR_NULL          # greedy mode still needs the draft tokens
     assert call(temp=float("nan")) == psd.PSD_ERR_TEMPERATURE
     assert call(temp=float("inf")) == psd.PSD_ERR_TEMPERATURE
     assert call(dtype=3) == psd.PSD_ERR_DTYPE

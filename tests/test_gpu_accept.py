@@ -124,3 +124,43 @@ def test_strided_sequences_and_repeat_calls_are_deterministic():
     ok = (ofl & 1) == 0
     assert np.array_equal(outs[0][0][ok], on[ok]) and np.array_equal(outs[0][1][ok], otok[ok])
     assert all(np.array_equal(outs[0][0], o[0]) and np.array_equal(outs[0][1], o[1]) for o in outs[1:])
+
+
+# ---------------------------------------------------------------- greedy verification (temperature 0)
+@pytest.mark.parametrize("rows,gamma,n_p,V,dtype", [
+    (64, 8, 9, 32000, torch.bfloat16), (64, 8, 8, 32000, torch.bfloat16), (3, 5, 6, 1000, torch.float32),
+    (16, 16, 17, 152064, torch.float32), (1, 10, 11, 128256, torch.float32), (7, 4, 5, 4099, torch.bfloat16),
+    (5, 0, 1, 777, torch.float32), (2, 64, 65, 512, torch.bfloat16),
+])
+def test_greedy_matches_oracle_bit_exact(rows, gamma, n_p, V, dtype):
+    """Greedy rule: drafts are the argmax of a noisy copy of p, so blocks end at every position.
+    bf16 logits tie often (coarse values): the lowest-index rule is exercised on every row."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(rows * 1000 + gamma)
+    p = torch.empty((rows, n_p, V), dtype=torch.float32, device="cuda").normal_(0, 2, generator=gen).to(dtype)
+    noise = torch.empty((rows, gamma, V), dtype=torch.float32, device="cuda").normal_(0, 0.7, generator=gen)
+    x = torch.argmax(p[:, :gamma].float() + noise, dim=-1).to(torch.int32)
+    acc = runtime.Acceptor()
+    n, tok, fl = acc(p, None, x, torch.empty((rows, gamma + 1), dtype=torch.float32, device="cuda"), 0.0)
+    torch.cuda.synchronize()
+    on, otok = oacc.greedy_accept(p.float().cpu().numpy(), x.cpu().numpy())
+    assert np.array_equal(n.cpu().numpy(), on) and np.array_equal(tok.cpu().numpy(), otok)
+    assert int(fl.abs().sum()) == 0
+    if gamma >= 4 and rows >= 16:
+        assert 0 < (on < gamma).mean() and on.max() > 0
+
+
+def test_greedy_strided_rows_and_infinities():
+    V, gamma = 1000, 3
+    buf = torch.full((4, 6, V), float("-inf"), dtype=torch.float32, device="cuda")
+    buf[:, :, 17] = 1.0
+    buf[1, 2, 5] = 1.0                 # tie at position 2 of sequence 1: index 5 wins
+    buf[2, 1, 900] = float("inf")
+    p = buf[:, :4]                     # sequences 6*V apart, 4 rows used
+    x = torch.tensor([[17, 17, 17], [17, 17, 17], [17, 17, 17], [17, 3, 17]], dtype=torch.int32, device="cuda")
+    acc = runtime.Acceptor()
+    n, tok, _ = acc(p, None, x, torch.empty((4, gamma + 1), device="cuda"), 0.0)
+    torch.cuda.synchronize()
+    on, otok = oacc.greedy_accept(p.cpu().numpy(), x.cpu().numpy())
+    assert n.cpu().tolist() == on.tolist() == [3, 2, 1, 1]
+    assert tok.cpu().tolist() == otok.tolist() == [17, 5, 900, 17]

@@ -250,11 +250,100 @@ def test_workload4_full_three_level_chain(chain4_models, sigma):
     torch.cuda.synchronize()
     t_ar = e0.elapsed_time(e1) / 32
     rep.update(target_only_ms_per_token=t_ar, speedup_vs_target_only=t_ar * n_gen / (rep["eq2_ms"] + rep["accept_ms"]))
+    rep.update(tokens_per_target_forward_var_full_blocks=float(np.var([n + 1 for n in full])),
+               iid_var_at_expected_alpha=float(__import__("oracle.theory", fromlist=["x"]).variance_tokens(alpha, 11)))
     sd_tokens = np.std([n + 1 for n in full]) / max(len(full), 1) ** 0.5
     assert abs(np.mean([n + 1 for n in full]) - expect) < 5 * sd_tokens + 0.35
     os.makedirs("gpurun_out", exist_ok=True)
     with open(f"gpurun_out/chain4_sigma{sigma}.json", "w") as f:
         json.dump(rep, f, indent=1)
     print("workload 4 report", json.dumps({k: (round(v, 4) if isinstance(v, float) else v) for k, v in rep.items()}))
+    for lv in levels:
+        lv.close()
+
+
+def test_greedy_three_level_chain_reproduces_target_greedy_decoding():
+    """Temperature 0 at every level (greedy drafting, greedy verification): the chain must emit the
+    target's own greedy continuation, which the oracle computes with one-token forwards and argmax.
+    Steps where the oracle's top two logits are closer than 1e-3 end the comparison (none expected)."""
+    shapes = [synth.TINY_TARGET, synth.TINY_INTERMEDIATE, synth.TINY_DRAFT]
+    gammas = [None, 8, 4]
+    n_gen, max_len = 48, 192
+    glevels, olevels = _setup(shapes, [101, 102, 103], torch.float32, max_len, gammas)
+    prompt = synth.make_tokens(512, (32,), 7).tolist()
+    # the tapes are indexed but not read at temperature 0; disagreeing levels make many short blocks
+    tapes = [synth.make_tape(9, 0, 400, 16), synth.make_tape(9, 1, 4000, 16), synth.make_tape(9, 2, 20000, 1)[:, 0]]
+    g = gchain.Chain(glevels, gammas, tapes, 0.0)
+    out = g.generate(prompt, n_gen)
+    tgt = olevels[0]
+    tgt.forward(prompt[:-1])
+    ref, last = [], prompt[-1]
+    for _ in range(n_gen):
+        row = tgt.forward([last])[-1]
+        top = np.sort(row)[-2:]
+        if top[1] - top[0] < 1e-3:
+            break
+        last = int(np.argmax(row))
+        ref.append(last)
+    assert len(ref) >= n_gen // 2
+    assert out[:len(ref)] == ref
+    # random-init levels rarely agree on the argmax: most blocks end early, and the target still decides every token
+    print("greedy chain: target forwards", glevels[0].forwards, "accept lens", g.accept_lens[0])
+    for lv in glevels:
+        lv.close()
+    # a drafter that IS the target agrees everywhere: every block is accepted whole and the bonus token is used
+    g2l, _ = _setup([synth.TINY_TARGET, synth.TINY_TARGET], [101, 101], torch.float32, max_len, [None, 5])
+    g2 = gchain.Chain(g2l, [None, 5], [tapes[0], tapes[2]], 0.0)
+    out2 = g2.generate(prompt, n_gen)
+    assert out2[:len(ref)] == ref
+    assert all(n == k for n, k in zip(g2.accept_lens[0], g2.block_lens[0]))
+    assert g2l[0].forwards <= n_gen // 6 + 1
+    for lv in g2l:
+        lv.close()
+
+
+def test_workload4_greedy_verification_block_length_variance(chain4_models):
+    """The paper's ablation compares the acceptance-length variance of greedy verification and
+    speculative sampling.  The same full-size chain and harness at sigma = 0.25, run at temperature 0
+    (greedy drafting and greedy verification at every level): every decision is re-made by the oracle's
+    greedy rule, and mean and variance of the tokens per target forward are set beside the truncated
+    geometric law at the measured per-token match rate (Thm 3.3's i.i.d. reference)."""
+    from oracle import theory
+    from paper_2510_26527_amd import shim
+    import json, os
+    gammas, sigma = [None, 10, 6], 0.25
+    n_gen, n_prompt, max_len = 256, 256, 896
+    levels = [gchain.Level(chain4_models[0], max_len, 11), gchain.Level(chain4_models[1], max_len, 11),
+              gchain.Level(chain4_models[2], max_len, 7)]
+    prompt = synth.make_tokens(synth.LLAMA3_8B.vocab, (n_prompt,), 77).tolist()
+    tapes = [synth.make_tape(14, 0, 3 * n_gen, 16), synth.make_tape(14, 1, 6 * n_gen, 16),
+             synth.make_tape(14, 2, 30 * n_gen, 1)[:, 0]]
+    st = {"tested": [0, 0], "passed": [0, 0]}
+
+    def sink(ev):
+        if ev[0] == "accept":
+            _, i, k, x, u, n, tok, flags, p, q = ev
+            on, otok = oacc.greedy_accept(p.numpy()[None], x[None])
+            assert (n, tok) == (int(on[0]), int(otok[0])), f"level {i}: gpu {(n, tok)} oracle {(on[0], otok[0])}"
+            st["tested"][i] += min(n + 1, k)
+            st["passed"][i] += n
+        elif ev[0] == "sample":
+            assert ev[3] == int(np.argmax(ev[4].numpy()))
+
+    g = shim.AgreementShimChain(levels, gammas, tapes, sigma, noise_seed=5, temperature=0.0, max_len=max_len,
+                                trace=True, sink=sink)
+    out = g.generate(prompt, n_gen)
+    assert len(out) == n_gen
+    full = np.array([n + 1 for n, k in zip(g.accept_lens[0], g.block_lens[0]) if k == 10])
+    rate = st["passed"][0] / st["tested"][0]
+    rep = {"sigma": sigma, "rule": "greedy", "match_rate": [st["passed"][i] / st["tested"][i] for i in range(2)],
+           "target_forwards": levels[0].forwards, "tokens_per_target_forward_mean": float(full.mean()),
+           "tokens_per_target_forward_var": float(full.var()),
+           "iid_mean_at_rate": theory.expected_tokens(rate, 11), "iid_var_at_rate": theory.variance_tokens(rate, 11)}
+    os.makedirs("gpurun_out", exist_ok=True)
+    with open("gpurun_out/chain4_greedy_sigma0.25.json", "w") as f:
+        json.dump(rep, f, indent=1)
+    print("workload 4 greedy report", json.dumps(rep))
+    assert abs(full.mean() - rep["iid_mean_at_rate"]) < 5 * (rep["iid_var_at_rate"] / len(full)) ** 0.5 + 0.5
     for lv in levels:
         lv.close()
