@@ -29,13 +29,21 @@ def weight_stream_bytes(shape):
     return 2 * (s.n_layers * per_layer + s.vocab * s.d_model)
 
 
+def stream_kernel_bytes(shape):
+    """The share of weight_stream_bytes read by gemm_bf16_stream_kernel: the QKV, gate|up and lm_head
+    projections (the O and down projections run on the one-slot column kernel)."""
+    s = shape
+    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
+    return 2 * (s.n_layers * (s.d_model * (hd + 2 * kvd) + 2 * s.d_model * s.d_ffn) + s.vocab * s.d_model)
+
+
 def measured_traffic_bytes():
-    """HBM bytes per launch of the M <= 64 GEMM kernels as measured with rocprofv3 --pmc FETCH_SIZE /
+    """HBM bytes per launch of gemm_bf16_stream_kernel as measured with rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE (the committed summary under profiles/ records the commands); None if it is not there."""
     path = os.path.join(ROOT, "profiles", "bench_verify_step_llama2_7b_hbm_traffic.txt")
     try:
         for line in open(path):
-            if line.startswith("TRAFFIC_MB_PER_LAUNCH gemm_m_le_64"):
+            if line.startswith("TRAFFIC_MB_PER_LAUNCH gemm_bf16_stream_kernel"):
                 return float(line.split("=")[1]) * 1e6
     except OSError:
         pass
@@ -127,13 +135,23 @@ def main():
     psd.psd_profile_enable(0)
     kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * ms / c, "ms_per_step": ms / prof_steps}
                for k, (ms, c) in prof.items() if c}
+    # dominant kernel: gemm_bf16_stream_kernel (QKV, gate|up and lm_head projections: 65 launches per step)
     sk_ms, sk_n = prof["gemm_skinny"]
     w_bytes = weight_stream_bytes(shape)
-    achieved = w_bytes * prof_steps / (sk_ms * 1e-3) / 1e9
+    stream_bytes = stream_kernel_bytes(shape)
+    achieved = stream_bytes * prof_steps / (sk_ms * 1e-3) / 1e9
     roofline = {"kernel": "gemm_bf16_stream_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
-                "bytes_per_launch": w_bytes * prof_steps / sk_n, "avg_launch_us": 1e3 * sk_ms / sk_n,
+                "bytes_per_launch": stream_bytes * prof_steps / sk_n, "avg_launch_us": 1e3 * sk_ms / sk_n,
                 "launches_per_step": sk_n / prof_steps}
+    if "gemm_column" in prof and prof["gemm_column"][1]:
+        c_ms, c_n = prof["gemm_column"]
+        c_bytes = w_bytes - stream_bytes
+        roofline["other_gemm"] = {"kernel": "gemm_bf16_column_kernel (O and down projections with the residual add)",
+                                  "achieved": c_bytes * prof_steps / (c_ms * 1e-3) / 1e9, "unit": "GB/s",
+                                  "bytes_per_launch": c_bytes * prof_steps / c_n, "avg_launch_us": 1e3 * c_ms / c_n,
+                                  "launches_per_step": c_n / prof_steps}
+        roofline["all_weight_streaming_GB/s"] = w_bytes * prof_steps / ((sk_ms + c_ms) * 1e-3) / 1e9
     kv_bytes = 2 * shape.n_layers * shape.n_kv_heads * (ctx + gamma) * shape.d_head * 2
     step_floor_ms = (w_bytes + kv_bytes) / (HBM_PEAK_GBS * 1e9) * 1e3
 

@@ -207,7 +207,8 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_ACCEPT_STATS 11
 #define PSD_KIND_ACCEPT_EMIT 12      /* fp64 pass over the one position the draw reads */
 #define PSD_KIND_ACCEPT_LOCATE 13
-#define PSD_KIND_COUNT 14
+#define PSD_KIND_GEMM_COLUMN 14      /* bf16 one-slot GEMM with the residual epilogue, M <= 64 */
+#define PSD_KIND_COUNT 15
 psd_status psd_profile_enable(int32_t max_launches);
 psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind);
 

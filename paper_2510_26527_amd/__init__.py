@@ -51,7 +51,7 @@ _SIGNATURES = {
 }
 
 PSD_KIND_NAMES = ("embed", "rmsnorm", "gemm_f32", "gemm_skinny", "gemm_tiled", "gemm_reduce", "rope_append", "attn",
-                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_emit", "accept_locate")
+                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_emit", "accept_locate", "gemm_column")
 
 _lib = None
 

@@ -163,19 +163,19 @@ psd_status psd_model_pack(psd_model *m, void *packed_mem, size_t packed_bytes, v
     for (int l = 0; l < d.n_layers; ++l) {
         const void *qkv[3] = {m->layer(l, W_Q), m->layer(l, W_K), m->layer(l, W_V)};
         const int n_qkv[3] = {hd, kvd, kvd};
-        launch_gemm_pack(qkv, n_qkv, 3, d.d_model, base + off[4 * l + P_QKV], st);
+        launch_gemm_pack(qkv, n_qkv, 3, d.d_model, base + off[4 * l + P_QKV], false, st);
         const void *o[1] = {m->layer(l, W_O)};
         const int n_o[1] = {d.d_model};
-        launch_gemm_pack(o, n_o, 1, hd, base + off[4 * l + P_O], st);
+        launch_gemm_pack(o, n_o, 1, hd, base + off[4 * l + P_O], true, st);
         const void *gu[2] = {m->layer(l, W_GATE), m->layer(l, W_UP)};
         const int n_gu[2] = {d.d_ffn, d.d_ffn};
-        launch_gemm_pack(gu, n_gu, 2, d.d_model, base + off[4 * l + P_GU], st);
+        launch_gemm_pack(gu, n_gu, 2, d.d_model, base + off[4 * l + P_GU], false, st);
         const void *dn[1] = {m->layer(l, W_DOWN)};
-        launch_gemm_pack(dn, n_o, 1, d.d_ffn, base + off[4 * l + P_DOWN], st);
+        launch_gemm_pack(dn, n_o, 1, d.d_ffn, base + off[4 * l + P_DOWN], true, st);
     }
     const void *hw[1] = {m->lm_head()};
     const int n_v[1] = {d.vocab};
-    launch_gemm_pack(hw, n_v, 1, d.d_model, base + off[4 * d.n_layers], st);
+    launch_gemm_pack(hw, n_v, 1, d.d_model, base + off[4 * d.n_layers], false, st);
     const psd_status s = check_launch();
     if (s == PSD_OK) {
         m->packed = base;
@@ -220,7 +220,8 @@ namespace {
 struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
-    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, total;
+    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, total;
+    bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= 64)
 };
 
 ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound) {
@@ -232,14 +233,15 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.width_qkv = hd + 2 * kvd;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
     const int Ml = batch * n_logit_rows;
+    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= 64;
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
         if (mdl->packed && rows <= 64) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
     p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
-    p.sk_o = splits(M, hd, d.d_model, n_o, 1);
+    p.sk_o = p.folded ? 1 : splits(M, hd, d.d_model, n_o, 1);
     p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
-    p.sk_down = splits(M, d.d_ffn, d.d_model, n_o, 1);
+    p.sk_down = p.folded ? 1 : splits(M, d.d_ffn, d.d_model, n_o, 1);
     p.sk_head = Ml > 0 ? splits(Ml, d.d_model, d.vocab, n_v, 1) : 1;
     p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
     const size_t act = 4;                                    // activations are fp32 for both dtypes
@@ -254,10 +256,11 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     auto need = [&](int sk, int rows, int N) { const size_t b = (size_t)sk * rows * N * 4; if (b > part) part = b; };
     need(p.sk_qkv, M, p.width_qkv); need(p.sk_o, M, d.d_model); need(p.sk_gu, M, 2 * d.d_ffn);
     need(p.sk_down, M, d.d_model);
-    if (p.sk_head > 1) need(p.sk_head, Ml, d.vocab);             // a single split writes the logits in place
+    if (p.sk_head > 1 || p.folded) need(p.sk_head, Ml, d.vocab);  // else a single split writes the logits in place
     p.off_partial = take(part);
     p.off_po = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * d.d_head * 4 : 0);
     p.off_pml = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * 2 * 4 : 0);
+    p.off_sumsq = take(p.folded ? (size_t)(d.d_model / 16) * M * 4 : 0);
     p.total = off;
     return p;
 }
@@ -325,12 +328,37 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         g.pack_tiles = gemm_pack_tiles(g.n, g.nseg);
         launch_gemm(d.dtype, g, st);
     };
-    launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, M, d.d_model, d.vocab, d.rms_eps, st);
+    // Folded mode: no RMSNorm kernel runs.  The projections that read the residual stream multiply it by
+    // the norm gain while loading it, the kernels that consume their output multiply by the row scale
+    // rsqrt(mean x^2 + eps), and the projections that write the residual stream add into it and leave
+    // per-16-column sums of squares behind (one slab of M floats per block).
+    float *sumsq = (float *)(ws + p.off_sumsq);
+    const int col_tiles = d.d_model / 16;
+    RowScale rs{nullptr, 0, 1.0f / (float)d.d_model, d.rms_eps};
+    if (p.folded) rs.sumsq = sumsq;
+    const float *act = xn;     // what QKV / gate|up / lm_head read: rmsnorm(x) * gain, or x * gain when folded
+    auto resid_gemm = [&](const float *xin, int K, const void *w, int sk, const void *wpack, const void *next_gain) {
+        if (p.folded) {
+            GemmArgs g{};
+            g.wpack = wpack; g.x = xin; g.x_rows_per_group = M; g.w[0] = w; g.n[0] = d.d_model; g.nseg = 1;
+            g.M = M; g.K = K; g.N = d.d_model; g.splitk = 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
+            g.x_resid = x; g.xg_out = xn; g.gain = next_gain; g.sumsq_out = sumsq;
+            launch_gemm(d.dtype, g, st);
+            rs.tiles = col_tiles;
+        } else {
+            gemm(xin, M, K, w, d.d_model, nullptr, 0, nullptr, 0, sk, partial, wpack);
+            launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, st);
+        }
+    };
+    launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, p.folded ? sumsq : nullptr, M, d.d_model,
+                      d.vocab, d.rms_eps, st);
+    rs.tiles = 1;
     for (int l = 0; l < d.n_layers; ++l) {
-        gemm(xn, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial, m->pack(l, P_QKV));
+        gemm(act, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial,
+             m->pack(l, P_QKV));
         char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
-        launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, q, kl, vl, kv->lens, B, n_new, d.n_q_heads, d.n_kv_heads,
-                                  d.d_head, kv->max_len, d.rope_theta, st);
+        launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, rs, q, kl, vl, kv->lens, B, n_new, d.n_q_heads,
+                                  d.n_kv_heads, d.d_head, kv->max_len, d.rope_theta, st);
         AttnArgs a{};
         a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn;
         a.B = B; a.R = n_new; a.h_q = d.n_q_heads; a.h_kv = d.n_kv_heads; a.d_h = d.d_head; a.max_len = kv->max_len;
@@ -338,24 +366,25 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         a.splits = p.attn_splits;
         launch_attention(d.dtype, a, st);
 
-        gemm(attn, M, hd, m->layer(l, W_O), d.d_model, nullptr, 0, nullptr, 0, p.sk_o, partial, m->pack(l, P_O));
-        launch_reduce_residual_norm(d.dtype, partial, p.sk_o, x, m->layer(l, W_FFN_NORM), xn, M, d.d_model, d.rms_eps, st);
-        gemm(xn, M, d.d_model, m->layer(l, W_GATE), d.d_ffn, m->layer(l, W_UP), d.d_ffn, nullptr, 0, p.sk_gu, partial, m->pack(l, P_GU));
-        launch_reduce_swiglu(partial, p.sk_gu, h, M, d.d_ffn, st);
-        gemm(h, M, d.d_ffn, m->layer(l, W_DOWN), d.d_model, nullptr, 0, nullptr, 0, p.sk_down, partial, m->pack(l, P_DOWN));
-        launch_reduce_residual_norm(d.dtype, partial, p.sk_down, x, norm_gain(l + 1), xn, M, d.d_model, d.rms_eps, st);
+        resid_gemm(attn, hd, m->layer(l, W_O), p.sk_o, m->pack(l, P_O), m->layer(l, W_FFN_NORM));
+        gemm(act, M, d.d_model, m->layer(l, W_GATE), d.d_ffn, m->layer(l, W_UP), d.d_ffn, nullptr, 0, p.sk_gu, partial,
+             m->pack(l, P_GU));
+        launch_reduce_swiglu(partial, p.sk_gu, rs, h, M, d.d_ffn, st);
+        resid_gemm(h, d.d_ffn, m->layer(l, W_DOWN), p.sk_down, m->pack(l, P_DOWN), norm_gain(l + 1));
     }
     if (n_logit_rows > 0) {
-        // lm_head on the last n_logit_rows rows of every sequence: xn already holds the final norm
+        // lm_head on the last n_logit_rows rows of every sequence (unfolded: xn already holds the final norm)
         GemmArgs hg{};
-        hg.x = xn; hg.x_rows_per_group = n_logit_rows; hg.x_group_stride = n_new; hg.x_group_offset = n_new - n_logit_rows;
+        hg.x = act; hg.x_rows_per_group = n_logit_rows; hg.x_group_stride = n_new; hg.x_group_offset = n_new - n_logit_rows;
         hg.w[0] = m->lm_head(); hg.n[0] = d.vocab; hg.nseg = 1;
         hg.M = B * n_logit_rows; hg.K = d.d_model; hg.N = d.vocab;
         hg.wpack = hg.M <= 64 ? m->pack_head() : nullptr;
         hg.pack_tiles = gemm_pack_tiles(hg.n, 1);
         hg.splitk = p.sk_head;
-        hg.partial = p.sk_head > 1 ? partial : logits_out_dev;
-        hg.reduced = p.sk_head > 1 ? logits_out_dev : nullptr;
+        const bool two_step = p.sk_head > 1 || p.folded;
+        hg.partial = two_step ? partial : logits_out_dev;
+        hg.reduced = two_step ? logits_out_dev : nullptr;
+        if (p.folded) { hg.scale = rs; hg.scale_rows = M; }
         launch_gemm(d.dtype, hg, st);
     }
     launch_advance_lens(kv->lens, B, n_new, kv->max_len, st);

@@ -85,20 +85,37 @@ __device__ __forceinline__ TileRef find_tile(const GemmArgs &g, int tile, int ti
     return t;
 }
 
+// 8 consecutive activations of one row (zeros for a row past M)
+__device__ __forceinline__ f32x8 load_act8(const float *xrow, int k, bool valid) {
+    return valid ? load_f32x8(xrow + k) : f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+}
+
 __device__ __forceinline__ void store_out(const GemmArgs &g, int ks, int m, int col, float v) {
     g.partial[((size_t)ks * g.M + m) * g.N + col] = v;
 }
 
 
 
+// reduced[m][:] = (sum over splits, in split order) * r_m; one row per blockIdx.y
 __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs g) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)g.M * g.N) return;
-    const size_t m = idx / g.N, col = idx % g.N;
+    __shared__ float red[4];
+    const int m = blockIdx.y;
+    float sc = 1.0f;
+    if (g.scale.sumsq) {
+        const size_t src = x_row(g, m);
+        float v = 0.f;
+        for (int t = threadIdx.x; t < g.scale.tiles; t += 256) v += g.scale.sumsq[(size_t)t * g.scale_rows + src];
+        v = wave_sum(v);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        sc = 1.0f / sqrtf((((red[0] + red[1]) + red[2]) + red[3]) * g.scale.inv_d + g.scale.eps);
+    }
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col >= g.N) return;
+    const size_t idx = (size_t)m * g.N + col;
     float v = 0.f;
     for (int ks = 0; ks < g.splitk; ++ks) v += g.partial[(size_t)ks * g.M * g.N + idx];
-    (void)m; (void)col;
-    g.reduced[idx] = v;
+    g.reduced[idx] = v * sc;
 }
 
 // ------------------------------------------------------------------------------ bf16 skinny
@@ -169,8 +186,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
             bf16x8 bh[MT], bl[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                f32x8 xv = load_f32x8(xp[mt] + kk + (q >> 1) * 64 + (q & 1) * 8);
-                if (!xvalid[mt]) xv = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                const int k = kk + (q >> 1) * 64 + (q & 1) * 8;
+                const f32x8 xv = load_act8(xp[mt], k, xvalid[mt]);
                 split_bf16(xv, &bh[mt], &bl[mt]);
             }
             // hi parts over all accumulators, then lo parts: no back-to-back MFMAs on one accumulator
@@ -291,8 +308,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g) {
             bf16x8 bh[MT], bl[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                f32x8 xv = load_f32x8(xp[mt] + kk + (q >> 1) * 64 + (q & 1) * 8);
-                if (!xvalid[mt]) xv = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                const int k = kk + (q >> 1) * 64 + (q & 1) * 8;
+                const f32x8 xv = load_act8(xp[mt], k, xvalid[mt]);
                 split_bf16(xv, &bh[mt], &bl[mt]);
             }
 #pragma unroll
@@ -350,6 +367,134 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g) {
         if (u + 1 < u1) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) a_cur[j] = a_nxt[j];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ bf16 one-slot column kernel
+// For the projections that write the residual stream (N = d_model): one block per 16 output columns over
+// the whole K range, its wavefronts (sixteen for up to 16 rows, eight above: registers) on different K ranges, added through LDS in wavefront order.
+// Every output element has a single owner, so the block finishes the job itself: x_resid[m][n] += y[m][n],
+// xg_out[m][n] = x_resid[m][n] * gain_next[n] (the operand of the next projection, RMSNorm gain folded in),
+// and the sum of squares of the updated 16 columns per row goes to sumsq_out, from which the consumer of the
+// next projection derives the RMSNorm scale.  No partial slots, no reduce kernel, no norm kernel.
+// Weights are packed strip-major for this kernel (gemm_pack_strip_kernel): strip (16 rows) x K step is 4 KB
+// = 4 slots of 1 KB in lane order, all K steps of a strip contiguous, so a block streams one contiguous
+// range and a wavefront a contiguous part of it, 16 KB in flight at a time.
+constexpr int kColDepth = 4;                       // K steps loaded per round
+constexpr int kStripVec = 16 * kSkinnyStepK * 2 / 16;   // 16-byte vectors per (strip, step)
+
+__global__ __launch_bounds__(256) void gemm_pack_strip_kernel(const uint16_t *W, int N, int K, u32x4 *dst) {
+    const size_t vec = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int ns = K / kSkinnyStepK;
+    const size_t strips = (size_t)((N + kSkinnyRows - 1) / kSkinnyRows) * 4;
+    if (vec >= strips * ns * kStripVec) return;
+    const size_t strip = vec / ((size_t)ns * kStripVec);
+    const int rem = (int)(vec % ((size_t)ns * kStripVec));
+    const int step = rem / kStripVec, q = (rem % kStripVec) >> 6, lane = rem & 63;
+    const int i = lane & 15, gq = lane >> 4;
+    const size_t row = strip * 16 + i;
+    const int k = step * kSkinnyStepK + (q >> 1) * 64 + gq * 16 + (q & 1) * 8;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (row < (size_t)N) v = *reinterpret_cast<const u32x4 *>(W + row * K + k);
+    dst[vec] = v;
+}
+
+template <int MT, int kColWaves>
+__global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmArgs g) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, gq = lane >> 4;
+    const int K = g.K, ns = K / kSkinnyStepK;
+    const int s0 = wave * ns / kColWaves, s1 = (wave + 1) * ns / kColWaves;
+
+    // the epilogue's operands, fetched before the main loop: thread t < 256 owns column n = t & 15 of rows mm = t >> 4
+    const int en = threadIdx.x & 15, emm = threadIdx.x >> 4;
+    const int ecol = blockIdx.x * 16 + en;
+    float e_res[MT], e_gain = 1.0f;
+    if (threadIdx.x < 256 && ecol < g.N) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int tok = mt * 16 + emm;
+            e_res[mt] = tok < g.M ? g.x_resid[(size_t)tok * g.N + ecol] : 0.f;
+        }
+        if (g.gain) e_gain = bf16_bits_to_f32(((const uint16_t *)g.gain)[ecol]);
+    }
+
+    const float *xp[MT];
+    bool xvalid[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int tok = mt * 16 + i;
+        xvalid[mt] = tok < g.M;
+        xp[mt] = g.x + x_row(g, min(tok, g.M - 1)) * K + gq * 16;
+    }
+    f32x4 acc[2][MT];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[h][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const u32x4 *wbase = reinterpret_cast<const u32x4 *>(g.wpack) + (size_t)blockIdx.x * ns * kStripVec + lane;
+    for (int step = s0; step < s1; step += kColDepth) {
+        u32x4 a[kColDepth * 4];
+#pragma unroll
+        for (int j = 0; j < kColDepth; ++j)
+            if (step + j < s1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    a[j * 4 + q] = __builtin_nontemporal_load(wbase + (size_t)(step + j) * kStripVec + q * 64);
+            }
+#pragma unroll
+        for (int j = 0; j < kColDepth; ++j) {
+            if (step + j >= s1) break;
+            f32x8 xv[4][MT];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    xv[q][mt] = load_act8(xp[mt], (step + j) * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid[mt]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bf16x8 aw = __builtin_bit_cast(bf16x8, a[j * 4 + q]);
+                bf16x8 bh[MT], bl[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) split_bf16(xv[q][mt], &bh[mt], &bl[mt]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[q & 1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh[mt], acc[q & 1][mt], 0, 0, 0);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[q & 1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl[mt], acc[q & 1][mt], 0, 0, 0);
+            }
+        }
+    }
+
+    // acc[.][mt][v] = y[token mt*16 + i][column 4*gq + v of the strip] over this wavefront's K steps
+    __shared__ float red[kColWaves][16][17];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if (mt) __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][4 * gq + v][i] = acc[0][mt][v] + acc[1][mt][v];
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            const int tok = mt * 16 + emm;
+            float v = 0.f, sq = 0.f;
+#pragma unroll
+            for (int w = 0; w < kColWaves; ++w) v += red[w][en][emm];
+            if (tok < g.M && ecol < g.N) {
+                const size_t o = (size_t)tok * g.N + ecol;
+                v += e_res[mt];
+                g.x_resid[o] = v;
+                if (g.xg_out) g.xg_out[o] = v * e_gain;
+                sq = v * v;
+            }
+            // the 16 columns of one row sit in 16 consecutive lanes
+            sq += __shfl_xor(sq, 8, 64);
+            sq += __shfl_xor(sq, 4, 64);
+            sq += __shfl_xor(sq, 2, 64);
+            sq += __shfl_xor(sq, 1, 64);
+            if (en == 0 && tok < g.M) g.sumsq_out[(size_t)blockIdx.x * g.M + tok] = sq;
         }
     }
 }
@@ -510,12 +655,15 @@ size_t gemm_pack_bytes(const int *n, int nseg, int K) {
     return (size_t)tiles_of(n, nseg, kSkinnyRows) * (K / kSkinnyStepK) * kUnitBytes;
 }
 
-void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, hipStream_t stream) {
+void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, bool strip_major, hipStream_t stream) {
     char *out = (char *)dst;
     for (int s = 0; s < nseg; ++s) {
         const size_t units = (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * (K / kSkinnyStepK);
         const size_t vecs = units * kUnitVec;
-        launch_kernel(gemm_pack_kernel, (unsigned)((vecs + 255) / 256), 256, 0, stream, (const uint16_t *)w[s], n[s], K, (u32x4 *)out);
+        if (strip_major)
+            launch_kernel(gemm_pack_strip_kernel, (unsigned)((vecs + 255) / 256), 256, 0, stream, (const uint16_t *)w[s], n[s], K, (u32x4 *)out);
+        else
+            launch_kernel(gemm_pack_kernel, (unsigned)((vecs + 255) / 256), 256, 0, stream, (const uint16_t *)w[s], n[s], K, (u32x4 *)out);
         out += units * kUnitBytes;
     }
 }
@@ -555,6 +703,15 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         launch_kernel(gemm_f32_kernel, (g.N + 3) / 4, 256, 0, stream, g);
         return;
     }
+    if (g.M <= 64 && g.wpack && g.x_resid) {
+        ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
+        const int grid = g.N / 16, mt = (g.M + 15) / 16;          // N = d_model is a multiple of 128
+        if (mt == 1) launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
+        else if (mt == 2) launch_kernel(gemm_bf16_column_kernel<2, 8>, grid, 512, 0, stream, g);
+        else if (mt == 3) launch_kernel(gemm_bf16_column_kernel<3, 8>, grid, 512, 0, stream, g);
+        else launch_kernel(gemm_bf16_column_kernel<4, 8>, grid, 512, 0, stream, g);
+        return;
+    }
     if (g.M <= 64 && g.wpack && gemm_use_stream(g.pack_tiles)) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         const int grid = gemm_stream_grid(g.pack_tiles, g.K);
@@ -589,10 +746,10 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         }
         launch_kernel(gemm_bf16_tiled_kernel, grid, 256, kTiledLds, stream, g);
     }
-    if (g.splitk > 1 && g.reduced) {
-        const unsigned blocks = (unsigned)(((size_t)g.M * g.N + 255) / 256);
+    if (g.reduced) {
+        const dim3 grid((unsigned)((g.N + 255) / 256), (unsigned)g.M);
         ScopedProf sp(PSD_KIND_GEMM_REDUCE, stream);
-        launch_kernel(gemm_splitk_reduce_kernel, blocks, 256, 0, stream, g);
+        launch_kernel(gemm_splitk_reduce_kernel, grid, 256, 0, stream, g);
     }
 }
 

@@ -34,6 +34,12 @@ void launch_accept_greedy(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
 // ---------------------------------------------------------------- GEMMs (gemm.hip)
 // y[m][n] = sum_k x[m][k] * W[n][k]; W is up to three row-major [n_i][K] matrices whose
 // outputs are concatenated along n (QKV, gate|up).
+// r_m from per-tile sums of squares: rsqrt(sum_t sumsq[t * M + m] * inv_d + eps); sumsq NULL: 1
+struct RowScale {
+    const float *sumsq;
+    int tiles;
+    float inv_d, eps;
+};
 struct GemmArgs {
     const float *x;               // fp32 activations, K contiguous; row m is read from source row
                                   //   (m / x_rows_per_group) * x_group_stride + x_group_offset + m % x_rows_per_group
@@ -46,7 +52,19 @@ struct GemmArgs {
     int pack_tiles;               //   its number of 64-row tiles
     float *partial;               // [splitk][M][N] fp32: split s holds its share of the K sum
     int splitk;
-    float *reduced;               // if non-NULL and splitk > 1: [M][N] <- sum over splits (logits)
+    float *reduced;               // if non-NULL: [M][N] <- sum over splits (logits), times the row scale if given
+    // -- bf16, M <= 64, packed weights only: RMSNorm folded into the projections around it -----------
+    // rmsnorm(x) W^T = r_m * ((x * gain) W^T) with r_m = rsqrt(mean_k x[m][k]^2 + eps).  The one-slot column
+    // kernel (selected by x_resid) adds its output into the residual stream x_resid [M][N], writes
+    // xg_out[m][n] = x_resid[m][n] * gain[n] (the operand of the next projection; gain = the next norm's)
+    // and sumsq_out[n / 16][m] = sum of x_resid[m][n]^2 over the block's 16 columns; the consumer of the next
+    // projection's output multiplies by r_m (RowScale).
+    float *x_resid;
+    float *xg_out;
+    const void *gain;             // [N] bf16
+    float *sumsq_out;             // [N/16][M]
+    RowScale scale;               // applied when writing `reduced` (row = the source row of m)
+    int scale_rows;               //   rows per tile slab of scale.sumsq
 };
 int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg);
 // repacked weights for the M <= 64 path
@@ -56,7 +74,8 @@ int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots
 bool gemm_use_stream(int tiles);
 int gemm_stream_grid(int tiles, int K);
 int gemm_stream_slots(int tiles, int K);
-void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, hipStream_t stream);
+// strip_major: the layout of the one-slot column kernel (projections with N = d_model)
+void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, bool strip_major, hipStream_t stream);
 void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention (attention.hip)
@@ -76,19 +95,19 @@ int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int le
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- row-wise kernels (rowwise.hip)
-// x = embed[token]; xn = rmsnorm(x) * gain
+// x = embed[token]; then xn = rmsnorm(x) * gain, or (sumsq_out non-NULL) xn = x * gain and sumsq_out[m] = sum_k x[m][k]^2
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       int M, int d, int vocab, float eps, hipStream_t stream);
+                       float *sumsq_out, int M, int d, int vocab, float eps, hipStream_t stream);
 // qkv = sum over splits of partial [S][M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended
 // to the cache (model dtype)
-void launch_reduce_rope_append(int dtype, const float *partial, int S, float *q_out, void *k_cache, void *v_cache,
-                               const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
-                               float theta, hipStream_t stream);
+void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,
+                               void *v_cache, const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h,
+                               int max_len, float theta, hipStream_t stream);
 // x += sum over splits of partial [S][M][d]; xn = rmsnorm(x) * gain
 void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
                                  int M, int d, float eps, hipStream_t stream);
 // h = silu(g) * u with [g | u] = sum over splits of partial [S][M][2f]
-void launch_reduce_swiglu(const float *partial, int S, float *h, int M, int f, hipStream_t stream);
+void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, hipStream_t stream);
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream);
 void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B,
                      hipStream_t stream);

@@ -36,7 +36,8 @@ __device__ __forceinline__ f32x4 load_row4(const uint16_t *row, int i4) { return
 template <typename TW, bool EMBED>
 __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *embed, const int32_t *tokens, int vocab,
                                                                     const float *partial, int S, size_t split_stride,
-                                                                    float *x, const TW *gain, float *xn, int d, float eps) {
+                                                                    float *x, const TW *gain, float *xn, float *sumsq_out,
+                                                                    int d, float eps) {
     __shared__ float red[4];
     const int m = blockIdx.x, tid = threadIdx.x, n4 = d >> 2;
     f32x4 v[kMaxV4];
@@ -96,7 +97,11 @@ __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *em
         }
     }
     const float tot = block_sum4(ss, red);
-    const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+    float scale = 1.0f / sqrtf(tot / (float)d + eps);
+    if (sumsq_out) {                       // the norm scale is applied by the consumer of the next projection
+        if (tid == 0) sumsq_out[m] = tot;
+        scale = 1.0f;
+    }
     f32x4 *orow = reinterpret_cast<f32x4 *>(xn + (size_t)m * d);
 #pragma unroll
     for (int j = 0; j < kMaxV4; ++j) {
@@ -111,12 +116,16 @@ __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *em
 // owns the rotation pair (i, i + d_h/2); the angle position * theta^(-2i/d_h) is evaluated in fp64.
 template <typename TC>
 __global__ __launch_bounds__(64) void reduce_rope_append_kernel(const float *partial, int S, size_t split_stride,
-                                                                float *q_out, TC *k_cache, TC *v_cache,
+                                                                RowScale rs, float *q_out, TC *k_cache, TC *v_cache,
                                                                 const int32_t *lens, int R, int h_q, int h_kv, int d_h,
                                                                 int max_len, float theta) {
     const int m = blockIdx.x, slot = blockIdx.y, b = m / R, r = m % R;
     const int pos = lens[b] + r;
     if (pos >= max_len) return;            // capacity was checked on the host; never write outside
+    // the sums of squares first, the projection's partials next, the reduction after both are in flight
+    float ssq = 0.f;
+    if (rs.sumsq)
+        for (int t = threadIdx.x; t < rs.tiles; t += 64) ssq += rs.sumsq[(size_t)t * gridDim.x + m];
     const int half = d_h / 2;
     const int width = (h_q + 2 * h_kv) * d_h;
     const float *src = partial + (size_t)m * width + (size_t)slot * d_h;
@@ -132,13 +141,16 @@ __global__ __launch_bounds__(64) void reduce_rope_append_kernel(const float *par
         for (; sp < S; ++sp) a += src[sp * split_stride + e];
         return a;
     };
+    auto scale_of = [&]() { return rs.sumsq ? 1.0f / sqrtf(wave_sum(ssq) * rs.inv_d + rs.eps) : 1.0f; };
     if (slot < h_q + h_kv) {
+        const float r1 = i < half ? value(i) : 0.f, r2 = i < half ? value(half + i) : 0.f;
+        const float sc = scale_of();
         if (i >= half) return;
         const double inv_freq = exp2(-2.0 * (double)i / (double)d_h * log2((double)theta));
         double sn, cs;
         sincos((double)pos * inv_freq, &sn, &cs);
         const float c = (float)cs, s = (float)sn;
-        const float x1 = value(i), x2 = value(half + i);
+        const float x1 = r1 * sc, x2 = r2 * sc;
         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
         if (slot < h_q) {
             float *dst = q_out + ((size_t)m * h_q + slot) * d_h;
@@ -152,28 +164,38 @@ __global__ __launch_bounds__(64) void reduce_rope_append_kernel(const float *par
     } else {
         // V is stored transposed: v_cache[b][h][d][pos]
         const int h = slot - h_q - h_kv;
-        for (int dd = i; dd < d_h; dd += 64)
-            store_elem(v_cache, (((size_t)b * h_kv + h) * d_h + dd) * max_len + pos, value(dd));
+        const float v0 = i < d_h ? value(i) : 0.f, v1 = i + 64 < d_h ? value(i + 64) : 0.f;     // d_h <= 128
+        const float sc = scale_of();
+        if (i < d_h) store_elem(v_cache, (((size_t)b * h_kv + h) * d_h + i) * max_len + pos, v0 * sc);
+        if (i + 64 < d_h) store_elem(v_cache, (((size_t)b * h_kv + h) * d_h + i + 64) * max_len + pos, v1 * sc);
     }
 }
 
-// h = silu(g) * u, four columns per thread; [g | u] arrive as split-K partials of the gate|up projection
-__global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float *partial, int S, size_t split_stride, float *h,
-                                                            int M, int f) {
-    const size_t idx4 = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int f4 = f >> 2;
-    if (idx4 >= (size_t)M * f4) return;
-    const size_t m = idx4 / f4, j4 = idx4 % f4;
+// h = silu(g) * u, four columns per thread, one row per blockIdx.y; [g | u] arrive as split-K partials of
+// the gate|up projection
+__global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float *partial, int S, size_t split_stride, RowScale rs,
+                                                            float *h, int M, int f) {
+    __shared__ float red[4];
+    const int m = blockIdx.y, f4 = f >> 2;
+    float ssq = 0.f;
+    if (rs.sumsq)
+        for (int t = threadIdx.x; t < rs.tiles; t += 256) ssq += rs.sumsq[(size_t)t * M + m];
+    const int j4 = blockIdx.x * 256 + threadIdx.x;
     f32x4 g = f32x4{0.f, 0.f, 0.f, 0.f}, u = g;
-    for (int sp = 0; sp < S; ++sp) {
-        const f32x4 *row = reinterpret_cast<const f32x4 *>(partial + sp * split_stride + m * 2 * f);
-        g += row[j4];
-        u += row[f4 + j4];
-    }
+    if (j4 < f4)
+        for (int sp = 0; sp < S; ++sp) {
+            const f32x4 *row = reinterpret_cast<const f32x4 *>(partial + sp * split_stride + (size_t)m * 2 * f);
+            g += row[j4];
+            u += row[f4 + j4];
+        }
+    const float sc = rs.sumsq ? 1.0f / sqrtf(block_sum4(ssq, red) * rs.inv_d + rs.eps) : 1.0f;
+    if (j4 >= f4) return;
+    g *= sc;
+    u *= sc;
     f32x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
-    reinterpret_cast<f32x4 *>(h)[idx4] = o;
+    reinterpret_cast<f32x4 *>(h + (size_t)m * f)[j4] = o;
 }
 
 __global__ void advance_lens_kernel(int32_t *lens, int B, int delta, int max_len) {
@@ -194,14 +216,14 @@ __global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
 }  // namespace
 
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       int M, int d, int vocab, float eps, hipStream_t stream) {
+                       float *sumsq_out, int M, int d, int vocab, float eps, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_EMBED, stream);
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, true>, M, kRowThreads, 0, stream, (const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
-                                                                           x, (const uint16_t *)gain, xn, d, eps);
+                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps);
     else
         launch_kernel(residual_norm_kernel<float, true>, M, kRowThreads, 0, stream, (const float *)embed, tokens, vocab, nullptr, 0, 0, x,
-                                                                        (const float *)gain, xn, d, eps);
+                                                                        (const float *)gain, xn, sumsq_out, d, eps);
 }
 
 void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
@@ -210,30 +232,30 @@ void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *
     const size_t stride = (size_t)M * d;
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                            (const uint16_t *)gain, xn, d, eps);
+                                                                            (const uint16_t *)gain, xn, nullptr, d, eps);
     else
         launch_kernel(residual_norm_kernel<float, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                         (const float *)gain, xn, d, eps);
+                                                                         (const float *)gain, xn, nullptr, d, eps);
 }
 
-void launch_reduce_rope_append(int dtype, const float *partial, int S, float *q_out, void *k_cache, void *v_cache,
-                               const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h, int max_len,
-                               float theta, hipStream_t stream) {
+void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,
+                               void *v_cache, const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h,
+                               int max_len, float theta, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_ROPE_APPEND, stream);
     const size_t stride = (size_t)B * R * (h_q + 2 * h_kv) * d_h;
     const dim3 grid(B * R, h_q + 2 * h_kv);
     if (dtype == PSD_BF16)
-        launch_kernel(reduce_rope_append_kernel<uint16_t>, grid, 64, 0, stream, partial, S, stride, q_out, (uint16_t *)k_cache,
+        launch_kernel(reduce_rope_append_kernel<uint16_t>, grid, 64, 0, stream, partial, S, stride, rs, q_out, (uint16_t *)k_cache,
                                                                      (uint16_t *)v_cache, lens, R, h_q, h_kv, d_h, max_len, theta);
     else
-        launch_kernel(reduce_rope_append_kernel<float>, grid, 64, 0, stream, partial, S, stride, q_out, (float *)k_cache, (float *)v_cache,
+        launch_kernel(reduce_rope_append_kernel<float>, grid, 64, 0, stream, partial, S, stride, rs, q_out, (float *)k_cache, (float *)v_cache,
                                                                   lens, R, h_q, h_kv, d_h, max_len, theta);
 }
 
-void launch_reduce_swiglu(const float *partial, int S, float *h, int M, int f, hipStream_t stream) {
+void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_SWIGLU, stream);
-    const unsigned blocks = (unsigned)(((size_t)M * (f / 4) + 255) / 256);
-    launch_kernel(reduce_swiglu_kernel, blocks, 256, 0, stream, partial, S, (size_t)M * 2 * f, h, M, f);
+    const dim3 grid((unsigned)((f / 4 + 255) / 256), (unsigned)M);
+    launch_kernel(reduce_swiglu_kernel, grid, 256, 0, stream, partial, S, (size_t)M * 2 * f, rs, h, M, f);
 }
 
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream) {
