@@ -500,15 +500,21 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 }
 
 // ------------------------------------------------------------------------------ bf16 tiled
-// Block tile 128 rows of activations x 256 rows of W x 64 of K; four wavefronts in a 2 x 2 grid, each
-// 64 x 128 = 2 x 4 tiles of the 32x32x16 MFMA.  The activation tile is staged in LDS twice (hi and lo
-// bf16 parts), so the wide side of the wavefront tile is the weight side: per 16-wide K step a wavefront
-// reads 4 + 4 operands for 16 MFMAs.  Rows are padded to 72 elements (144 B): conflict-free 16-byte reads.
-// LDS is dynamic (73.7 KB per block, two blocks per CU).
-constexpr int kBM = 128, kBN = 256, kBK = 64, kLdsStride = 72;
-constexpr size_t kTiledLds = (size_t)(2 * kBM + kBN) * kLdsStride * sizeof(uint16_t);
+// Block tile 128 rows of activations x 32*NB rows of W x 64 of K; four wavefronts, each on 32 activation rows
+// x the whole tile width (1 x NB tiles of the 32x32x16 MFMA).  The activation tile is staged in LDS twice (hi
+// and lo bf16 parts): per 16-wide K step a wavefront reads 2 + NB operands for 2 NB MFMAs.  Rows are padded to
+// 72 elements (144 B): conflict-free 16-byte reads.  LDS is dynamic (at most 73.7 KB per block), two blocks
+// per CU: one block's staging and barriers overlap the other's MFMAs.
+// The tile width NB (4..8) and the K split are chosen per projection by the host so that the number of blocks
+// comes close to a multiple of the 512 block slots: with a fixed 256-wide tile the gate|up projection of a 7B
+// model at M = 256 has 296 blocks and leaves 42 % of the CUs idle.
+constexpr int kBM = 128, kBK = 64, kLdsStride = 72, kMaxNB = 8;
+constexpr size_t kTiledLds = (size_t)(2 * kBM + 32 * kMaxNB) * kLdsStride * sizeof(uint16_t);
 
+template <int NB>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
+    constexpr int BN = 32 * NB;
+    constexpr int WCH = BN * 8 / 256;                       // 16-byte chunks of the W tile per thread (BN x 64 bf16)
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_tiled[];
     uint16_t *Xh = lds_tiled;                               // activation tile, hi parts
     uint16_t *Xl = Xh + kBM * kLdsStride;                   // activation tile, lo parts
@@ -517,7 +523,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
     const int li = lane & 31, lg = lane >> 5;
     const int m_tiles = (g.M + kBM - 1) / kBM;
     const int mt = blockIdx.x % m_tiles;                 // M tiles of one W tile are neighbours: W is re-read from L2
-    const TileRef t = find_tile(g, blockIdx.x / m_tiles, kBN);
+    const TileRef t = find_tile(g, blockIdx.x / m_tiles, BN);
     const int seg_rows = g.n[t.seg];
     const uint16_t *W = (const uint16_t *)g.w[t.seg];
     const float *X = (const float *)g.x;
@@ -525,12 +531,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
     const int nk = K / kBK;
     const int k0 = (int)((long)blockIdx.y * nk / g.splitk), k1 = (int)((long)(blockIdx.y + 1) * nk / g.splitk);
     const int m_base = mt * kBM;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;   // this wavefront's 64 x 128 sub-tile
+    const int wm = wave * 32;                             // this wavefront's 32 activation rows
 
-    // global -> register staging per K tile: 4 x 8 fp32 of X and 8 x 8 bf16 of W per thread
+    // global -> register staging per K tile: 4 x 8 fp32 of X and NB x 8 bf16 of W per thread
     const float *xg[4];
-    const uint16_t *wg[8];
-    int xoff[4], woff[8];
+    const uint16_t *wg[WCH];
+    int xoff[4], woff[WCH];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
@@ -538,18 +544,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
         xoff[c] = row * kLdsStride + col;
     }
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
+    for (int c = 0; c < WCH; ++c) {
         const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
         wg[c] = W + (size_t)min(t.row0 + row, seg_rows - 1) * K + col;
         woff[c] = row * kLdsStride + col;
     }
     f32x8 xr[4];
-    u32x4 wr[8];
+    u32x4 wr[WCH];
     auto load_tiles = [&](int kt) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) xr[c] = load_f32x8(xg[c] + (size_t)kt * kBK);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) wr[c] = *reinterpret_cast<const u32x4 *>(wg[c] + (size_t)kt * kBK);
+        for (int c = 0; c < WCH; ++c) wr[c] = *reinterpret_cast<const u32x4 *>(wg[c] + (size_t)kt * kBK);
     };
     auto store_tiles = [&]() {
 #pragma unroll
@@ -560,16 +566,14 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
             *reinterpret_cast<bf16x8 *>(&Xl[xoff[c]]) = lo;
         }
 #pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = wr[c];
+        for (int c = 0; c < WCH; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = wr[c];
     };
 
-    f32x16 acc[2][4];
+    f32x16 acc[NB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
     if (k0 < k1) {
         load_tiles(k0);
@@ -580,43 +584,32 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
         if (kt + 1 < k1) load_tiles(kt + 1);
 #pragma unroll
         for (int ks = 0; ks < kBK / 16; ++ks) {
-            bf16x8 fa[2], fl[2], fb[4];
+            const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(&Xh[(wm + li) * kLdsStride + ks * 16 + lg * 8]);
+            const bf16x8 fl = *reinterpret_cast<const bf16x8 *>(&Xl[(wm + li) * kLdsStride + ks * 16 + lg * 8]);
+            bf16x8 fb[NB];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                fa[a] = *reinterpret_cast<const bf16x8 *>(&Xh[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
-                fl[a] = *reinterpret_cast<const bf16x8 *>(&Xl[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
-            }
+            for (int b = 0; b < NB; ++b)
+                fb[b] = *reinterpret_cast<const bf16x8 *>(&Ws[(b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                fb[b] = *reinterpret_cast<const bf16x8 *>(&Ws[(wn + b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
+            for (int b = 0; b < NB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[b], acc[b], 0, 0, 0);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[a], fb[b], acc[a][b], 0, 0, 0);
+            for (int b = 0; b < NB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[b], acc[b], 0, 0, 0);
         }
         __syncthreads();
         if (kt + 1 < k1) store_tiles();
         __syncthreads();
     }
-    // acc[a][b][v] = y[m_base + wm + a*32 + 8*(v/4) + 4*lg + v%4][row0 + wn + b*32 + li]
+    // acc[b][v] = y[m_base + wm + 8*(v/4) + 4*lg + v%4][row0 + b*32 + li]
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int b = 0; b < NB; ++b) {
+        const int row = t.row0 + b * 32 + li;
+        if (row >= seg_rows) continue;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int row = t.row0 + wn + b * 32 + li;
-            if (row >= seg_rows) continue;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m_base + wm + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                if (m < g.M) store_out(g, blockIdx.y, m, t.col0 + row, acc[a][b][v]);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int m = m_base + wm + 8 * (v >> 2) + 4 * lg + (v & 3);
+            if (m < g.M) store_out(g, blockIdx.y, m, t.col0 + row, acc[b][v]);
         }
+    }
 }
 
 int tiles_of(const int *n, int nseg, int rows) {
@@ -631,6 +624,26 @@ int tiles_of(const int *n, int nseg, int rows) {
 // (N = d_model projections) the K range of a tile is split over the four wavefronts of a block, added
 // through LDS, and over blocks (gemm_bf16_skinny_kernel), which keeps the partial slots few.
 bool gemm_use_stream(int tiles) { return tiles >= 128; }
+
+// Tile width (NB x 32 columns) and K split of the tiled kernel: the pair with the least estimated time: rounds
+// of 512 resident blocks x K tiles per block x the MFMA time of one K tile of two co-resident blocks (512 NB
+// cycles at the 45 % issue rate the kernel reaches), plus writing and re-reading one fp32 partial slot of
+// M x N per split at about 3 TB/s.
+static void tiled_choice(int M, int K, const int *n, int nseg, int *nb_out, int *sk_out) {
+    const int nk = K / kBK, m_tiles = (M + kBM - 1) / kBM;
+    long N = 0;
+    for (int s = 0; s < nseg; ++s) N += n[s];
+    const double slot_us = 2.0 * (double)M * (double)N * 4.0 / 3.0e6;
+    double best = 1e300;
+    *nb_out = kMaxNB; *sk_out = 1;
+    for (int nb = 4; nb <= kMaxNB; ++nb)
+        for (int sk = 1; sk <= 16 && (sk == 1 || nk / sk >= 4); ++sk) {
+            const long blocks = (long)tiles_of(n, nseg, 32 * nb) * m_tiles * sk;
+            const long rounds = (blocks + 511) / 512;
+            const double cost = rounds * (double)((nk + sk - 1) / sk) * 512.0 * nb / 2400.0 / 0.45 + sk * slot_us;
+            if (cost < best) { best = cost; *nb_out = nb; *sk_out = sk; }
+        }
+}
 
 int gemm_stream_grid(int tiles, int K) {
     const long U = (long)tiles * (K / kSkinnyStepK);
@@ -687,14 +700,9 @@ int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
         if (want > 16) want = 16;
         return want < 1 ? 1 : want;
     }
-    const int tiles = tiles_of(n, nseg, kBN) * ((M + kBM - 1) / kBM);
-    if (tiles >= 200) return 1;
-    int want = (256 + tiles / 2) / tiles;                 // about one block per CU
-    int cap = K / kBK / 4;
-    if (cap < 1) cap = 1;
-    if (want > cap) want = cap;
-    if (want > 16) want = 16;
-    return want < 1 ? 1 : want;
+    int nb, sk;
+    tiled_choice(M, K, n, nseg, &nb, &sk);
+    return sk;
 }
 
 void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
@@ -737,14 +745,24 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         }
     } else {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
-        dim3 grid(tiles_of(g.n, g.nseg, kBN) * ((g.M + kBM - 1) / kBM), g.splitk);
-        static bool lds_ok = false;                      // opt in once to more than 64 KB of dynamic LDS
-        if (!lds_ok) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_tiled_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTiledLds);
-            lds_ok = true;
-        }
-        launch_kernel(gemm_bf16_tiled_kernel, grid, 256, kTiledLds, stream, g);
+        int nb, sk;
+        tiled_choice(g.M, g.K, g.n, g.nseg, &nb, &sk);
+        if (sk != g.splitk) nb = kMaxNB;                  // the caller sized the partial slots for its own split
+        dim3 grid(tiles_of(g.n, g.nseg, 32 * nb) * ((g.M + kBM - 1) / kBM), g.splitk);
+        static bool lds_ok[kMaxNB + 1] = {};              // opt in once per instantiation to more than 64 KB of dynamic LDS
+        auto go = [&](auto kernel) {
+            if (!lds_ok[nb]) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)kTiledLds);
+                lds_ok[nb] = true;
+            }
+            launch_kernel(kernel, grid, 256, kTiledLds, stream, g);
+        };
+        if (nb == 4) go(gemm_bf16_tiled_kernel<4>);
+        else if (nb == 5) go(gemm_bf16_tiled_kernel<5>);
+        else if (nb == 6) go(gemm_bf16_tiled_kernel<6>);
+        else if (nb == 7) go(gemm_bf16_tiled_kernel<7>);
+        else go(gemm_bf16_tiled_kernel<8>);
     }
     if (g.reduced) {
         const dim3 grid((unsigned)((g.N + 255) / 256), (unsigned)g.M);
