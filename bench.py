@@ -60,6 +60,12 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten plain 1 GiB device-to-device copies (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--workload", choices=["verify", "stress", "chain"], default="verify",
+                    help="verify (default): configs[2] verify step + configs[1] acceptance, the headline line; "
+                         "stress: configs[4], 16 sequences x 16 rows of a Qwen2-7B-shaped model; "
+                         "chain: configs[3], the full-size three-level chain with the agreement harness")
+    ap.add_argument("--sigma", type=float, default=0.25, help="noise of the agreement harness (--workload chain)")
+    ap.add_argument("--tokens", type=int, default=512, help="tokens to generate (--workload chain)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
@@ -85,6 +91,11 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": "10 x copy of 1 GiB (reads 1 GiB, writes 1 GiB each)"}))
         return
+
+    if args.workload == "stress":
+        return stress_workload(args, dev)
+    if args.workload == "chain":
+        return chain_workload(args, dev)
 
     shape, gamma, ctx, max_len, temperature = synth.LLAMA2_7B, 8, 1024, 1088, 1.0
     w_cpu = synth.make_weights(shape, 3, torch.bfloat16)
@@ -219,6 +230,138 @@ def main():
         "accepted_this_step": accepted,
         "step_floor_ms_at_hbm_peak": step_floor_ms,
         "roofline": roofline, "cpu_baseline": cpu_baseline, "accept_kernel": accept, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+def stress_workload(args, dev):
+    """configs[4]: Qwen2-7B-shaped bf16 model, 16 independent sequences, 16 new rows each against 4096-token
+    caches, per-sequence acceptance against a synthetic drafter (q = p + N(0, 0.5^2)), on-device rollback."""
+    import torch
+    import paper_2510_26527_amd as psd
+    from paper_2510_26527_amd import runtime, synth
+    shape, B, gamma, ctx, max_len = synth.QWEN2_7B, 16, 16, 4096, 4160
+    w = synth.make_weights(shape, 5, torch.bfloat16, device=dev)
+    model = runtime.Model(shape, w, dev)
+    kv = runtime.KVCache(model, B, max_len)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(51)
+    kv.k.normal_(generator=gen)
+    kv.v.normal_(generator=gen)
+    kv.load([kv.k[l, :, :, :ctx] for l in range(shape.n_layers)],
+            [kv.v[l, :, :, :, :ctx].transpose(-1, -2) for l in range(shape.n_layers)], ctx)
+    tokens = torch.from_numpy(synth.make_tokens(shape.vocab, (B, gamma), 55)).to(dev)
+    p_buf = torch.empty((B, gamma, shape.vocab), dtype=torch.float32, device=dev)
+    base = torch.full((B,), ctx, dtype=torch.int32, device=dev)
+    acc = runtime.Acceptor(dev)
+    uniforms = synth.make_uniforms((B, gamma + 1), 56, dev)
+    runtime.forward(model, kv, tokens, logits_out=p_buf)
+    psd.psd_kv_truncate_to(kv.handle, ctx)
+    q_logits, draft = synth.make_draft_from_target(p_buf, 0.5, 57)
+    out = {}
+
+    def step():
+        runtime.forward(model, kv, tokens, logits_out=p_buf)
+        n, tok, fl = acc(p_buf, q_logits, draft, uniforms, 1.0)
+        psd.psd_kv_truncate(kv.handle, base, n, 1)
+        psd.psd_kv_truncate_to(kv.handle, ctx)
+        out["n"] = n
+
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    prof_steps = 3
+    psd.psd_profile_enable(3000 * prof_steps)
+    for _ in range(prof_steps):
+        step()
+    prof = psd.psd_profile_collect()
+    psd.psd_profile_enable(0)
+    kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * t / c, "ms_per_step": t / prof_steps}
+               for k, (t, c) in prof.items() if c}
+    s = shape
+    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
+    flops = 2.0 * B * gamma * (s.n_layers * (s.d_model * (hd + 2 * kvd) + hd * s.d_model + 3 * s.d_model * s.d_ffn)
+                               + s.vocab * s.d_model)
+    g_ms = prof["gemm_tiled"][0] / prof_steps
+    kv_bytes = 2.0 * s.n_layers * B * s.n_kv_heads * (ctx + gamma) * s.d_head * 2
+    a_ms = prof["attn"][0] / prof_steps
+    tf = flops / (g_ms * 1e-3) / 1e12
+    line = {
+        "metric": "stress verify-step tokens/s (Qwen2-7B shape, 16 sequences x gamma=16, ctx 4k)",
+        "value": B * gamma * 1e3 / ms, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[4]: Qwen2-7B-shaped random-init bf16, 16 sequences, gamma=16 new tokens each on "
+                               "4096-token N(0,1) caches, forward + per-sequence acceptance + KV rollback",
+                   "gamma": gamma, "n_new": gamma, "kv_len": ctx, "batch": B, "temperature": 1.0},
+        "accepted_mean": float(out["n"].float().mean().item()),
+        "roofline": {"kernel": "gemm_bf16_tiled_kernel", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": tf / 2500.0, "traffic": None, "flop_per_step": flops, "ms_per_step": g_ms,
+                     "note": "useful flops; activations enter as bf16 hi + lo pairs, so twice as many MFMAs are issued"},
+        "attention": {"kernel": "attn_mfma_wide_kernel", "bytes_per_step": kv_bytes, "ms_per_step": a_ms,
+                      "GB/s": kv_bytes / (a_ms * 1e-3) / 1e9},
+        "cpu_baseline": None, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+def chain_workload(args, dev):
+    """configs[3]: LLaMA3-8B-shaped target, 16-layer intermediate, one-layer draft sharing the target's embedding and
+    lm_head; 256-token prompt, gamma_draft 6, gamma_intermediate 10, temperature 1, agreement harness at --sigma."""
+    import torch
+    import paper_2510_26527_amd as psd
+    from paper_2510_26527_amd import chain as gchain
+    from paper_2510_26527_amd import costmodel, runtime, shim, synth
+    n_gen, n_prompt, max_len, gammas = args.tokens, 256, 256 + args.tokens + 128, [None, 10, 6]
+    max_len = (max_len + 63) // 64 * 64
+    tw = synth.make_weights(synth.LLAMA3_8B, 401, torch.bfloat16, device=dev)
+    mw = synth.make_weights(synth.CHAIN_INTERMEDIATE, 402, torch.bfloat16, device=dev)
+    dw = synth.make_weights(synth.CHAIN_DRAFT, 403, torch.bfloat16, device=dev,
+                            share={"embed": tw["embed"], "lm_head": tw["lm_head"]})
+    models = [runtime.Model(synth.LLAMA3_8B, tw, dev).pack(), runtime.Model(synth.CHAIN_INTERMEDIATE, mw, dev).pack(),
+              runtime.Model(synth.CHAIN_DRAFT, dw, dev).pack()]
+    levels = [gchain.Level(models[0], max_len, 11), gchain.Level(models[1], max_len, 11), gchain.Level(models[2], max_len, 7)]
+    prompt = synth.make_tokens(synth.LLAMA3_8B.vocab, (n_prompt,), 77).tolist()
+    tapes = [synth.make_tape(14, 0, 3 * n_gen, 16), synth.make_tape(14, 1, 6 * n_gen, 16),
+             synth.make_tape(14, 2, 30 * n_gen, 1)[:, 0]]
+    g = shim.AgreementShimChain(levels, gammas, tapes, args.sigma, noise_seed=5, temperature=1.0, max_len=max_len, timed=True)
+    t0 = time.perf_counter()
+    g.generate(prompt, n_gen)
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    rep = costmodel.chain_report(n_gen, [lv.forwards for lv in levels], [lv.time_ms for lv in levels], g.accept_ms)
+    # the target decoding alone, one token per forward, same kernels and cache length
+    tgt = levels[0]
+    at = n_prompt + n_gen // 2
+    psd.psd_kv_truncate_to(tgt.kv.handle, at)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for it in range(40):
+        if it == 8:
+            e0.record()
+        psd.psd_model_forward(tgt.model.handle, g.seq[at:at + 1], 1, tgt.kv.handle, tgt.rows[0:1], 1, tgt.ws)
+        psd.psd_kv_truncate_to(tgt.kv.handle, at)
+    e1.record()
+    torch.cuda.synchronize()
+    t_ar = e0.elapsed_time(e1) / 32
+    chain_ms = rep["eq2_ms"] + rep["accept_ms"]
+    line = {
+        "metric": "three-level chain tokens/s (LLaMA3-8B-shaped target, harness sigma %.2f)" % args.sigma,
+        "value": n_gen * 1e3 / chain_ms, "unit": "tokens/s", "n_gpus": 1, "steps": n_gen, "warmup": 0,
+        "ms_per_step": chain_ms / n_gen, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[3]: LLaMA3-8B-shaped target, 16-layer d=2048 intermediate, 1-layer draft, bf16 random "
+                               "init, 256-token prompt, gamma_draft 6, gamma_intermediate 10, temperature 1",
+                   "sigma": args.sigma, "tokens": n_gen},
+        "value_counts": "GPU time of the three models' forwards and the acceptance calls (Eq. 2 + acceptance); the harness's "
+                        "untimed target peeks and the host loop are excluded",
+        "report": rep, "tokens_per_target_forward": n_gen / rep["F"][0],
+        "target_only_ms_per_token": t_ar, "speedup_vs_target_only": t_ar * n_gen / chain_ms,
+        "harness": {"peeks": g.peeks, "peek_ms": g.peek_ms, "wall_ms": wall_ms}, "cpu_baseline": None,
     }
     print(json.dumps(line))
 

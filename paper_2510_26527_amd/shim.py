@@ -21,8 +21,12 @@ from paper_2510_26527_amd.chain import Chain
 
 
 class AgreementShimChain(Chain):
-    def __init__(self, levels, gammas, tapes, sigma, noise_seed=0, **kw):
+    def __init__(self, levels, gammas, tapes, sigma, noise_seed=0, noise_terms=None, **kw):
+        """noise_terms[i]: how many of the N_j vectors level i's rows carry (default i: each level one more than
+        the level above it; a two-level chain whose draft should sit as far from the target as the draft of a
+        three-level chain passes [0, 2])."""
         super().__init__(levels, gammas, tapes, **kw)
+        self.noise_terms = list(noise_terms) if noise_terms is not None else list(range(len(levels)))
         tgt = levels[0]
         self.sigma = float(sigma)
         self.noise_seed = int(noise_seed)
@@ -58,7 +62,7 @@ class AgreementShimChain(Chain):
         for r in range(n_logit_rows):
             pos = self.seq_len - n_logit_rows + r + 1            # index of the token row r predicts
             noise = self._noise(1, pos)
-            for j in range(2, i + 1):
+            for j in range(2, self.noise_terms[i] + 1):
                 noise = noise + self._noise(j, pos)
             torch.add(peek[r], noise, alpha=self.sigma, out=dst[r])
 

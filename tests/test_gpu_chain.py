@@ -347,3 +347,41 @@ def test_workload4_greedy_verification_block_length_variance(chain4_models):
     assert abs(full.mean() - rep["iid_mean_at_rate"]) < 5 * (rep["iid_var_at_rate"] / len(full)) ** 0.5 + 0.5
     for lv in levels:
         lv.close()
+
+
+def test_workload4_insertion_criterion_live(chain4_models):
+    """Thm 3.2 on measured numbers: the same target and draft (the draft two sigma-steps away from the target)
+    decoded as a two-level chain and as a three-level chain with the intermediate inserted.  Whether the
+    insertion pays off is read from the measured Eq. (2) times, and compared with what the theorem's two
+    conditions say when evaluated on the measured T and L."""
+    from paper_2510_26527_amd import shim
+    import json, os
+    sigma, n_gen, n_prompt, max_len = 0.25, 256, 256, 896
+    prompt = synth.make_tokens(synth.LLAMA3_8B.vocab, (n_prompt,), 77).tolist()
+
+    def run(models, gammas, rows, noise_terms):
+        levels = [gchain.Level(m, max_len, r) for m, r in zip(models, rows)]
+        tapes = [synth.make_tape(15, i, 4 * n_gen, 16) for i in range(len(models) - 1)]
+        tapes.append(synth.make_tape(15, 9, 12 * n_gen, 1)[:, 0])
+        g = shim.AgreementShimChain(levels, gammas, tapes, sigma, noise_seed=6, noise_terms=noise_terms,
+                                    temperature=1.0, max_len=max_len, timed=True)
+        g.generate(prompt, n_gen)
+        rep = costmodel.chain_report(n_gen, [lv.forwards for lv in levels], [lv.time_ms for lv in levels], g.accept_ms)
+        for lv in levels:
+            lv.close()
+        return rep
+
+    two = run([chain4_models[0], chain4_models[2]], [None, 6], [7, 7], [0, 2])
+    three = run(chain4_models, [None, 10, 6], [11, 11, 7], [0, 1, 2])
+    # notation of the theorem: M_i = target, M_{i+1} = draft, M_new = intermediate
+    T_i, T_next, T_new = two["T_ms"][0], two["T_ms"][1], three["T_ms"][1]
+    L_i, L_i_new, L_new = two["L"][0], three["L"][0], three["L"][1]
+    c1, c2, helps = costmodel.insertion_criterion(T_new, T_i, T_next, L_new, L_i, L_i_new, two["beta"])
+    measured_helps = three["eq2_ms"] + three["accept_ms"] < two["eq2_ms"] + two["accept_ms"]
+    rep = {"two_level": two, "three_level": three, "condition_1": c1, "condition_2": c2, "theorem_says_helps": helps,
+           "measured_helps": measured_helps}
+    os.makedirs("gpurun_out", exist_ok=True)
+    with open("gpurun_out/chain4_insertion.json", "w") as f:
+        json.dump(rep, f, indent=1)
+    print("insertion check", json.dumps(rep))
+    assert two["L"][0] > 1 and three["L"][0] > two["L"][0]        # the intermediate raises the target's acceptance length
