@@ -60,10 +60,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten plain 1 GiB device-to-device copies (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
-    ap.add_argument("--workload", choices=["verify", "stress", "chain"], default="verify",
+    ap.add_argument("--workload", choices=["verify", "stress", "chain", "sweep"], default="verify",
                     help="verify (default): configs[2] verify step + configs[1] acceptance, the headline line; "
                          "stress: configs[4], 16 sequences x 16 rows of a Qwen2-7B-shaped model; "
-                         "chain: configs[3], the full-size three-level chain with the agreement harness")
+                         "chain: configs[3], the full-size three-level chain with the agreement harness; "
+                         "sweep: the projections of a LLaMA2-7B-shaped layer at 8 ... 4096 rows")
     ap.add_argument("--sigma", type=float, default=0.25, help="noise of the agreement harness (--workload chain)")
     ap.add_argument("--tokens", type=int, default=512, help="tokens to generate (--workload chain)")
     args = ap.parse_args()
@@ -96,6 +97,8 @@ def main():
         return stress_workload(args, dev)
     if args.workload == "chain":
         return chain_workload(args, dev)
+    if args.workload == "sweep":
+        return sweep_workload(args, dev)
 
     shape, gamma, ctx, max_len, temperature = synth.LLAMA2_7B, 8, 1024, 1088, 1.0
     w_cpu = synth.make_weights(shape, 3, torch.bfloat16)
@@ -364,6 +367,54 @@ def chain_workload(args, dev):
         "harness": {"peeks": g.peeks, "peek_ms": g.peek_ms, "wall_ms": wall_ms}, "cpu_baseline": None,
     }
     print(json.dumps(line))
+
+
+def sweep_workload(args, dev):
+    """The four projections of LLaMA2-7B-shaped layers (plus a 32000-row lm_head) at M = 8 ... 4096 rows: one
+    forward of a two-layer model per M on an empty cache; GEMM time from the per-launch timers.  Up to 16 rows
+    the projections stream the weights (HBM-bound, GB/s); above, they run on the LDS-tiled MFMA kernel (TFLOP/s)."""
+    import torch
+    import paper_2510_26527_amd as psd
+    from paper_2510_26527_amd import runtime, synth
+    q = synth.LLAMA2_7B
+    shape = synth.Shape(2, q.d_model, q.n_q_heads, q.n_kv_heads, q.d_head, q.d_ffn, q.vocab, q.rope_theta)
+    w = synth.make_weights(shape, 3, torch.bfloat16, device=dev)
+    model = runtime.Model(shape, w, dev).pack()
+    s = shape
+    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
+    params = s.n_layers * (s.d_model * (hd + 2 * kvd) + hd * s.d_model + 3 * s.d_model * s.d_ffn) + s.vocab * s.d_model
+    rows = []
+    for M in (8, 16, 32, 64, 128, 256, 512, 1024, 4096):
+        max_len = (M + 63) // 64 * 64
+        kv = runtime.KVCache(model, 1, max_len)
+        toks = torch.from_numpy(synth.make_tokens(s.vocab, (1, M), M)).to(dev)
+        logits = torch.empty((1, M, s.vocab), dtype=torch.float32, device=dev)
+        for _ in range(2):
+            runtime.forward(model, kv, toks, logits_out=logits)
+            psd.psd_kv_truncate_to(kv.handle, 0)
+        reps = 5
+        psd.psd_profile_enable(200 * reps)
+        for _ in range(reps):
+            runtime.forward(model, kv, toks, logits_out=logits)
+            psd.psd_kv_truncate_to(kv.handle, 0)
+        torch.cuda.synchronize()
+        prof = psd.psd_profile_collect()
+        psd.psd_profile_enable(0)
+        g_ms = sum(prof[k][0] for k in ("gemm_skinny", "gemm_column", "gemm_tiled")) / reps
+        flops = 2.0 * M * params
+        rows.append({"M": M, "gemm_ms": g_ms, "TFLOP/s": flops / (g_ms * 1e-3) / 1e12,
+                     "frac_of_bf16_mfma_peak": flops / (g_ms * 1e-3) / 2.5e15,
+                     "weight_GB/s": 2.0 * params / (g_ms * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": 2.0 * params / (g_ms * 1e-3) / 8e12,
+                     "kernel": "weight streaming" if M <= 16 else "LDS-tiled MFMA"})
+        kv.close()
+        del logits
+    print(json.dumps({"metric": "projection GEMMs of a LLaMA2-7B-shaped layer over M", "unit": "TFLOP/s and GB/s",
+                      "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "two LLaMA2-7B-shaped layers + lm_head, one forward of M rows on an empty cache",
+                                 "weights_GB": 2.0 * params / 1e9},
+                      "note": "useful flops: activations enter the matrix cores as bf16 hi + lo pairs, twice as many MFMAs are issued",
+                      "sweep": rows}))
 
 
 if __name__ == "__main__":

@@ -89,15 +89,15 @@ psd_status psd_model_create(const psd_model_desc *desc, const void *const *weigh
                             int32_t n_ptrs, psd_model **out);
 psd_status psd_model_destroy(psd_model *m);
 
-/* Optional streaming copy of the projection weights for verify steps of up to 64 rows
- * (batch * n_new <= 64), where the forward pass is bound by reading the weights once from HBM.
+/* Optional streaming copy of the projection weights for verify steps of up to 16 rows
+ * (batch * n_new <= 16), where the forward pass is bound by reading the weights once from HBM.
  * psd_model_pack rewrites every projection matrix into caller memory in the order the
  * wavefronts of the streaming GEMM load it (64-row x 128-column units of 16 KB, each stored
  * as the 64 lanes' 16-byte operands, units of one projection contiguous), so that each
  * wavefront reads one contiguous byte range.  packed_mem: device, 256-byte aligned, at least
  * psd_model_packed_bytes() bytes (about the size of the weights), kept alive with the model;
  * the row-major weights stay in use for larger steps and must stay alive too.  After a
- * successful call, forwards with batch * n_new <= 64 read the packed copy; results are the same
+ * successful call, forwards with batch * n_new <= 16 read the packed copy; results are the same
  * up to fp32 summation order.  Call it before sizing workspaces: the workspace need changes.
  * PSD_BF16 models only (PSD_ERR_DTYPE otherwise); psd_model_packed_bytes returns 0 for others. */
 size_t psd_model_packed_bytes(const psd_model *m);
@@ -196,8 +196,8 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_EMBED 0
 #define PSD_KIND_RMSNORM 1
 #define PSD_KIND_GEMM_F32 2
-#define PSD_KIND_GEMM_SKINNY 3       /* bf16 weight-streaming GEMM, M <= 64 */
-#define PSD_KIND_GEMM_TILED 4        /* bf16 LDS-tiled GEMM, M > 64 */
+#define PSD_KIND_GEMM_SKINNY 3       /* bf16 weight-streaming GEMM, M <= 16 */
+#define PSD_KIND_GEMM_TILED 4        /* bf16 LDS-tiled GEMM, M > 16 */
 #define PSD_KIND_GEMM_REDUCE 5       /* split-K reduction */
 #define PSD_KIND_ROPE_APPEND 6
 #define PSD_KIND_ATTN 7
@@ -207,7 +207,7 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_ACCEPT_STATS 11
 #define PSD_KIND_ACCEPT_EMIT 12      /* fp64 pass over the one position the draw reads */
 #define PSD_KIND_ACCEPT_LOCATE 13
-#define PSD_KIND_GEMM_COLUMN 14      /* bf16 one-slot GEMM with the residual epilogue, M <= 64 */
+#define PSD_KIND_GEMM_COLUMN 14      /* bf16 one-slot GEMM with the residual epilogue, M <= 16 */
 #define PSD_KIND_COUNT 15
 psd_status psd_profile_enable(int32_t max_launches);
 psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind);

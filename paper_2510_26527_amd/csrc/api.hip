@@ -41,7 +41,7 @@ struct psd_model {
     const void *layer(int l, int which) const { return w[1 + 9 * l + which]; }
     const void *final_norm() const { return w[1 + 9 * d.n_layers]; }
     const void *lm_head() const { return w[2 + 9 * d.n_layers]; }
-    // repacked copies for the M <= 64 path (psd_model_pack): per layer qkv, o, gate|up, down; then lm_head
+    // repacked copies for the weight-streaming path (psd_model_pack): per layer qkv, o, gate|up, down; then lm_head
     const char *packed = nullptr;
     std::vector<size_t> pack_off;    // 4 * n_layers + 1 offsets into `packed`
     const void *pack(int l, int which) const { return packed ? packed + pack_off[4 * l + which] : nullptr; }
@@ -221,7 +221,7 @@ struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
     size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, total;
-    bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= 64)
+    bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
 };
 
 ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound) {
@@ -233,9 +233,9 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.width_qkv = hd + 2 * kvd;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
     const int Ml = batch * n_logit_rows;
-    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= 64;
+    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
-        if (mdl->packed && rows <= 64) return gemm_packed_splits(rows, K, n, nseg);
+        if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
     p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
@@ -320,7 +320,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
     auto gemm = [&](const float *xin, int rows, int K, const void *w0, int n0, const void *w1, int n1,
                     const void *w2, int n2, int sk, float *dst, const void *wpack) {
         GemmArgs g{};
-        g.wpack = rows <= 64 ? wpack : nullptr;
+        g.wpack = rows <= kStreamMaxRows ? wpack : nullptr;
         g.x = xin; g.x_rows_per_group = rows > 0 ? rows : 1; g.x_group_stride = 0; g.x_group_offset = 0;
         g.w[0] = w0; g.w[1] = w1; g.w[2] = w2; g.n[0] = n0; g.n[1] = n1; g.n[2] = n2;
         g.nseg = w2 ? 3 : (w1 ? 2 : 1);
@@ -378,7 +378,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         hg.x = act; hg.x_rows_per_group = n_logit_rows; hg.x_group_stride = n_new; hg.x_group_offset = n_new - n_logit_rows;
         hg.w[0] = m->lm_head(); hg.n[0] = d.vocab; hg.nseg = 1;
         hg.M = B * n_logit_rows; hg.K = d.d_model; hg.N = d.vocab;
-        hg.wpack = hg.M <= 64 ? m->pack_head() : nullptr;
+        hg.wpack = hg.M <= kStreamMaxRows ? m->pack_head() : nullptr;
         hg.pack_tiles = gemm_pack_tiles(hg.n, 1);
         hg.splitk = p.sk_head;
         const bool two_step = p.sk_head > 1 || p.folded;

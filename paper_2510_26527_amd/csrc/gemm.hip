@@ -3,16 +3,19 @@
 // Three kernels, chosen by model dtype and row count M (M = batch * n_new of a verify step):
 //   gemm_f32_kernel          fp32 weights, plain ALU dot products, one wavefront per output
 //                            column (the tiny fp32 chain; fp32 1e-4 parity, not speed).
-//   gemm_bf16_skinny_kernel  M <= 64.  HBM-bound weight streaming: W rows go straight from
+//   gemm_bf16_skinny_kernel  M <= 16.  HBM-bound weight streaming: W rows go straight from
 //                            global memory into MFMA A-operand registers with 16-byte loads
 //                            (no LDS), the few activation rows are the B operand, K is split
 //                            over the four wavefronts of a block and over blocks.
-//   gemm_bf16_stream_kernel  M <= 64 on weights repacked by gemm_pack_kernel: the same MFMA tiling,
+//   gemm_bf16_stream_kernel  M <= 16 on weights repacked by gemm_pack_kernel: the same MFMA tiling,
 //                            but every 16 KB unit (64 rows x 128 k) is stored in exactly the order the
 //                            lanes load it, units of a GEMM are contiguous, and the grid is persistent:
 //                            each wavefront streams an equal, contiguous byte range of the weights
 //                            (stream-K) and writes one partial per tile it touches.
-//   gemm_bf16_tiled_kernel   M > 64.  128x256x64 LDS-staged tiles, 32x32x16 bf16 MFMA.
+//   gemm_bf16_column_kernel  M <= 16, the projections that write the residual stream: one block per 16
+//                            output columns over the whole K range; the residual add, the gain-scaled copy
+//                            and the RMSNorm statistics happen in its epilogue.
+//   gemm_bf16_tiled_kernel   M > 16.  128 x (128..256) x 64 LDS-staged tiles, 32x32x16 bf16 MFMA.
 // Activations are fp32 in memory in every case.  The bf16 kernels feed each activation to the
 // matrix cores as a pair of bf16 values hi + lo (two MFMAs against the same weight operand):
 // with plain bf16 activations the logits of the 7B-shaped random-init models are 3e-2 off the
@@ -690,7 +693,7 @@ int gemm_packed_splits(int M, int K, const int *n, int nseg) {
 int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
     (void)N;
     if (dtype != PSD_BF16) return 1;
-    if (M <= 64) {
+    if (M <= kStreamMaxRows) {
         const int tiles = tiles_of(n, nseg, kSkinnyRows);
         const int nsteps = K / kSkinnyStepK;
         int want = (512 + tiles - 1) / tiles;             // aim at >= 512 blocks (2048 wavefronts)
@@ -711,37 +714,23 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         launch_kernel(gemm_f32_kernel, (g.N + 3) / 4, 256, 0, stream, g);
         return;
     }
-    if (g.M <= 64 && g.wpack && g.x_resid) {
+    if (g.M <= kStreamMaxRows && g.wpack && g.x_resid) {
         ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
-        const int grid = g.N / 16, mt = (g.M + 15) / 16;          // N = d_model is a multiple of 128
-        if (mt == 1) launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
-        else if (mt == 2) launch_kernel(gemm_bf16_column_kernel<2, 8>, grid, 512, 0, stream, g);
-        else if (mt == 3) launch_kernel(gemm_bf16_column_kernel<3, 8>, grid, 512, 0, stream, g);
-        else launch_kernel(gemm_bf16_column_kernel<4, 8>, grid, 512, 0, stream, g);
+        const int grid = g.N / 16;                        // N = d_model is a multiple of 128; M <= 16: one row tile
+        launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
         return;
     }
-    if (g.M <= 64 && g.wpack && gemm_use_stream(g.pack_tiles)) {
+    if (g.M <= kStreamMaxRows && g.wpack && gemm_use_stream(g.pack_tiles)) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         const int grid = gemm_stream_grid(g.pack_tiles, g.K);
-        const int mt = (g.M + 15) / 16;
-        if (mt == 1) launch_kernel(gemm_bf16_stream_kernel<1>, grid, 256, 0, stream, g);
-        else if (mt == 2) launch_kernel(gemm_bf16_stream_kernel<2>, grid, 256, 0, stream, g);
-        else if (mt == 3) launch_kernel(gemm_bf16_stream_kernel<3>, grid, 256, 0, stream, g);
-        else launch_kernel(gemm_bf16_stream_kernel<4>, grid, 256, 0, stream, g);
-    } else if (g.M <= 64) {
+        launch_kernel(gemm_bf16_stream_kernel<1>, grid, 256, 0, stream, g);
+    } else if (g.M <= kStreamMaxRows) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
-        const int mt = (g.M + 15) / 16;
         if (g.wpack) {
-            if (mt == 1) launch_kernel(gemm_bf16_skinny_kernel<1, true>, grid, 256, 0, stream, g);
-            else if (mt == 2) launch_kernel(gemm_bf16_skinny_kernel<2, true>, grid, 256, 0, stream, g);
-            else if (mt == 3) launch_kernel(gemm_bf16_skinny_kernel<3, true>, grid, 256, 0, stream, g);
-            else launch_kernel(gemm_bf16_skinny_kernel<4, true>, grid, 256, 0, stream, g);
+            launch_kernel(gemm_bf16_skinny_kernel<1, true>, grid, 256, 0, stream, g);
         } else {
-            if (mt == 1) launch_kernel(gemm_bf16_skinny_kernel<1, false>, grid, 256, 0, stream, g);
-            else if (mt == 2) launch_kernel(gemm_bf16_skinny_kernel<2, false>, grid, 256, 0, stream, g);
-            else if (mt == 3) launch_kernel(gemm_bf16_skinny_kernel<3, false>, grid, 256, 0, stream, g);
-            else launch_kernel(gemm_bf16_skinny_kernel<4, false>, grid, 256, 0, stream, g);
+            launch_kernel(gemm_bf16_skinny_kernel<1, false>, grid, 256, 0, stream, g);
         }
     } else {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);

@@ -32,6 +32,11 @@ void launch_accept(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
 void launch_accept_greedy(const AcceptArgs &a, bool vec_ok, hipStream_t stream);
 
 // ---------------------------------------------------------------- GEMMs (gemm.hip)
+// Up to this many rows (one 16-row MFMA tile) the bf16 projections stream the weights straight into MFMA
+// operands (HBM-bound); above it the activation operand traffic of that scheme outgrows the weights and the
+// LDS-tiled kernel wins (measured on two LLaMA2-7B-shaped layers: 0.28 ms at 16 rows; at 32 rows 0.43 ms
+// streaming against 0.38 ms tiled, at 64 rows 0.66 against 0.38).
+constexpr int kStreamMaxRows = 16;
 // y[m][n] = sum_k x[m][k] * W[n][k]; W is up to three row-major [n_i][K] matrices whose
 // outputs are concatenated along n (QKV, gate|up).
 // r_m from per-tile sums of squares: rsqrt(sum_t sumsq[t * M + m] * inv_d + eps); sumsq NULL: 1
@@ -48,12 +53,12 @@ struct GemmArgs {
     int n[3];
     int nseg;
     int M, K, N;                  // N = sum n[i]
-    const void *wpack;            // optional repacked copy of all segments (bf16, M <= 64): see gemm.hip
+    const void *wpack;            // optional repacked copy of all segments (bf16, M <= kStreamMaxRows): see gemm.hip
     int pack_tiles;               //   its number of 64-row tiles
     float *partial;               // [splitk][M][N] fp32: split s holds its share of the K sum
     int splitk;
     float *reduced;               // if non-NULL: [M][N] <- sum over splits (logits), times the row scale if given
-    // -- bf16, M <= 64, packed weights only: RMSNorm folded into the projections around it -----------
+    // -- bf16, M <= kStreamMaxRows, packed weights only: RMSNorm folded into the projections around it -----------
     // rmsnorm(x) W^T = r_m * ((x * gain) W^T) with r_m = rsqrt(mean_k x[m][k]^2 + eps).  The one-slot column
     // kernel (selected by x_resid) adds its output into the residual stream x_resid [M][N], writes
     // xg_out[m][n] = x_resid[m][n] * gain[n] (the operand of the next projection; gain = the next norm's)
@@ -67,7 +72,7 @@ struct GemmArgs {
     int scale_rows;               //   rows per tile slab of scale.sumsq
 };
 int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg);
-// repacked weights for the M <= 64 path
+// repacked weights for the M <= kStreamMaxRows path
 int gemm_pack_tiles(const int *n, int nseg);
 size_t gemm_pack_bytes(const int *n, int nseg, int K);
 int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots (the splitk to use) with packed weights

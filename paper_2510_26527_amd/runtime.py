@@ -37,7 +37,7 @@ class Model:
         self.packed = None
 
     def pack(self):
-        """Build the streaming copy of the projection weights (bf16 models) for steps of <= 64 rows."""
+        """Build the streaming copy of the projection weights (bf16 models) for steps of <= 16 rows."""
         need = psd.psd_model_packed_bytes(self.handle)
         if need == 0:
             return self
