@@ -522,7 +522,10 @@ int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int le
     const int QT = q_tiles(NQ, d_h);
     const int chunks = use_wide(NQ) ? (NQ + wide_rows(NQ) - 1) / wide_rows(NQ) : (NQ + QT * 16 - 1) / (QT * 16);
     const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
-    int by_grid = 1024 / (B * h_kv * chunks);
+    // the LDS-staged kernel loads its 64-128 query rows and writes as many partial rows per block: about one
+    // block per CU keeps that overhead below the K/V bytes (measured at 16 x 4 KV heads x 4096 keys: 4 splits
+    // 78 us, 8 splits 91 us, 16 splits 113 us per layer); the direct kernel has light blocks and wants many
+    int by_grid = (use_wide(NQ) ? 256 : 1024) / (B * h_kv * chunks);
     if (by_grid < 1) by_grid = 1;
     int s = by_len < by_grid ? by_len : by_grid;
     return s < 1 ? 1 : s;
