@@ -218,6 +218,14 @@ def main():
         okv.truncate(ctx)
         c1 = time.perf_counter()
         threads = max([torch.get_num_threads()] + [p.get("num_threads", 1) for p in threadpool_info()])
+        # the acceptance oracle alone on one configs[1] input set (single-threaded C, fp64)
+        s0 = sets[0]
+        a0 = time.perf_counter()
+        oacc.spec_accept(s0["p"].float().cpu().numpy(), s0["q"].float().cpu().numpy(), s0["tokens"].cpu().numpy(),
+                         s0["uniforms"].cpu().double().numpy(), 1.0)
+        a1 = time.perf_counter()
+        accept["cpu_oracle_ms"] = (a1 - a0) * 1e3
+        accept["cpu_oracle_GB/s"] = a_bytes / (a1 - a0) / 1e9
         cpu_baseline = {"value": gamma / (c1 - c0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
                         "sample": "one whole step of the same workload (32 layers + lm_head forward in numpy fp64, "
                                   "acceptance in C fp64, rollback), %.1f s" % (c1 - c0)}
