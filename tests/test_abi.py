@@ -119,3 +119,14 @@ def test_spec_accept_validation(lib):
     assert call(w=0) == psd.PSD_ERR_WORKSPACE
     assert call(wb=8) == psd.PSD_ERR_WORKSPACE
     assert call(rows=0) == psd.PSD_OK                     # nothing to do, nothing launched
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build has no multi-GPU path: bench.py says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
