@@ -638,8 +638,8 @@ static void tiled_choice(int M, int K, const int *n, int nseg, int *nb_out, int 
     for (int s = 0; s < nseg; ++s) N += n[s];
     const double slot_us = 2.0 * (double)M * (double)N * 4.0 / 3.0e6;
     double best = 1e300;
-    *nb_out = kMaxNB; *sk_out = 1;
-    for (int nb = 4; nb <= kMaxNB; ++nb)
+    *nb_out = 5; *sk_out = 1;
+    for (int nb = 4; nb < kMaxNB; ++nb)               // the 256-wide tile runs out of registers: measured 2x slower
         for (int sk = 1; sk <= 16 && (sk == 1 || nk / sk >= 4); ++sk) {
             const long blocks = (long)tiles_of(n, nseg, 32 * nb) * m_tiles * sk;
             const long rounds = (blocks + 511) / 512;
@@ -736,7 +736,7 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         int nb, sk;
         tiled_choice(g.M, g.K, g.n, g.nseg, &nb, &sk);
-        if (sk != g.splitk) nb = kMaxNB;                  // the caller sized the partial slots for its own split
+        if (sk != g.splitk) nb = 5;                       // the caller sized the partial slots for its own split
         dim3 grid(tiles_of(g.n, g.nseg, 32 * nb) * ((g.M + kBM - 1) / kBM), g.splitk);
         static bool lds_ok[kMaxNB + 1] = {};              // opt in once per instantiation to more than 64 KB of dynamic LDS
         auto go = [&](auto kernel) {
