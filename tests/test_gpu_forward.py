@@ -19,7 +19,7 @@ BF16_REL_TOL = 2e-2
 
 
 def _progress(msg):
-    """Long tests leave a trace under gpurun_out/ so a quiet run is not mistaken for a hang."""
+    """Long tests append to a progress file so that a quiet run is not mistaken for a hang."""
     os.makedirs("gpurun_out", exist_ok=True)
     with open("gpurun_out/test_progress.log", "a") as f:
         f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
