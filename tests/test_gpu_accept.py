@@ -164,3 +164,24 @@ def test_greedy_strided_rows_and_infinities():
     on, otok = oacc.greedy_accept(p.cpu().numpy(), x.cpu().numpy())
     assert n.cpu().tolist() == on.tolist() == [3, 2, 1, 1]
     assert tok.cpu().tolist() == otok.tolist() == [17, 5, 900, 17]
+
+
+def test_edge_sizes():
+    """One-entry vocabulary (every ratio is 1, every draw is token 0), the longest block the boundary accepts
+    (gamma = 64), and rows = 0 (a no-op that launches nothing)."""
+    dev = torch.device("cuda")
+    acc = runtime.Acceptor(dev)
+    one = {"p": torch.randn(3, 3, 1), "q": torch.randn(3, 2, 1), "tokens": torch.zeros((3, 2), dtype=torch.int32),
+           "uniforms": synth.make_uniforms((3, 3), 1)}
+    n, tok, _ = _compare(one)
+    assert np.all(n == 2) and np.all(tok == 0)
+    inp = synth.make_accept_inputs(3, 64, 300, seed=64, n_p_rows=65, dtype=torch.float32, noise_std=0.1)
+    n, tok, _ = _compare(inp)
+    assert n.max() > 8
+    empty = torch.empty((0, 3, 16), dtype=torch.float32, device=dev)
+    ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    psd.psd_spec_accept(empty, empty[:, :2], torch.empty((0, 2), dtype=torch.int32, device=dev), 2,
+                        torch.empty((0, 3), dtype=torch.float32, device=dev), 1.0,
+                        torch.empty(0, dtype=torch.int32, device=dev), torch.empty(0, dtype=torch.int32, device=dev),
+                        0, 3, 16, psd.PSD_F32, 48, 32, None, ws)
+    torch.cuda.synchronize()
