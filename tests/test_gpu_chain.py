@@ -385,3 +385,33 @@ def test_workload4_insertion_criterion_live(chain4_models):
         json.dump(rep, f, indent=1)
     print("insertion check", json.dumps(rep))
     assert two["L"][0] > 1 and three["L"][0] > two["L"][0]        # the intermediate raises the target's acceptance length
+
+
+def test_four_level_tiny_chain():
+    """The chain driver is n-level generic (the paper's conclusion names deeper chains as the next step): four
+    fp32 models, block sizes 8 / 4 / 2, lockstep against the oracle and the same text from a free-running
+    oracle chain."""
+    extra = synth.Shape(1, 96, 3, 3, 32, 192, 512)
+    shapes = [synth.TINY_TARGET, synth.TINY_INTERMEDIATE, synth.TINY_DRAFT, extra]
+    gammas = [None, 8, 4, 2]
+    n_gen, max_len = 48, 192
+    seeds = [101, 102, 103, 104]
+    glevels, olevels = _setup(shapes, seeds, torch.float32, max_len, gammas)
+    prompt = synth.make_tokens(512, (20,), 17).tolist()
+    tapes = [synth.make_tape(19, 0, 200, 16), synth.make_tape(19, 1, 400, 16), synth.make_tape(19, 2, 800, 16),
+             synth.make_tape(19, 3, 2000, 1)[:, 0]]
+    g = gchain.Chain(glevels, gammas, tapes, 1.0, trace=True)
+    out = g.generate(prompt, n_gen)
+    for lvl in olevels:
+        lvl.forward(prompt[:-1])
+    worst, ties, n_accept = _lockstep(g.events, olevels, 1e-4)
+    _, olevels2 = _setup(shapes, seeds, torch.float32, max_len, gammas)
+    o = ochain.Chain(olevels2, gammas, [np.asarray(t, np.float64) for t in tapes], 1.0)
+    ref = o.generate(prompt, n_gen)
+    assert out == ref
+    assert [lv.forwards for lv in glevels] == o.stats.forwards
+    F = [lv.forwards for lv in glevels]
+    assert F[0] <= F[1] <= F[2] <= F[3]
+    print(f"four levels: forwards {F}, lockstep max abs err {worst:.2e}, accept calls {n_accept}, near-ties {ties}")
+    for lv in glevels:
+        lv.close()
