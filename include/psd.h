@@ -89,6 +89,23 @@ psd_status psd_model_create(const psd_model_desc *desc, const void *const *weigh
                             int32_t n_ptrs, psd_model **out);
 psd_status psd_model_destroy(psd_model *m);
 
+/* A model whose seven projection matrices per layer are 4-bit weight-only quantised with groups of 128
+ * input channels, the format of the paper's intermediate model M_2 ("a quantized 4-bit version of M_1",
+ * group size 128: Sec. 3.3 system design and Sec. 4.1 setup): W[n][k] = scale[n][k/128] * (q[n][k] - zero[n][k/128]).
+ * desc and weight_ptrs are as for psd_model_create with dtype PSD_BF16, except that the pointers of
+ * wq, wk, wv, wo, w_gate, w_up, w_down address the 4-bit codes: device uint8 [n][K/2], byte b of a row holds
+ * k = 2b in its low nibble and k = 2b + 1 in its high nibble.  scale_ptrs / zero_ptrs: 7 * n_layers device
+ * pointers in the order (wq, wk, wv, wo, w_gate, w_up, w_down) per layer, to bf16 [n][K/128] and to uint8
+ * [n][K/128] with values 0..15.  Embedding, norm gains, lm_head and the KV cache stay bf16; activations are
+ * handled as in PSD_BF16 models; no weight is rounded: the codes enter the matrix cores as exact integers and
+ * scale and zero point are applied per group in fp32.
+ * Such a model must be packed (psd_model_pack) before its first forward, and a forward takes at most 16 rows
+ * (batch * n_new <= 16; longer prompts are fed in several calls): otherwise PSD_ERR_UNIMPLEMENTED.
+ * Further limit: n_kv_heads * d_head a multiple of 64. */
+psd_status psd_model_create_w4(const psd_model_desc *desc, const void *const *weight_ptrs, int32_t n_ptrs,
+                               const void *const *scale_ptrs, const void *const *zero_ptrs,
+                               int32_t n_quant_ptrs, psd_model **out);
+
 /* Optional streaming copy of the projection weights for verify steps of up to 16 rows
  * (batch * n_new <= 16), where the forward pass is bound by reading the weights once from HBM.
  * psd_model_pack rewrites every projection matrix into caller memory in the order the

@@ -33,6 +33,8 @@ _SIGNATURES = {
     "psd_last_hip_error": (_i32, []),
     "psd_model_create": (_i32, [ctypes.POINTER(psd_model_desc), ctypes.POINTER(_vp), _i32, ctypes.POINTER(_vp)]),
     "psd_model_destroy": (_i32, [_vp]),
+    "psd_model_create_w4": (_i32, [ctypes.POINTER(psd_model_desc), ctypes.POINTER(_vp), _i32, ctypes.POINTER(_vp),
+                                   ctypes.POINTER(_vp), _i32, ctypes.POINTER(_vp)]),
     "psd_model_workspace_bytes": (_sz, [_vp, _i32, _i32, _i32]),
     "psd_model_packed_bytes": (_sz, [_vp]),
     "psd_model_pack": (_i32, [_vp, _vp, _sz, _vp]),
@@ -110,6 +112,18 @@ def psd_model_create(desc: psd_model_desc, weight_ptrs):
     arr = (_vp * len(weight_ptrs))(*weight_ptrs)
     out = _vp()
     _check(lib().psd_model_create(ctypes.byref(desc), arr, len(weight_ptrs), ctypes.byref(out)), "psd_model_create")
+    return out
+
+
+def psd_model_create_w4(desc: psd_model_desc, weight_ptrs, scale_ptrs, zero_ptrs):
+    """As psd_model_create; the projection pointers address 4-bit codes, scale_ptrs / zero_ptrs their group
+    scales and zero points (7 per layer)."""
+    arr = (_vp * len(weight_ptrs))(*weight_ptrs)
+    sc = (_vp * len(scale_ptrs))(*scale_ptrs)
+    zp = (_vp * len(zero_ptrs))(*zero_ptrs)
+    out = _vp()
+    _check(lib().psd_model_create_w4(ctypes.byref(desc), arr, len(weight_ptrs), sc, zp, len(scale_ptrs),
+                                     ctypes.byref(out)), "psd_model_create_w4")
     return out
 
 

@@ -46,6 +46,12 @@ struct psd_model {
     std::vector<size_t> pack_off;    // 4 * n_layers + 1 offsets into `packed`
     const void *pack(int l, int which) const { return packed ? packed + pack_off[4 * l + which] : nullptr; }
     const void *pack_head() const { return packed ? packed + pack_off[4 * d.n_layers] : nullptr; }
+    // 4-bit projections (psd_model_create_w4): per layer and projection (q, k, v, o, gate, up, down) the group
+    // scales and zero points; w[] then points at the nibbles
+    bool w4 = false;
+    std::vector<const void *> w4_scale, w4_zero;
+    const void *qscale(int l, int j) const { return w4_scale[7 * l + j]; }
+    const void *qzero(int l, int j) const { return w4_zero[7 * l + j]; }
 };
 enum { P_QKV = 0, P_O, P_GU, P_DOWN };
 enum { W_ATTN_NORM = 0, W_Q, W_K, W_V, W_O, W_FFN_NORM, W_GATE, W_UP, W_DOWN };
@@ -124,17 +130,41 @@ psd_status psd_model_destroy(psd_model *m) {
     return PSD_OK;
 }
 
+psd_status psd_model_create_w4(const psd_model_desc *desc, const void *const *weight_ptrs, int32_t n_ptrs,
+                               const void *const *scale_ptrs, const void *const *zero_ptrs, int32_t n_quant_ptrs,
+                               psd_model **out) {
+    if (!desc || !scale_ptrs || !zero_ptrs) return PSD_ERR_NULL;
+    if (desc->dtype != PSD_BF16) return PSD_ERR_DTYPE;
+    if (n_quant_ptrs != 7 * desc->n_layers) return PSD_ERR_SHAPE;
+    if ((desc->n_kv_heads * desc->d_head) % 64) return PSD_ERR_SHAPE;      // every projection a multiple of 64 wide
+    for (int i = 0; i < n_quant_ptrs; ++i) {
+        if (!scale_ptrs[i] || !zero_ptrs[i]) return PSD_ERR_NULL;
+        if ((uintptr_t)scale_ptrs[i] % 2) return PSD_ERR_SHAPE;
+    }
+    psd_model *m = nullptr;
+    const psd_status s = psd_model_create(desc, weight_ptrs, n_ptrs, &m);
+    if (s != PSD_OK) return s;
+    m->w4 = true;
+    m->w4_scale.assign(scale_ptrs, scale_ptrs + n_quant_ptrs);
+    m->w4_zero.assign(zero_ptrs, zero_ptrs + n_quant_ptrs);
+    *out = m;
+    return PSD_OK;
+}
+
 static void pack_layout(const psd_model *m, std::vector<size_t> *off, size_t *total) {
     const psd_model_desc &d = m->d;
     const int hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
     size_t at = 0;
     off->clear();
+    auto bytes = [&](const int *n, int nseg, int K) {
+        return align256(m->w4 ? gemm_pack_w4_bytes(n, nseg, K) : gemm_pack_bytes(n, nseg, K));
+    };
     for (int l = 0; l < d.n_layers; ++l) {
-        off->push_back(at); at += gemm_pack_bytes(n_qkv, 3, d.d_model);
-        off->push_back(at); at += gemm_pack_bytes(n_o, 1, hd);
-        off->push_back(at); at += gemm_pack_bytes(n_gu, 2, d.d_model);
-        off->push_back(at); at += gemm_pack_bytes(n_o, 1, d.d_ffn);
+        off->push_back(at); at += bytes(n_qkv, 3, d.d_model);
+        off->push_back(at); at += bytes(n_o, 1, hd);
+        off->push_back(at); at += bytes(n_gu, 2, d.d_model);
+        off->push_back(at); at += bytes(n_o, 1, d.d_ffn);
     }
     off->push_back(at); at += gemm_pack_bytes(n_v, 1, d.d_model);
     *total = at;
@@ -160,7 +190,21 @@ psd_status psd_model_pack(psd_model *m, void *packed_mem, size_t packed_bytes, v
     hipStream_t st = (hipStream_t)hip_stream;
     char *base = (char *)packed_mem;
     (void)hipGetLastError();
-    for (int l = 0; l < d.n_layers; ++l) {
+    for (int l = 0; l < d.n_layers && m->w4; ++l) {
+        const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn};
+        const void *qkv[3] = {m->layer(l, W_Q), m->layer(l, W_K), m->layer(l, W_V)};
+        const void *qkv_s[3] = {m->qscale(l, 0), m->qscale(l, 1), m->qscale(l, 2)};
+        const void *qkv_z[3] = {m->qzero(l, 0), m->qzero(l, 1), m->qzero(l, 2)};
+        launch_gemm_pack_w4(qkv, qkv_s, qkv_z, n_qkv, 3, d.d_model, base + off[4 * l + P_QKV], st);
+        const void *o[1] = {m->layer(l, W_O)}, *o_s[1] = {m->qscale(l, 3)}, *o_z[1] = {m->qzero(l, 3)};
+        launch_gemm_pack_w4(o, o_s, o_z, n_o, 1, hd, base + off[4 * l + P_O], st);
+        const void *gu[2] = {m->layer(l, W_GATE), m->layer(l, W_UP)};
+        const void *gu_s[2] = {m->qscale(l, 4), m->qscale(l, 5)}, *gu_z[2] = {m->qzero(l, 4), m->qzero(l, 5)};
+        launch_gemm_pack_w4(gu, gu_s, gu_z, n_gu, 2, d.d_model, base + off[4 * l + P_GU], st);
+        const void *dn[1] = {m->layer(l, W_DOWN)}, *dn_s[1] = {m->qscale(l, 6)}, *dn_z[1] = {m->qzero(l, 6)};
+        launch_gemm_pack_w4(dn, dn_s, dn_z, n_o, 1, d.d_ffn, base + off[4 * l + P_DOWN], st);
+    }
+    for (int l = 0; l < d.n_layers && !m->w4; ++l) {
         const void *qkv[3] = {m->layer(l, W_Q), m->layer(l, W_K), m->layer(l, W_V)};
         const int n_qkv[3] = {hd, kvd, kvd};
         launch_gemm_pack(qkv, n_qkv, 3, d.d_model, base + off[4 * l + P_QKV], false, st);
@@ -233,8 +277,9 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.width_qkv = hd + 2 * kvd;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
     const int Ml = batch * n_logit_rows;
-    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;
+    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;        // 4-bit models: always (checked by the caller)
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
+        if (mdl->w4 && n != n_v) return 1;                  // the one-slot column kernel
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
@@ -301,6 +346,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
     if (n_logit_rows < 0 || n_logit_rows > n_new) return PSD_ERR_SHAPE;
     if (n_logit_rows > 0 && !logits_out_dev) return PSD_ERR_NULL;
     if (kv->len_ub + n_new > kv->max_len) return PSD_ERR_CAPACITY;
+    if (m->w4 && (!m->packed || B * n_new > kStreamMaxRows)) return PSD_ERR_UNIMPLEMENTED;
     const int len_bound = kv->len_ub + n_new;
     const ForwardPlan p = plan_forward(m, B, n_new, n_logit_rows, len_bound);
     if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < p.total) return PSD_ERR_WORKSPACE;
@@ -326,6 +372,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         g.nseg = w2 ? 3 : (w1 ? 2 : 1);
         g.M = rows; g.K = K; g.N = n0 + n1 + n2; g.partial = dst; g.splitk = sk; g.reduced = nullptr;
         g.pack_tiles = gemm_pack_tiles(g.n, g.nseg);
+        g.w4 = m->w4;
         launch_gemm(d.dtype, g, st);
     };
     // Folded mode: no RMSNorm kernel runs.  The projections that read the residual stream multiply it by
@@ -342,7 +389,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
             GemmArgs g{};
             g.wpack = wpack; g.x = xin; g.x_rows_per_group = M; g.w[0] = w; g.n[0] = d.d_model; g.nseg = 1;
             g.M = M; g.K = K; g.N = d.d_model; g.splitk = 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
-            g.x_resid = x; g.xg_out = xn; g.gain = next_gain; g.sumsq_out = sumsq;
+            g.x_resid = x; g.xg_out = xn; g.gain = next_gain; g.sumsq_out = sumsq; g.w4 = m->w4;
             launch_gemm(d.dtype, g, st);
             rs.tiles = col_tiles;
         } else {

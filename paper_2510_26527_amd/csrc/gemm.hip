@@ -403,7 +403,51 @@ __global__ __launch_bounds__(256) void gemm_pack_strip_kernel(const uint16_t *W,
     dst[vec] = v;
 }
 
-template <int MT, int kColWaves>
+// 4-bit weights (W4A16, asymmetric, groups of 128 along K = one K step): w = scale * (q - zero).  Strip-major
+// layout for the column kernel: (strip, step) is 1088 bytes = 1 KB of nibbles in lane order (lane (i, gq) owns one
+// 16-byte vector: dword q holds its eight nibbles of K offsets (q>>1)*64 + gq*16 + (q&1)*8 ..+7, element e at bit
+// 4*(e/2) + 16*(e&1), so that (dword >> 4p) & 0x000F000F is the element pair (2p, 2p+1)), then the 16 rows'
+// scales as bf16 and their zero points + 128 as bf16.  The kernel multiplies the nibbles as the exact bf16
+// integers 128 + q (bit pattern 0x4300 | q), and takes scale * (sum (128 + q) x - (128 + zero) sum x) per
+// group, so no weight is ever rounded.
+constexpr int kW4StripBytes = 1024 + 64;
+constexpr int kW4StripVec = kW4StripBytes / 16;
+
+__global__ __launch_bounds__(64) void gemm_pack_w4_kernel(const uint8_t *Q, const uint16_t *scale, const uint8_t *zero,
+                                                          int N, int K, uint8_t *dst) {
+    const int ns = K / kSkinnyStepK;
+    const size_t strip = blockIdx.x / ns;
+    const int step = blockIdx.x % ns, lane = threadIdx.x, i = lane & 15, gq = lane >> 4;
+    const size_t row = strip * 16 + i;
+    uint8_t *out = dst + (size_t)blockIdx.x * kW4StripBytes;
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (row < (size_t)N) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k = step * kSkinnyStepK + (q >> 1) * 64 + gq * 16 + (q & 1) * 8;
+            const uint32_t raw = *reinterpret_cast<const uint32_t *>(Q + (row * K + k) / 2);   // byte b: k + 2b, k + 2b + 1
+            uint32_t w = 0;
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+                w |= ((raw >> (8 * bb)) & 0xFu) << (4 * bb);                // element 2 bb
+                w |= ((raw >> (8 * bb + 4)) & 0xFu) << (16 + 4 * bb);       // element 2 bb + 1
+            }
+            v[q] = w;
+        }
+    }
+    reinterpret_cast<u32x4 *>(out)[lane] = v;
+    if (lane < 16) {
+        uint16_t sc = 0, zp = 0x4300;                                        // rows past the end: scale 0
+        if (row < (size_t)N) {
+            sc = scale[row * ns + step];
+            zp = (uint16_t)(0x4300u | zero[row * ns + step]);               // bf16 of 128 + zero (zero <= 15)
+        }
+        reinterpret_cast<uint16_t *>(out + 1024)[lane] = sc;
+        reinterpret_cast<uint16_t *>(out + 1056)[lane] = zp;
+    }
+}
+
+template <int MT, int kColWaves, bool W4>
 __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
@@ -418,7 +462,7 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int tok = mt * 16 + emm;
-            e_res[mt] = tok < g.M ? g.x_resid[(size_t)tok * g.N + ecol] : 0.f;
+            e_res[mt] = tok < g.M && g.x_resid ? g.x_resid[(size_t)tok * g.N + ecol] : 0.f;
         }
         if (g.gain) e_gain = bf16_bits_to_f32(((const uint16_t *)g.gain)[ecol]);
     }
@@ -437,6 +481,57 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[h][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    if constexpr (W4) {
+        static_assert(MT == 1, "4-bit weights: one row tile");
+        const uint8_t *wq = (const uint8_t *)g.wpack + (size_t)blockIdx.x * ns * kW4StripBytes;
+        const u32x4 ones4 = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+        for (int step = s0; step < s1; step += kColDepth) {
+            u32x4 a[kColDepth];
+            uint2 sc[kColDepth], zr[kColDepth];
+#pragma unroll
+            for (int j = 0; j < kColDepth; ++j)
+                if (step + j < s1) {
+                    const uint8_t *base = wq + (size_t)(step + j) * kW4StripBytes;
+                    a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + lane);
+                    sc[j] = *reinterpret_cast<const uint2 *>(base + 1024 + gq * 8);     // rows 4 gq .. 4 gq + 3
+                    zr[j] = *reinterpret_cast<const uint2 *>(base + 1056 + gq * 8);
+                }
+#pragma unroll
+            for (int j = 0; j < kColDepth; ++j) {
+                if (step + j >= s1) break;
+                f32x8 xv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    xv[q] = load_act8(xp[0], (step + j) * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid[0]);
+                f32x4 u0 = f32x4{0.f, 0.f, 0.f, 0.f}, u1 = u0, xs = u0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t w = a[j][q];
+                    const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
+                                           ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u};
+                    const bf16x8 aw = __builtin_bit_cast(bf16x8, wi);
+                    bf16x8 bh, bl;
+                    split_bf16(xv[q], &bh, &bl);
+                    if (q & 1) {
+                        u1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u1, 0, 0, 0);
+                        u1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u1, 0, 0, 0);
+                    } else {
+                        u0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u0, 0, 0, 0);
+                        u0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u0, 0, 0, 0);
+                    }
+                    xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh, xs, 0, 0, 0);     // sum of x over the group
+                    xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl, xs, 0, 0, 0);
+                }
+                const float scl[4] = {__uint_as_float(sc[j].x << 16), __uint_as_float(sc[j].x & 0xffff0000u),
+                                      __uint_as_float(sc[j].y << 16), __uint_as_float(sc[j].y & 0xffff0000u)};
+                const float zpt[4] = {__uint_as_float(zr[j].x << 16), __uint_as_float(zr[j].x & 0xffff0000u),
+                                      __uint_as_float(zr[j].y << 16), __uint_as_float(zr[j].y & 0xffff0000u)};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[0][0][v] += scl[v] * ((u0[v] + u1[v]) - zpt[v] * xs[v]);
+            }
+        }
+    } else {
     const u32x4 *wbase = reinterpret_cast<const u32x4 *>(g.wpack) + (size_t)blockIdx.x * ns * kStripVec + lane;
     for (int step = s0; step < s1; step += kColDepth) {
         u32x4 a[kColDepth * 4];
@@ -471,6 +566,7 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
             }
         }
     }
+    }
 
     // acc[.][mt][v] = y[token mt*16 + i][column 4*gq + v of the strip] over this wavefront's K steps
     __shared__ float red[kColWaves][16][17];
@@ -487,17 +583,21 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
             for (int w = 0; w < kColWaves; ++w) v += red[w][en][emm];
             if (tok < g.M && ecol < g.N) {
                 const size_t o = (size_t)tok * g.N + ecol;
-                v += e_res[mt];
-                g.x_resid[o] = v;
-                if (g.xg_out) g.xg_out[o] = v * e_gain;
-                sq = v * v;
+                if (g.x_resid) {
+                    v += e_res[mt];
+                    g.x_resid[o] = v;
+                    if (g.xg_out) g.xg_out[o] = v * e_gain;
+                    sq = v * v;
+                } else {
+                    g.partial[o] = v;                        // one slot: the projection's output itself
+                }
             }
             // the 16 columns of one row sit in 16 consecutive lanes
             sq += __shfl_xor(sq, 8, 64);
             sq += __shfl_xor(sq, 4, 64);
             sq += __shfl_xor(sq, 2, 64);
             sq += __shfl_xor(sq, 1, 64);
-            if (en == 0 && tok < g.M) g.sumsq_out[(size_t)blockIdx.x * g.M + tok] = sq;
+            if (en == 0 && tok < g.M && g.sumsq_out) g.sumsq_out[(size_t)blockIdx.x * g.M + tok] = sq;
         }
     }
 }
@@ -684,6 +784,24 @@ void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void 
     }
 }
 
+size_t gemm_pack_w4_bytes(const int *n, int nseg, int K) {
+    size_t strips = 0;
+    for (int s = 0; s < nseg; ++s) strips += (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * 4;
+    return strips * (K / kSkinnyStepK) * kW4StripBytes;
+}
+
+void launch_gemm_pack_w4(const void *const *q, const void *const *scale, const void *const *zero, const int *n,
+                         int nseg, int K, void *dst, hipStream_t stream) {
+    uint8_t *out = (uint8_t *)dst;
+    const int ns = K / kSkinnyStepK;
+    for (int s = 0; s < nseg; ++s) {
+        const size_t strips = (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * 4;
+        launch_kernel(gemm_pack_w4_kernel, (unsigned)(strips * ns), 64, 0, stream, (const uint8_t *)q[s],
+                      (const uint16_t *)scale[s], (const uint8_t *)zero[s], n[s], K, out);
+        out += strips * ns * kW4StripBytes;
+    }
+}
+
 int gemm_packed_splits(int M, int K, const int *n, int nseg) {
     const int tiles = tiles_of(n, nseg, kSkinnyRows);
     if (gemm_use_stream(tiles)) return gemm_stream_slots(tiles, K);
@@ -714,10 +832,11 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         launch_kernel(gemm_f32_kernel, (g.N + 3) / 4, 256, 0, stream, g);
         return;
     }
-    if (g.M <= kStreamMaxRows && g.wpack && g.x_resid) {
+    if (g.M <= kStreamMaxRows && g.wpack && (g.x_resid || g.w4)) {
         ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
-        const int grid = g.N / 16;                        // N = d_model is a multiple of 128; M <= 16: one row tile
-        launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
+        const int grid = g.N / 16;                        // every segment is a multiple of 64 wide; M <= 16: one row tile
+        if (g.w4) launch_kernel(gemm_bf16_column_kernel<1, 16, true>, grid, 1024, 0, stream, g);
+        else launch_kernel(gemm_bf16_column_kernel<1, 16, false>, grid, 1024, 0, stream, g);
         return;
     }
     if (g.M <= kStreamMaxRows && g.wpack && gemm_use_stream(g.pack_tiles)) {

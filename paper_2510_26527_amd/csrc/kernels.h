@@ -68,6 +68,10 @@ struct GemmArgs {
     float *xg_out;
     const void *gain;             // [N] bf16
     float *sumsq_out;             // [N/16][M]
+    // -- 4-bit weights (W4A16, groups of 128 along K): wpack holds the strip-major 4-bit layout of
+    // launch_gemm_pack_w4 and every projection runs on the one-slot column kernel (S = 1 partial, or the
+    // residual epilogue above)
+    bool w4;
     RowScale scale;               // applied when writing `reduced` (row = the source row of m)
     int scale_rows;               //   rows per tile slab of scale.sumsq
 };
@@ -81,6 +85,11 @@ int gemm_stream_grid(int tiles, int K);
 int gemm_stream_slots(int tiles, int K);
 // strip_major: the layout of the one-slot column kernel (projections with N = d_model)
 void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, bool strip_major, hipStream_t stream);
+// 4-bit weight-only quantised projections: q [n][K/2] bytes (low nibble = even k), scale bf16 [n][K/128],
+// zero u8 [n][K/128]; w = scale * (q - zero).  Each n[s] a multiple of 64.
+size_t gemm_pack_w4_bytes(const int *n, int nseg, int K);
+void launch_gemm_pack_w4(const void *const *q, const void *const *scale, const void *const *zero, const int *n,
+                         int nseg, int K, void *dst, hipStream_t stream);
 void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention (attention.hip)

@@ -8,6 +8,7 @@ import torch
 import paper_2510_26527_amd as psd
 
 _LAYER_WEIGHTS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+_QUANT_WEIGHTS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
 
 
 def weight_order(n_layers):
@@ -20,8 +21,10 @@ def weight_order(n_layers):
 class Model:
     """A psd_model handle plus the weight tensors it points at (kept alive here)."""
 
-    def __init__(self, shape, weights, device="cuda"):
+    def __init__(self, shape, weights, device="cuda", quant=None):
         # shape: any object with the psd_model_desc field names; weights: name -> tensor
+        # quant: for a 4-bit model, name -> (scale bf16 [n, K/128], zero uint8 [n, K/128]) for every projection;
+        #        weights[name] then holds the codes, uint8 [n, K/2]
         dt = weights["embed"].dtype
         self.dtype = dt
         self.code = psd.dtype_code(dt)
@@ -32,7 +35,16 @@ class Model:
                                        self.code)
         self.shape = shape
         ptrs = [self.weights[n].data_ptr() for n in weight_order(shape.n_layers)]
-        self.handle = psd.psd_model_create(self.desc, ptrs)
+        self.quant = None
+        self.max_rows_per_call = None
+        if quant is None:
+            self.handle = psd.psd_model_create(self.desc, ptrs)
+        else:
+            self.quant = {k: (s.to(self.device).contiguous(), z.to(self.device).contiguous()) for k, (s, z) in quant.items()}
+            names = [f"l{l}.{n}" for l in range(shape.n_layers) for n in _QUANT_WEIGHTS]
+            self.handle = psd.psd_model_create_w4(self.desc, ptrs, [self.quant[n][0].data_ptr() for n in names],
+                                                  [self.quant[n][1].data_ptr() for n in names])
+            self.max_rows_per_call = 16
         self._ws = None
         self.packed = None
 

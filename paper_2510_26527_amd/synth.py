@@ -174,3 +174,28 @@ def make_tape(seed: int, level: int, calls: int, width: int):
     (Philox keyed by seed and level) so both sides index the same numbers by (call, slot)."""
     rng = np.random.Generator(np.random.Philox(key=[seed, level]))
     return rng.random((calls, width), dtype=np.float32)
+
+
+QUANT_WEIGHTS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+def quantize_w4(weights, group=128):
+    """4-bit weight-only quantisation of every projection matrix by plain round-to-nearest per group of `group`
+    input channels (asymmetric: scale = (max - min) / 15 rounded to bf16, zero = round(-min / scale) in 0..15),
+    a stand-in for the calibrated quantiser the paper's intermediate model uses.  Returns (codes_and_rest, quant):
+    the weight dict with each projection replaced by its codes, uint8 [n, K/2] (low nibble = even k), and
+    quant[name] = (scale bf16 [n, K/group], zero uint8 [n, K/group])."""
+    out, quant = dict(weights), {}
+    for name, w in weights.items():
+        if name.split(".")[-1] not in QUANT_WEIGHTS:
+            continue
+        n, K = w.shape
+        g = w.float().reshape(n, K // group, group)
+        lo, hi = g.amin(-1), g.amax(-1)
+        scale = ((hi - lo) / 15.0).clamp_min(1e-8).to(torch.bfloat16)
+        sf = scale.float()
+        zero = torch.round(-lo / sf).clamp(0, 15)
+        q = torch.round(g / sf[..., None] + zero[..., None]).clamp(0, 15).to(torch.uint8).reshape(n, K)
+        out[name] = (q[:, 0::2] | (q[:, 1::2] << 4)).contiguous()
+        quant[name] = (scale.contiguous(), zero.to(torch.uint8).contiguous())
+    return out, quant

@@ -43,10 +43,20 @@ class Pair:
     """The same model, cache contents and lengths on both sides."""
 
     def __init__(self, shape, dtype, batch, max_len, seed=0, ctx=None, lens=None, std=0.02, oracle_kv_dtype=np.float64,
-                 oracle_rows=None, pack=False, share=None):
+                 oracle_rows=None, pack=False, share=None, w4=False):
         self.shape, self.dtype, self.batch = shape, dtype, batch
         self.w = synth.make_weights(shape, seed, dtype, std=std, share=share)
-        self.model = runtime.Model(shape, self.w)
+        if w4:
+            # 4-bit projections: the GPU gets codes + scales + zero points, the oracle the dequantised matrices
+            from oracle import quant as oquant
+            codes, quant = synth.quantize_w4(self.w)
+            self.model = runtime.Model(shape, codes, quant=quant)
+            self.w = {k: (torch.from_numpy(oquant.dequantize(codes[k].numpy(), quant[k][0].float().numpy(),
+                                                               quant[k][1].numpy())) if k in quant else v)
+                      for k, v in self.w.items()}
+            pack = True
+        else:
+            self.model = runtime.Model(shape, self.w)
         if pack:
             self.model.pack()
         self.kv = runtime.KVCache(self.model, batch, max_len, fill_garbage=True)
@@ -240,3 +250,31 @@ def test_workload4_chain_models_full_size():
     e = mid.step(toks[:, :7], what="intermediate 7 rows")
     _progress(f"w4: intermediate rel err {e:.3e}")
     mid.close()
+
+
+@pytest.mark.parametrize("shape,steps,ctx", [
+    (SMALL_GQA, (1, 8, 16, 3), 300), (SMALL_MHA, (9, 16), 77), (SMALL_G7, (5, 11), 520), (SMALL_GQA, (16, 16, 16), 0),
+])
+def test_w4_small_models(shape, steps, ctx):
+    """4-bit weight-only quantised projections (the format of the paper's intermediate model): steps of 1 to 16
+    rows, with and without cached context, against the oracle run on the dequantised weights."""
+    max_len = (ctx + sum(steps) + 17 + 63) // 64 * 64
+    p = Pair(shape, torch.bfloat16, 1, max_len, seed=ctx + 1, ctx=ctx or None, std=0.05, w4=True)
+    toks = synth.make_tokens(shape.vocab, (1, sum(steps)), ctx + 2)
+    at, errs = 0, []
+    for n in steps:
+        errs.append(p.step(toks[:, at:at + n], what=f"{n} rows"))
+        at += n
+    print("w4 rel err", errs)
+    with pytest.raises(psd.PsdError) as e:                 # more than 16 rows per call: not built for 4-bit models
+        runtime.forward(p.model, p.kv, torch.zeros((1, 17), dtype=torch.int32, device="cuda"))
+    assert e.value.status == psd.PSD_ERR_UNIMPLEMENTED
+    p.close()
+
+
+def test_w4_batch_of_sequences():
+    p = Pair(SMALL_GQA, torch.bfloat16, 4, 448, seed=8, ctx=384, lens=[384, 10, 200, 77], std=0.05, w4=True)
+    toks = synth.make_tokens(SMALL_GQA.vocab, (4, 8), 5)
+    p.step(toks[:, :4], what="4 sequences x 4 rows")
+    p.step(toks[:, 4:8], n_logit_rows=2, what="4 x 4 rows, last 2 logits rows")
+    p.close()
