@@ -447,7 +447,7 @@ __global__ __launch_bounds__(64) void gemm_pack_w4_kernel(const uint8_t *Q, cons
     }
 }
 
-template <int MT, int kColWaves, bool W4>
+template <int MT, int kColWaves>
 __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
@@ -481,57 +481,6 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[h][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if constexpr (W4) {
-        static_assert(MT == 1, "4-bit weights: one row tile");
-        const uint8_t *wq = (const uint8_t *)g.wpack + (size_t)blockIdx.x * ns * kW4StripBytes;
-        const u32x4 ones4 = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
-        for (int step = s0; step < s1; step += kColDepth) {
-            u32x4 a[kColDepth];
-            uint2 sc[kColDepth], zr[kColDepth];
-#pragma unroll
-            for (int j = 0; j < kColDepth; ++j)
-                if (step + j < s1) {
-                    const uint8_t *base = wq + (size_t)(step + j) * kW4StripBytes;
-                    a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + lane);
-                    sc[j] = *reinterpret_cast<const uint2 *>(base + 1024 + gq * 8);     // rows 4 gq .. 4 gq + 3
-                    zr[j] = *reinterpret_cast<const uint2 *>(base + 1056 + gq * 8);
-                }
-#pragma unroll
-            for (int j = 0; j < kColDepth; ++j) {
-                if (step + j >= s1) break;
-                f32x8 xv[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    xv[q] = load_act8(xp[0], (step + j) * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid[0]);
-                f32x4 u0 = f32x4{0.f, 0.f, 0.f, 0.f}, u1 = u0, xs = u0;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t w = a[j][q];
-                    const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
-                                           ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u};
-                    const bf16x8 aw = __builtin_bit_cast(bf16x8, wi);
-                    bf16x8 bh, bl;
-                    split_bf16(xv[q], &bh, &bl);
-                    if (q & 1) {
-                        u1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u1, 0, 0, 0);
-                        u1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u1, 0, 0, 0);
-                    } else {
-                        u0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u0, 0, 0, 0);
-                        u0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u0, 0, 0, 0);
-                    }
-                    xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh, xs, 0, 0, 0);     // sum of x over the group
-                    xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl, xs, 0, 0, 0);
-                }
-                const float scl[4] = {__uint_as_float(sc[j].x << 16), __uint_as_float(sc[j].x & 0xffff0000u),
-                                      __uint_as_float(sc[j].y << 16), __uint_as_float(sc[j].y & 0xffff0000u)};
-                const float zpt[4] = {__uint_as_float(zr[j].x << 16), __uint_as_float(zr[j].x & 0xffff0000u),
-                                      __uint_as_float(zr[j].y << 16), __uint_as_float(zr[j].y & 0xffff0000u)};
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[0][0][v] += scl[v] * ((u0[v] + u1[v]) - zpt[v] * xs[v]);
-            }
-        }
-    } else {
     const u32x4 *wbase = reinterpret_cast<const u32x4 *>(g.wpack) + (size_t)blockIdx.x * ns * kStripVec + lane;
     for (int step = s0; step < s1; step += kColDepth) {
         u32x4 a[kColDepth * 4];
@@ -566,7 +515,6 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
             }
         }
     }
-    }
 
     // acc[.][mt][v] = y[token mt*16 + i][column 4*gq + v of the strip] over this wavefront's K steps
     __shared__ float red[kColWaves][16][17];
@@ -599,6 +547,118 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
             sq += __shfl_xor(sq, 1, 64);
             if (en == 0 && tok < g.M && g.sumsq_out) g.sumsq_out[(size_t)blockIdx.x * g.M + tok] = sq;
         }
+    }
+}
+
+// ------------------------------------------------------------------------------ 4-bit weights, M <= 16
+// One block per 64 output columns (four strips of the strip-major 4-bit layout) over the whole K range, eight
+// wavefronts on different K ranges, added through LDS in wavefront order; single owner per output, the same
+// epilogue as the column kernel (plain output, or residual add + gain-scaled copy + per-strip sums of squares).
+// 4-bit weights are a quarter of the bytes, so the activations (4 bytes each, re-read by every block) weigh
+// as much as the weights of a 64-row tile; a 16-row strip per block would read four times more of them.
+// Per group of 128 K (one step): u = sum (128 + q) x on the matrix cores with the codes as exact bf16
+// integers, xs = sum x with an all-ones operand, then acc += scale * (u - (128 + zero) * xs) in fp32.
+constexpr int kW4Waves = 16, kW4Strips = 2, kW4Cols = 16 * kW4Strips;
+
+__global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, gq = lane >> 4;
+    const int K = g.K, ns = K / kSkinnyStepK;
+    const int s0 = wave * ns / kW4Waves, s1 = (wave + 1) * ns / kW4Waves;
+    const bool xvalid = i < g.M;
+    const float *xp = g.x + x_row(g, min(i, g.M - 1)) * K + gq * 16;
+    const uint8_t *wq = (const uint8_t *)g.wpack + (size_t)blockIdx.x * kW4Strips * ns * kW4StripBytes;
+    const size_t strip_stride = (size_t)ns * kW4StripBytes;
+    const u32x4 ones4 = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+
+    f32x4 acc[kW4Strips];
+#pragma unroll
+    for (int s = 0; s < kW4Strips; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    constexpr int D = 4;                                   // K steps per round: 8 KB of codes in flight per wavefront
+    for (int step = s0; step < s1; step += D) {
+        u32x4 a[D][kW4Strips];
+        uint2 sc[D][kW4Strips], zr[D][kW4Strips];
+#pragma unroll
+        for (int j = 0; j < D; ++j)
+            if (step + j < s1) {
+#pragma unroll
+                for (int s = 0; s < kW4Strips; ++s) {
+                    const uint8_t *base = wq + s * strip_stride + (size_t)(step + j) * kW4StripBytes;
+                    a[j][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + lane);
+                    sc[j][s] = *reinterpret_cast<const uint2 *>(base + 1024 + gq * 8);     // rows 4 gq .. 4 gq + 3
+                    zr[j][s] = *reinterpret_cast<const uint2 *>(base + 1056 + gq * 8);
+                }
+            }
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            if (step + j >= s1) break;
+            f32x8 xv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                xv[q] = load_act8(xp, (step + j) * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid);
+            f32x4 u[kW4Strips], xs = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < kW4Strips; ++s) u[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x8 bh, bl;
+                split_bf16(xv[q], &bh, &bl);
+#pragma unroll
+                for (int s = 0; s < kW4Strips; ++s) {
+                    const uint32_t w = a[j][s][q];
+                    const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
+                                           ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u};
+                    const bf16x8 aw = __builtin_bit_cast(bf16x8, wi);
+                    u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u[s], 0, 0, 0);
+                    u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u[s], 0, 0, 0);
+                }
+                xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh, xs, 0, 0, 0);       // sum of x over the group
+                xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl, xs, 0, 0, 0);
+            }
+#pragma unroll
+            for (int s = 0; s < kW4Strips; ++s) {
+                const float scl[4] = {__uint_as_float(sc[j][s].x << 16), __uint_as_float(sc[j][s].x & 0xffff0000u),
+                                      __uint_as_float(sc[j][s].y << 16), __uint_as_float(sc[j][s].y & 0xffff0000u)};
+                const float zpt[4] = {__uint_as_float(zr[j][s].x << 16), __uint_as_float(zr[j][s].x & 0xffff0000u),
+                                      __uint_as_float(zr[j][s].y << 16), __uint_as_float(zr[j][s].y & 0xffff0000u)};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[s][v] += scl[v] * (u[s][v] - zpt[v] * xs[v]);
+            }
+        }
+    }
+
+    // acc[s][v] = y[token i][tile column s*16 + 4*gq + v] over this wavefront's K steps
+    __shared__ float red[kW4Waves][kW4Cols][17];
+#pragma unroll
+    for (int s = 0; s < kW4Strips; ++s)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][v];
+    __syncthreads();
+    // thread t < 512: column n = t & 15 of strip t >> 8, token mm = (t >> 4) & 15
+    if (threadIdx.x < 256 * kW4Strips) {
+        const int en = threadIdx.x & 15, emm = (threadIdx.x >> 4) & 15, strip = threadIdx.x >> 8;
+        const int col = blockIdx.x * kW4Cols + strip * 16 + en;
+        float v = 0.f, sq = 0.f;
+#pragma unroll
+        for (int w = 0; w < kW4Waves; ++w) v += red[w][strip * 16 + en][emm];
+        if (emm < g.M && col < g.N) {
+            const size_t o = (size_t)emm * g.N + col;
+            if (g.x_resid) {
+                v += g.x_resid[o];
+                g.x_resid[o] = v;
+                if (g.xg_out) g.xg_out[o] = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
+                sq = v * v;
+            } else {
+                g.partial[o] = v;
+            }
+        }
+        sq += __shfl_xor(sq, 8, 64);
+        sq += __shfl_xor(sq, 4, 64);
+        sq += __shfl_xor(sq, 2, 64);
+        sq += __shfl_xor(sq, 1, 64);
+        if (en == 0 && emm < g.M && g.sumsq_out) g.sumsq_out[(size_t)(blockIdx.x * kW4Strips + strip) * g.M + emm] = sq;
     }
 }
 
@@ -835,8 +895,8 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
     if (g.M <= kStreamMaxRows && g.wpack && (g.x_resid || g.w4)) {
         ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
         const int grid = g.N / 16;                        // every segment is a multiple of 64 wide; M <= 16: one row tile
-        if (g.w4) launch_kernel(gemm_bf16_column_kernel<1, 16, true>, grid, 1024, 0, stream, g);
-        else launch_kernel(gemm_bf16_column_kernel<1, 16, false>, grid, 1024, 0, stream, g);
+        if (g.w4) launch_kernel(gemm_w4_tile_kernel, g.N / kW4Cols, kW4Waves * 64, 0, stream, g);
+        else launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
         return;
     }
     if (g.M <= kStreamMaxRows && g.wpack && gemm_use_stream(g.pack_tiles)) {

@@ -24,7 +24,8 @@ class AgreementShimChain(Chain):
     def __init__(self, levels, gammas, tapes, sigma, noise_seed=0, noise_terms=None, **kw):
         """noise_terms[i]: how many of the N_j vectors level i's rows carry (default i: each level one more than
         the level above it; a two-level chain whose draft should sit as far from the target as the draft of a
-        three-level chain passes [0, 2])."""
+        three-level chain passes [0, 2]; 0 for a level below the target leaves that level's own
+        logits in place, e.g. a quantised copy of the target that needs no help to agree with it)."""
         super().__init__(levels, gammas, tapes, **kw)
         self.noise_terms = list(noise_terms) if noise_terms is not None else list(range(len(levels)))
         tgt = levels[0]
@@ -42,8 +43,8 @@ class AgreementShimChain(Chain):
         return torch.randn(self.vocab, dtype=torch.float32, device=self.dev, generator=self._gen)
 
     def _rows_ready(self, i, dst, n_logit_rows):
-        if i == 0 or dst is None or n_logit_rows == 0:
-            return
+        if i == 0 or dst is None or n_logit_rows == 0 or self.noise_terms[i] == 0:
+            return             # the target, or a level that keeps its own logits (noise_terms 0)
         tgt = self.levels[0]
         keep = tgt.kv_len
         n_new = self.seq_len - keep
