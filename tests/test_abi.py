@@ -64,6 +64,28 @@ def test_model_create_validation(lib):
     assert psd.status_string(psd.PSD_ERR_CAPACITY) == "KV cache capacity exceeded"
 
 
+def test_w4_model_create_validation(lib):
+    d = _desc()
+    n, nq = 3 + 9 * d.n_layers, 7 * d.n_layers
+    m = psd.psd_model_create_w4(d, [0x1000] * n, [0x2000] * nq, [0x3000] * nq)
+    assert psd.psd_model_packed_bytes(m) > 0
+    # a 4-bit model must be packed before its first forward; nothing is launched
+    kv = ctypes.c_void_p()
+    assert lib.psd_kv_create(m, 1, 128, 0x1000, 0x2000, 0x3000, 0, ctypes.byref(kv)) == psd.PSD_OK
+    assert lib.psd_model_forward(m, 0x1000, 4, kv, 0x2000, 4, 0x4000, 1 << 30, 0) == psd.PSD_ERR_UNIMPLEMENTED
+    psd.psd_kv_destroy(kv)
+    psd.psd_model_destroy(m)
+    for args, code in ((([0x1000] * n, [0x2000] * (nq - 1), [0x3000] * (nq - 1)), psd.PSD_ERR_SHAPE),
+                       (([0x1000] * n, [0] * nq, [0x3000] * nq), psd.PSD_ERR_NULL),
+                       (([0x1000] * n, [0x2001] * nq, [0x3000] * nq), psd.PSD_ERR_SHAPE)):
+        with pytest.raises(psd.PsdError) as e:
+            psd.psd_model_create_w4(d, *args)
+        assert e.value.status == code
+    with pytest.raises(psd.PsdError) as e:
+        psd.psd_model_create_w4(_desc(dtype=psd.PSD_F32), [0x1000] * n, [0x2000] * nq, [0x3000] * nq)
+    assert e.value.status == psd.PSD_ERR_DTYPE
+
+
 def test_kv_and_forward_validation(lib):
     m = _create(_desc())
     assert psd.psd_kv_bytes(m, 2, 128) == 1 * 2 * 2 * 128 * 64 * 2
