@@ -375,10 +375,10 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         g.w4 = m->w4;
         launch_gemm(d.dtype, g, st);
     };
-    // Folded mode: no RMSNorm kernel runs.  The projections that read the residual stream multiply it by
-    // the norm gain while loading it, the kernels that consume their output multiply by the row scale
-    // rsqrt(mean x^2 + eps), and the projections that write the residual stream add into it and leave
-    // per-16-column sums of squares behind (one slab of M floats per block).
+    // Folded mode: no RMSNorm kernel runs.  The projections that write the residual stream add into it and
+    // leave behind x * gain of the next norm (in xn) and per-16-column sums of squares (one slab of M floats
+    // per strip); the projections that read the residual stream take xn as it is, and the kernels that consume
+    // their output multiply by the row scale rsqrt(mean x^2 + eps).
     float *sumsq = (float *)(ws + p.off_sumsq);
     const int col_tiles = d.d_model / 16;
     RowScale rs{nullptr, 0, 1.0f / (float)d.d_model, d.rms_eps};
