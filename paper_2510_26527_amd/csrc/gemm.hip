@@ -1,6 +1,6 @@
 // Decoder projections y[m][n] = sum_k x[m][k] W[n][k] on gfx950.
 //
-// Three kernels, chosen by model dtype and row count M (M = batch * n_new of a verify step):
+// The kernels, chosen by model dtype and row count M (M = batch * n_new of a verify step):
 //   gemm_f32_kernel          fp32 weights, plain ALU dot products, one wavefront per output
 //                            column (the tiny fp32 chain; fp32 1e-4 parity, not speed).
 //   gemm_bf16_skinny_kernel  M <= 16.  HBM-bound weight streaming: W rows go straight from
@@ -15,12 +15,16 @@
 //   gemm_bf16_column_kernel  M <= 16, the projections that write the residual stream: one block per 16
 //                            output columns over the whole K range; the residual add, the gain-scaled copy
 //                            and the RMSNorm statistics happen in its epilogue.
-//   gemm_bf16_tiled_kernel   M > 16.  128 x (128..256) x 64 LDS-staged tiles, 32x32x16 bf16 MFMA.
+//   gemm_w4_tile_kernel      M <= 16, 4-bit weight-only quantised projections (groups of 128 along K): one
+//                            block per 32 output columns, the codes multiplied as exact bf16 integers, scale
+//                            and zero point applied per group in fp32, the same epilogue.
+//   gemm_bf16_tiled_kernel   M > 16.  128 x (128..224) x 64 LDS-staged tiles, 32x32x16 bf16 MFMA.
 // Activations are fp32 in memory in every case.  The bf16 kernels feed each activation to the
 // matrix cores as a pair of bf16 values hi + lo (two MFMAs against the same weight operand):
 // with plain bf16 activations the logits of the 7B-shaped random-init models are 3e-2 off the
 // fp64 result, above the 2e-2 bar; the weights, which are what streams from HBM, stay bf16.
-// Every kernel writes its result as split-K partials [splitk][M][N] (splitk >= 1); the consumer
+// Every kernel but the two single-owner ones writes its result as split-K partials [splitk][M][N]
+// (splitk >= 1); the consumer
 // (the fused row-wise kernels, or gemm_splitk_reduce_kernel for the logits) adds them in split
 // order, so results are bit-reproducible.
 #include "common.h"
