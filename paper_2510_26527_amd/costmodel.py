@@ -30,3 +30,14 @@ def insertion_criterion(T_new, T_i, T_next, L_new, L_i, L_i_new, beta):
     c1 = (T_new / T_i, L_new * (1.0 / L_i - 1.0 / L_i_new))
     c2 = (T_new / T_next, beta * (L_new / L_i - 1.0))
     return c1, c2, (c1[0] < c1[1]) or (c2[0] < c2[1])
+
+
+def insertion_time_change(N, T_new, T_i, T_next, L_new, L_i, L_i_new, beta):
+    """The quantity the proof of Theorem 3.2 starts from: (three-model time) - (two-model time) by Lemma 3.1
+    with the same beta and an unchanged drafter,
+        N (1/L_{i-new} - 1/L_i) T_i + (N/L_new) T_new + beta N (1/L_new - 1/L_i) T_{i+1}.
+    Negative: the insertion is predicted to pay off.  The theorem's two conditions say that the first two, or
+    the last two, of these terms already sum to less than zero; each is sufficient when
+    L_{i-new} > L_new > L_i, neither is necessary."""
+    return (N * (1.0 / L_i_new - 1.0 / L_i) * T_i + N / L_new * T_new
+            + beta * N * (1.0 / L_new - 1.0 / L_i) * T_next)

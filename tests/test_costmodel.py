@@ -26,4 +26,23 @@ def test_insertion_criterion_on_table1():
         T_i, L_i_new, T_new, L_new, T_next, L_i, s0, s1 = (float(v) for v in f[1:9])
         c1, c2, helps = costmodel.insertion_criterion(T_new, T_i, T_next, L_new, L_i, L_i_new, beta=1.0)
         assert c1 == pytest.approx(theory.insertion_gain(T_new, T_i, L_new, L_i, L_i_new))
+        assert c2 == pytest.approx(theory.insertion_gain_lower(T_new, T_next, L_new, L_i, 1.0))
         assert (c1[0] < c1[1]) == (s1 > s0), f[0]
+
+
+def test_insertion_criterion_matches_the_oracle_on_random_inputs():
+    import numpy as np
+    rng = np.random.default_rng(5)
+    for _ in range(500):
+        T_new, T_i, T_next = rng.uniform(0.1, 30, 3)
+        L_new, L_i, L_i_new = rng.uniform(1.05, 12, 3)
+        beta = rng.uniform(0.2, 10)
+        c1, c2, helps = costmodel.insertion_criterion(T_new, T_i, T_next, L_new, L_i, L_i_new, beta)
+        o1 = theory.insertion_gain(T_new, T_i, L_new, L_i, L_i_new)
+        o2 = theory.insertion_gain_lower(T_new, T_next, L_new, L_i, beta)
+        assert c1 == pytest.approx(o1, rel=1e-12) and c2 == pytest.approx(o2, rel=1e-12)
+        assert helps == ((o1[0] < o1[1]) or (o2[0] < o2[1]))
+        d = costmodel.insertion_time_change(1.0, T_new, T_i, T_next, L_new, L_i, L_i_new, beta)
+        ref = theory.lemma31_time(1.0, [L_i_new, L_new], [T_i, T_new, T_next], beta) - \
+            theory.lemma31_time(1.0, [L_i], [T_i, T_next], beta)
+        assert d == pytest.approx(ref, rel=1e-9, abs=1e-12)
