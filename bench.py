@@ -124,7 +124,7 @@ def main():
     def step():
         runtime.forward(model, kv, tokens, logits_out=p_buf)
         n, tok, fl = acc(p_buf, q_logits, draft, uniforms, temperature)
-        psd.psd_kv_truncate(kv.handle, base, n, 1)
+        psd.psd_kv_truncate(kv.handle, base, n, 1, ctx + 1 + gamma)
         psd.psd_kv_truncate_to(kv.handle, ctx)          # back to the benchmark's cache length
         out["n"] = n
 
@@ -196,8 +196,7 @@ def main():
               "algorithmic_bytes": a_bytes, "call_us": call_us, "GB/s": a_bytes / call_us / 1e3,
               "frac_of_hbm_peak": a_bytes / call_us / 1e3 / HBM_PEAK_GBS,
               "stats_kernel_us": stats_us, "stats_kernel_GB/s": a_bytes / stats_us / 1e3,
-              "emit_kernel_us": 1e3 * aprof["accept_emit"][0] / aprof["accept_emit"][1],
-              "locate_kernel_us": 1e3 * aprof["accept_locate"][0] / aprof["accept_locate"][1]}
+              "draw_kernel_us": 1e3 * aprof["accept_draw"][0] / aprof["accept_draw"][1]}
 
     # ---- the oracle on the host cores, one whole step of the same workload
     cpu_baseline = None
@@ -274,8 +273,8 @@ def stress_workload(args, dev):
     def step():
         runtime.forward(model, kv, tokens, logits_out=p_buf)
         n, tok, fl = acc(p_buf, q_logits, draft, uniforms, 1.0)
-        psd.psd_kv_truncate(kv.handle, base, n, 1)
-        psd.psd_kv_truncate_to(kv.handle, ctx)
+        psd.psd_kv_truncate(kv.handle, base, n, 1, ctx + 1 + gamma)
+        psd.psd_kv_truncate_to(kv.handle, ctx)          # back to the benchmark's cache length
         out["n"] = n
 
     steps, warmup = min(args.steps, 20), min(args.warmup, 3)

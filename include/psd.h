@@ -191,12 +191,18 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
                            void *workspace, size_t ws_bytes, void *hip_stream);
 
 /* Rollback after verification (Sec. 3.3): on the stream, for every sequence b,
- *   lens[b] <- min(lens[b], base_lens_dev[b] + keep_dev[b] + keep_offset)   (never below 0).
+ *   lens[b] <- min(lens[b], base_lens_dev[b] + keep_dev[b] + keep_offset, new_len_upper_bound)   (never below 0).
  * base_lens_dev / keep_dev are device int32[batch] (e.g. the lengths before the verify
  * forward and psd_spec_accept's out_accept_len; keep_offset = 1 keeps the x* row too).
+ * new_len_upper_bound: an upper bound, known to the host, of the lengths after the rollback: a
+ * decoding loop reads the accepted lengths back to steer itself and passes the largest
+ * base + keep + keep_offset.  The host-side bound behind psd_model_forward's capacity check (which
+ * otherwise only grows, by n_new per forward) is lowered to it, and the device enforces it too, so
+ * a loop of forward / accept / truncate needs no other call to keep that bound tight.  A negative
+ * value leaves the host bound as it is.
  * No data moves; stale rows are overwritten by the next append. */
 psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *keep_dev,
-                           int32_t keep_offset, void *hip_stream);
+                           int32_t keep_offset, int32_t new_len_upper_bound, void *hip_stream);
 /* Host-scalar variant: lens[b] <- min(lens[b], new_len) for all b; also lowers the host
  * upper bound to new_len. */
 psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
@@ -222,8 +228,8 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_SWIGLU 9
 #define PSD_KIND_LENS 10             /* length advance / truncate */
 #define PSD_KIND_ACCEPT_STATS 11
-#define PSD_KIND_ACCEPT_EMIT 12      /* fp64 pass over the one position the draw reads */
-#define PSD_KIND_ACCEPT_LOCATE 13
+#define PSD_KIND_ACCEPT_DRAW 12      /* first rejection + fp64 pass over the one position the draw reads */
+#define PSD_KIND_ACCEPT_LOCATE 13    /* greedy verification: the walk over the per-position argmax */
 #define PSD_KIND_GEMM_COLUMN 14      /* bf16 one-slot GEMM with the residual epilogue, M <= 16 */
 #define PSD_KIND_COUNT 15
 psd_status psd_profile_enable(int32_t max_launches);

@@ -46,14 +46,14 @@ _SIGNATURES = {
     "psd_spec_accept_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
     "psd_spec_accept": (_i32, [_vp, _vp, _vp, _i32, _vp, _f32, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i64,
                                _vp, _vp, _sz, _vp]),
-    "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _vp]),
+    "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "psd_kv_truncate_to": (_i32, [_vp, _i32, _vp]),
     "psd_profile_enable": (_i32, [_i32]),
     "psd_profile_collect": (_i32, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]),
 }
 
 PSD_KIND_NAMES = ("embed", "rmsnorm", "gemm_f32", "gemm_skinny", "gemm_tiled", "gemm_reduce", "rope_append", "attn",
-                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_emit", "accept_locate", "gemm_column")
+                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_draw", "accept_locate", "gemm_column")
 
 _lib = None
 
@@ -183,8 +183,9 @@ def psd_spec_accept(p_logits, q_logits, draft_tokens, gamma, uniforms, temperatu
                                  _stream_ptr(stream)), "psd_spec_accept")
 
 
-def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, stream=None):
-    _check(lib().psd_kv_truncate(kv, _ptr(base_lens_dev), _ptr(keep_dev), keep_offset, _stream_ptr(stream)),
+def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, new_len_upper_bound=-1, stream=None):
+    _check(lib().psd_kv_truncate(kv, _ptr(base_lens_dev), _ptr(keep_dev), keep_offset, new_len_upper_bound,
+                                 _stream_ptr(stream)),
            "psd_kv_truncate")
 
 

@@ -87,7 +87,7 @@ const char *psd_status_string(psd_status s) {
         case PSD_ERR_SHAPE: return "unsupported shape";
         case PSD_ERR_DTYPE: return "unsupported dtype";
         case PSD_ERR_CAPACITY: return "KV cache capacity exceeded";
-        case PSD_ERR_TEMPERATURE: return "temperature must be finite and > 0";
+        case PSD_ERR_TEMPERATURE: return "temperature must be finite and >= 0 (0 selects greedy verification)";
         case PSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case PSD_ERR_HIP: return "HIP launch failed";
         case PSD_ERR_UNIMPLEMENTED: return "not implemented";
@@ -313,6 +313,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
 bool forward_shape_ok(const psd_model *m, int batch, int n_new) {
     if (batch <= 0 || batch > 65535 || n_new <= 0) return false;
     if ((long)batch * n_new > 65535) return false;
+    if ((long)batch * m->d.n_kv_heads > 65535) return false;      // grid z of the attention launch
     if ((long)(m->d.n_q_heads / m->d.n_kv_heads) * n_new > 4096) return false;
     return true;
 }
@@ -486,11 +487,14 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
 }
 
 psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *keep_dev, int32_t keep_offset,
-                           void *hip_stream) {
+                           int32_t new_len_upper_bound, void *hip_stream) {
     if (!kv || !base_lens_dev || !keep_dev) return PSD_ERR_NULL;
+    const int cap = new_len_upper_bound < 0 || new_len_upper_bound > kv->len_ub ? kv->len_ub : new_len_upper_bound;
     (void)hipGetLastError();
-    launch_truncate(kv->lens, base_lens_dev, keep_dev, keep_offset, kv->batch, (hipStream_t)hip_stream);
-    return check_launch();
+    launch_truncate(kv->lens, base_lens_dev, keep_dev, keep_offset, cap, kv->batch, (hipStream_t)hip_stream);
+    const psd_status s = check_launch();
+    if (s == PSD_OK) kv->len_ub = cap;
+    return s;
 }
 
 psd_status psd_profile_enable(int32_t max_launches) {

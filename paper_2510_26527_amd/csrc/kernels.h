@@ -19,8 +19,9 @@ struct AcceptArgs {
     int chunkA, n_chunksA;        // statistics pass: elements per block, blocks per logits row
     int chunkE, n_chunksE;        // draw pass chunking
     float2 *stats;                // [rows][n_p_rows+gamma][n_chunksA] (max raw logit, sum exp)
-    double2 *zpart;               // [rows][n_chunksE] fp64 partial softmax denominators (p, q)
-    double2 *ppart;               // [rows][n_chunksE] the same sums over the entries with positive residual
+    float *xlogit;                // [rows][gamma][2] the draft token's logit under p and under q
+    double *part;                 // [rows][n_chunksE][6] fp64 chunk sums of the draw position (accept.hip)
+    uint32_t *counter;            // [rows] chunks of the draw position done so far
     int32_t *out_n, *out_tok, *flags;
 };
 // vec: rows are 16-byte aligned and V is a multiple of the elements per 16-byte load
@@ -123,7 +124,7 @@ void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *
 // h = silu(g) * u with [g | u] = sum over splits of partial [S][M][2f]
 void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, hipStream_t stream);
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream);
-void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B,
+void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int cap, int B,
                      hipStream_t stream);
 void launch_truncate_to(int32_t *lens, int new_len, int B, hipStream_t stream);
 

@@ -203,9 +203,9 @@ __global__ void advance_lens_kernel(int32_t *lens, int B, int delta, int max_len
     if (b < B) lens[b] = min(lens[b] + delta, max_len);
 }
 
-__global__ void truncate_kernel(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B) {
+__global__ void truncate_kernel(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int cap, int B) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) lens[b] = max(0, min(lens[b], base[b] + keep[b] + offset));
+    if (b < B) lens[b] = max(0, min(min(lens[b], cap), base[b] + keep[b] + offset));
 }
 
 __global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
@@ -262,9 +262,10 @@ void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream
     ScopedProf sp(PSD_KIND_LENS, stream);
     launch_kernel(advance_lens_kernel, (B + 63) / 64, 64, 0, stream, lens, B, delta, max_len);
 }
-void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int B, hipStream_t stream) {
+void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int cap, int B,
+                     hipStream_t stream) {
     ScopedProf sp(PSD_KIND_LENS, stream);
-    launch_kernel(truncate_kernel, (B + 63) / 64, 64, 0, stream, lens, base, keep, offset, B);
+    launch_kernel(truncate_kernel, (B + 63) / 64, 64, 0, stream, lens, base, keep, offset, cap, B);
 }
 void launch_truncate_to(int32_t *lens, int new_len, int B, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_LENS, stream);

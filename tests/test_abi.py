@@ -108,7 +108,7 @@ def test_kv_and_forward_validation(lib):
     assert f(m, 0x4000, 4, kv, 0x5000, 4, 0x10000, 16, 0) == psd.PSD_ERR_WORKSPACE    # too small
     assert f(m, 0x4000, 4, kv, 0x5000, 4, 0x10010, need, 0) == psd.PSD_ERR_WORKSPACE  # misaligned
     assert f(m, 0x4000, 0, kv, 0x5000, 0, 0x10000, need, 0) == psd.PSD_ERR_SHAPE
-    assert L.psd_kv_truncate(kv, 0, 0x1000, 1, 0) == psd.PSD_ERR_NULL
+    assert L.psd_kv_truncate(kv, 0, 0x1000, 1, -1, 0) == psd.PSD_ERR_NULL
     assert L.psd_kv_truncate_to(kv, -1, 0) == psd.PSD_ERR_SHAPE
     psd.psd_kv_destroy(kv)
     psd.psd_model_destroy(m)

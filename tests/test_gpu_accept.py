@@ -35,6 +35,9 @@ def _compare(inp, temperature=1.0, n_p_rows=None):
     assert not np.any(tok_mismatch), f"emitted token differs: rows {np.nonzero(tok_mismatch)[0][:8]}, gpu {tok[tok_mismatch][:8]} oracle {otok[tok_mismatch][:8]}"
     # the kernel's own near-tie flag covers every excused row
     assert np.all((fl[len_mismatch] & psd.PSD_FLAG_NEAR_TIE) != 0)
+    # "the residual was empty, the draw used p" is reported for the same rows
+    zr, ozr = (fl & psd.PSD_FLAG_ZERO_RESIDUAL) != 0, (ofl & oacc.FLAG_ZERO_RESIDUAL) != 0
+    assert np.array_equal(zr[same], ozr[same]), f"zero-residual flag differs: rows {np.nonzero(same & (zr != ozr))[0][:8]}"
     assert np.all(n >= 0) and np.all(n <= inp["q"].shape[1])
     print(f"rows {len(n)}: near-tie rows {int(tie.sum())}, excused length flips {int(len_mismatch.sum())}, "
           f"mean accept_len {n.mean():.3f}")
@@ -102,6 +105,77 @@ def test_degenerate_inputs():
     torch.cuda.synchronize()
     ref = oacc.sample(_to_f64(inp["p"][:, 0]), _to_f64(inp["uniforms"][:, 0]))
     assert np.array_equal(tok.cpu().numpy(), ref) and np.all(n.cpu().numpy() == 0)
+
+
+def _one_entry_apart(V, mass_log, direction, seed, rows=4):
+    """q equals p except at one entry k per row whose probability under p is about exp(mass_log) and is doubled
+    ("raised") or halved ("lowered") under q.  The draft token of position 0 is k when raised (ratio 1/2,
+    rejected by u_0 = 0.75) and another token when lowered (ratio 1 - exp(mass_log)/2, rejected by the largest
+    fp32 uniform below 1).  fp32 logits, gamma = 2, bonus row present."""
+    rng = np.random.default_rng(seed)
+    gamma = 2
+    p = rng.normal(0.0, 2.0, (rows, gamma + 1, V)).astype(np.float32)
+    q = p[:, :gamma].copy()
+    k = rng.integers(0, V, rows)
+    x = rng.integers(0, V, (rows, gamma)).astype(np.int32)
+    u = rng.uniform(0.05, 0.95, (rows, gamma + 1)).astype(np.float32)
+    for b in range(rows):
+        lse = np.log(np.exp(p[b, 0].astype(np.float64)).sum())
+        p[b, 0, k[b]] = np.float32(lse + mass_log)
+        q[b, 0] = p[b, 0]
+        q[b, 0, k[b]] = p[b, 0, k[b]] + np.float32(np.log(2.0) * (1 if direction == "raised" else -1))
+        if direction == "raised":
+            x[b, 0] = k[b]
+            u[b, 0] = 0.75
+        else:
+            x[b, 0] = (k[b] + 1) % V
+            u[b, 0] = np.nextafter(np.float32(1.0), np.float32(0.0))
+    return {"p": torch.from_numpy(p), "q": torch.from_numpy(q), "tokens": torch.from_numpy(x),
+            "uniforms": torch.from_numpy(u)}, k
+
+
+def _draw_margin(inp, b):
+    """Distance of u * (residual mass) from the nearest step of the residual's running sum at position 0 of row b,
+    relative to the mass (numpy fp64; used only to keep the test's inputs away from a coin-flip draw)."""
+    lp, lq = inp["p"][b, 0].double().numpy(), inp["q"][b, 0].double().numpy()
+    pp = np.exp(lp - lp.max()); pp /= pp.sum()
+    qq = np.exp(lq - lq.max()); qq /= qq.sum()
+    r = np.maximum(pp - qq, 0.0)
+    C = np.cumsum(r)
+    t = float(inp["uniforms"][b, 2]) * r.sum()
+    return np.abs(C - t).min() / r.sum(), r.sum()
+
+
+@pytest.mark.parametrize("V", [3000, 40000])
+def test_residual_support_q_equals_p_but_for_one_raised_entry(V):
+    """Every other entry then has p_i - q_i = p_i (1 - Zp/Zq) > 0 by about 1e-9 p_i: a residual that exists only
+    in fp64.  The emitted token and the zero-residual flag (not set: the residual is not empty) must be the
+    oracle's."""
+    inp, k = _one_entry_apart(V, np.log(1e-9), "raised", seed=V)
+    # both sides compute these residual entries as differences of nearly equal numbers, good to ~1e-7 of their
+    # size: keep each row's draw 100 times further than that from a step of the running sum
+    rng = np.random.default_rng(V + 7)
+    for b in range(inp["p"].shape[0]):
+        for _ in range(200):
+            margin, mass = _draw_margin(inp, b)
+            assert 1e-10 < mass < 1e-8
+            if margin >= 2e-5:
+                break
+            inp["uniforms"][b, 2] = float(rng.uniform(0.05, 0.95))
+        assert margin >= 2e-5
+    n, tok, fl = _compare(inp)
+    assert np.all(n == 0) and np.all(tok != k)
+    assert np.all((fl & psd.PSD_FLAG_ZERO_RESIDUAL) == 0)
+
+
+@pytest.mark.parametrize("V", [3000, 40000])
+def test_residual_support_q_equals_p_but_for_one_lowered_entry(V):
+    """The residual is then the one lowered entry alone (every other p_i - q_i is negative by 5e-5 p_i); the
+    rejection has to come from another token, whose ratio 1 - 5e-5 only the largest uniform below 1 rejects."""
+    inp, k = _one_entry_apart(V, np.log(1e-4), "lowered", seed=V + 1)
+    n, tok, fl = _compare(inp)
+    assert np.all(n == 0) and np.array_equal(tok, k)
+    assert np.all((fl & psd.PSD_FLAG_ZERO_RESIDUAL) == 0)
 
 
 def test_strided_sequences_and_repeat_calls_are_deterministic():

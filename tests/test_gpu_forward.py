@@ -110,10 +110,10 @@ def test_fp32_batch_with_ragged_lengths_and_truncate():
     # roll back to base + keep + 1 per sequence on the device, mirror it in the oracle
     base = torch.tensor([20, 7, 13], dtype=torch.int32, device="cuda")
     keep = torch.tensor([5, 0, 2], dtype=torch.int32, device="cuda")
-    psd.psd_kv_truncate(p.kv.handle, base, keep, 1)
+    psd.psd_kv_truncate(p.kv.handle, base, keep, 1, 26)
     p.okv.truncate([26, 8, 16])
     torch.cuda.synchronize()
-    assert p.kv.lens.cpu().tolist() == [26, 8, 16]
+    assert p.kv.lens.cpu().tolist() == [26, 8, 16] and psd.psd_kv_len_upper_bound(p.kv.handle) == 26
     p.step(toks[:, 6:14], what="after truncate")
     # truncation never lengthens
     psd.psd_kv_truncate_to(p.kv.handle, 1000)
@@ -157,11 +157,55 @@ def test_bf16_batch_ragged_lengths_truncate():
     p.step(toks[:, :16], what="16 rows x 4 sequences")
     base = torch.tensor([512, 100, 333, 1], dtype=torch.int32, device="cuda")
     keep = torch.tensor([16, 0, 7, 3], dtype=torch.int32, device="cuda")
-    psd.psd_kv_truncate(p.kv.handle, base, keep, 0)
+    psd.psd_kv_truncate(p.kv.handle, base, keep, 0)          # bound argument left out: the host bound stays
+    assert psd.psd_kv_len_upper_bound(p.kv.handle) == 528
     p.okv.truncate([528, 100, 340, 4])
     p.step(toks[:, 16:33], what="17 rows after truncate")
     torch.cuda.synchronize()
     assert p.kv.lens.cpu().tolist() == [545, 117, 357, 21]
+    p.close()
+
+
+def test_batched_verify_loop_with_per_sequence_rollback_only():
+    """Fourteen consecutive verify steps of 16 sequences near the end of their caches: forward over gamma + 1
+    rows, acceptance against a synthetic drafter, then psd_kv_truncate alone (no psd_kv_truncate_to), the way a
+    decoding loop runs: it reads the accepted lengths back to steer itself and hands the largest resulting length
+    to the rollback.  Every step's logits and every acceptance are compared with the oracle.  A host bound that
+    only ever grew by gamma + 1 per step would pass the cache size after eleven steps and refuse the rest."""
+    from oracle import accept as oacc
+    shape, B, gamma, max_len, steps = SMALL_GQA, 16, 7, 384, 14
+    rng = np.random.default_rng(3)
+    lens0 = [int(v) for v in rng.integers(260, 300, B)]
+    p = Pair(shape, torch.bfloat16, B, max_len, seed=31, ctx=300, lens=lens0, std=0.05, pack=True)
+    acc = runtime.Acceptor("cuda")
+    lens = np.array(lens0)
+    assert psd.psd_kv_len_upper_bound(p.kv.handle) == lens.max()
+    assert lens.max() + steps * (gamma + 1) > max_len
+    total_kept = 0
+    for it in range(steps):
+        toks = synth.make_tokens(shape.vocab, (B, gamma + 1), 100 + it)
+        t = torch.from_numpy(toks).cuda()
+        base = torch.from_numpy(lens.astype(np.int32)).cuda()
+        logits = runtime.forward(p.model, p.kv, t)
+        ref = ofwd.forward(p.cfg, p.w, toks, p.okv)
+        check_logits(logits, ref, torch.bfloat16, f"step {it}")
+        q, _ = synth.make_draft_from_target(logits[:, :gamma], 1.0, 200 + it)
+        x = t[:, 1:].contiguous()                       # the rows after x* verify the tokens fed after it
+        u = synth.make_uniforms((B, gamma + 1), 300 + it, "cuda")
+        n, tok, fl = acc(logits, q, x, u, 1.0)
+        keep = n.cpu().numpy().astype(np.int64)         # the loop's one read-back per step
+        lens = lens + 1 + keep
+        psd.psd_kv_truncate(p.kv.handle, base, n, 1, int(lens.max()))
+        torch.cuda.synchronize()
+        on, otok, ofl = oacc.spec_accept(logits.cpu().double().numpy(), q.cpu().double().numpy(), x.cpu().numpy(),
+                                         u.cpu().double().numpy())
+        ok = (ofl & oacc.FLAG_NEAR_TIE) == 0
+        assert np.array_equal(keep[ok], on[ok]) and np.array_equal(tok.cpu().numpy()[ok], otok[ok])
+        total_kept += int(keep.sum())
+        p.okv.truncate([int(v) for v in lens])
+        assert p.kv.lens.cpu().tolist() == [int(v) for v in lens]
+        assert psd.psd_kv_len_upper_bound(p.kv.handle) == lens.max()
+    assert 0 < total_kept < steps * B * gamma
     p.close()
 
 
