@@ -449,11 +449,11 @@ size_t psd_spec_accept_workspace_bytes(int32_t rows, int32_t gamma, int32_t n_p_
     return accept_workspace_bytes(a);
 }
 
-psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int32_t *draft_tokens, int32_t gamma,
-                           const float *uniforms, float temperature, int32_t *out_accept_len, int32_t *out_token,
-                           int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype, int64_t p_seq_stride,
-                           int64_t q_seq_stride, int32_t *out_flags, void *workspace, size_t ws_bytes,
-                           void *hip_stream) {
+static psd_status spec_accept_impl(const void *p_logits, const void *q_logits, const int32_t *draft_tokens, int32_t gamma,
+                                   const float *uniforms, float temperature, int32_t *out_accept_len, int32_t *out_token,
+                                   int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype, int64_t p_seq_stride,
+                                   int64_t q_seq_stride, int32_t *out_flags, void *workspace, size_t ws_bytes,
+                                   void *(*late_workspace)(), void *hip_stream) {
     if (dtype != PSD_F32 && dtype != PSD_BF16) return PSD_ERR_DTYPE;
     if (rows < 0 || gamma < 0 || gamma > 64 || vocab <= 0 || vocab > (1 << 23)) return PSD_ERR_SHAPE;
     if (n_p_rows != gamma && n_p_rows != gamma + 1) return PSD_ERR_SHAPE;
@@ -475,7 +475,9 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
                      (uintptr_t)p_logits % 16 == 0 && (uintptr_t)q_logits % 16 == 0;
     AcceptArgs a{};
     accept_plan(rows, gamma, n_p_rows, vocab, dtype, vec, &a);
-    if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < accept_workspace_bytes(a)) return PSD_ERR_WORKSPACE;
+    if (ws_bytes < accept_workspace_bytes(a)) return PSD_ERR_WORKSPACE;
+    if (late_workspace) workspace = late_workspace();    // the built-in buffer: looked up once the sizes are known to fit
+    if (!workspace || (uintptr_t)workspace % 256) return late_workspace ? PSD_ERR_HIP : PSD_ERR_WORKSPACE;
     accept_bind_workspace(&a, workspace, out_flags);
     a.p = p_logits; a.q = q_logits; a.x = draft_tokens; a.u = uniforms;
     a.p_stride = p_seq_stride; a.q_stride = q_seq_stride; a.temperature = temperature;
@@ -484,6 +486,16 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
     if (greedy) launch_accept_greedy(a, vec, (hipStream_t)hip_stream);
     else launch_accept(a, vec, (hipStream_t)hip_stream);
     return check_launch();
+}
+
+psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int32_t *draft_tokens, int32_t gamma,
+                           const float *uniforms, float temperature, int32_t *out_accept_len, int32_t *out_token,
+                           int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype, int64_t p_seq_stride,
+                           int64_t q_seq_stride, int32_t *out_flags, void *workspace, size_t ws_bytes,
+                           void *hip_stream) {
+    return spec_accept_impl(p_logits, q_logits, draft_tokens, gamma, uniforms, temperature, out_accept_len, out_token,
+                            rows, n_p_rows, vocab, dtype, p_seq_stride, q_seq_stride, out_flags, workspace, ws_bytes,
+                            nullptr, hip_stream);
 }
 
 psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *keep_dev, int32_t keep_offset,
