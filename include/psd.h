@@ -190,6 +190,25 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
                            int64_t p_seq_stride, int64_t q_seq_stride, int32_t *out_flags,
                            void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* For callers that cannot allocate device memory or size a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): psd_spec_accept on a scratch buffer that is part of the
+ * library, a fixed PSD_STATIC_SCRATCH_BYTES array in device memory of every GPU the library runs on (held until
+ * the process ends).  Arguments, results and error behaviour are those of psd_spec_accept without workspace /
+ * ws_bytes; sizes whose psd_spec_accept_workspace_bytes() exceeds PSD_STATIC_SCRATCH_BYTES are refused with
+ * PSD_ERR_WORKSPACE before anything is launched (64 x 8 x 32000 needs 0.07 MB, 16 x 16 x 152064 0.13 MB).
+ * The call allocates and frees nothing and enqueues only kernels (no memset nodes); the buffer's address on the
+ * current GPU is looked up on the first call there (PSD_ERR_HIP if that fails).  All calls on one GPU share
+ * the buffer, which keeps the previous call's contents; whatever must start at zero is cleared by the call's
+ * first kernel.  Calls that overlap in time on one GPU (different streams or threads) race on it: give
+ * concurrent callers psd_spec_accept with workspaces of their own. */
+#define PSD_STATIC_SCRATCH_BYTES (1u << 20)
+psd_status psd_spec_accept_static(const void *p_logits, const void *q_logits, const int32_t *draft_tokens,
+                                  int32_t gamma, const float *uniforms, float temperature,
+                                  int32_t *out_accept_len, int32_t *out_token,
+                                  int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype,
+                                  int64_t p_seq_stride, int64_t q_seq_stride, int32_t *out_flags,
+                                  void *hip_stream);
+
 /* Rollback after verification (Sec. 3.3): on the stream, for every sequence b,
  *   lens[b] <- min(lens[b], base_lens_dev[b] + keep_dev[b] + keep_offset, new_len_upper_bound)   (never below 0).
  * base_lens_dev / keep_dev are device int32[batch] (e.g. the lengths before the verify

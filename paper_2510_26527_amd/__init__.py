@@ -14,6 +14,7 @@ PSD_ERR_NULL, PSD_ERR_SHAPE, PSD_ERR_DTYPE, PSD_ERR_CAPACITY = -1, -2, -3, -4
 PSD_ERR_TEMPERATURE, PSD_ERR_WORKSPACE, PSD_ERR_HIP, PSD_ERR_UNIMPLEMENTED = -5, -6, -7, -8
 PSD_F32, PSD_BF16 = 0, 1
 PSD_FLAG_NEAR_TIE, PSD_FLAG_ZERO_RESIDUAL = 1, 2
+PSD_STATIC_SCRATCH_BYTES = 1 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpsd.so")
@@ -46,6 +47,8 @@ _SIGNATURES = {
     "psd_spec_accept_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
     "psd_spec_accept": (_i32, [_vp, _vp, _vp, _i32, _vp, _f32, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i64,
                                _vp, _vp, _sz, _vp]),
+    "psd_spec_accept_static": (_i32, [_vp, _vp, _vp, _i32, _vp, _f32, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i64,
+                                      _vp, _vp]),
     "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "psd_kv_truncate_to": (_i32, [_vp, _i32, _vp]),
     "psd_profile_enable": (_i32, [_i32]),
@@ -181,6 +184,14 @@ def psd_spec_accept(p_logits, q_logits, draft_tokens, gamma, uniforms, temperatu
                                  dtype, p_seq_stride, q_seq_stride, _ptr(out_flags), _ptr(workspace),
                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
                                  _stream_ptr(stream)), "psd_spec_accept")
+
+
+def psd_spec_accept_static(p_logits, q_logits, draft_tokens, gamma, uniforms, temperature, out_accept_len, out_token,
+                           rows, n_p_rows, vocab, dtype, p_seq_stride, q_seq_stride, out_flags, stream=None):
+    _check(lib().psd_spec_accept_static(_ptr(p_logits), _ptr(q_logits), _ptr(draft_tokens), gamma, _ptr(uniforms),
+                                        float(temperature), _ptr(out_accept_len), _ptr(out_token), rows, n_p_rows,
+                                        vocab, dtype, p_seq_stride, q_seq_stride, _ptr(out_flags),
+                                        _stream_ptr(stream)), "psd_spec_accept_static")
 
 
 def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, new_len_upper_bound=-1, stream=None):

@@ -498,6 +498,42 @@ psd_status psd_spec_accept(const void *p_logits, const void *q_logits, const int
                             nullptr, hip_stream);
 }
 
+// ---- the entry point that allocates nothing: acceptance on a scratch buffer built into the library
+// One copy of the array per GPU; host code never uses its name as an address, only the device address that
+// hipGetSymbolAddress returns for the current device (looked up on the first call per device and kept).
+static __device__ __align__(256) unsigned char scratch[PSD_STATIC_SCRATCH_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_dev[kMaxDevices] = {};
+void *static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        g_last_hip_error = (int32_t)hipGetLastError();
+        return nullptr;
+    }
+    if (!g_scratch_dev[dev]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            g_last_hip_error = (int32_t)e;
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_dev[dev] = ptr;
+    }
+    return g_scratch_dev[dev];
+}
+}  // namespace
+
+psd_status psd_spec_accept_static(const void *p_logits, const void *q_logits, const int32_t *draft_tokens, int32_t gamma,
+                                  const float *uniforms, float temperature, int32_t *out_accept_len,
+                                  int32_t *out_token, int32_t rows, int32_t n_p_rows, int32_t vocab, int32_t dtype,
+                                  int64_t p_seq_stride, int64_t q_seq_stride, int32_t *out_flags, void *hip_stream) {
+    return spec_accept_impl(p_logits, q_logits, draft_tokens, gamma, uniforms, temperature, out_accept_len, out_token,
+                            rows, n_p_rows, vocab, dtype, p_seq_stride, q_seq_stride, out_flags, nullptr,
+                            PSD_STATIC_SCRATCH_BYTES, static_scratch, hip_stream);
+}
+
 psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *keep_dev, int32_t keep_offset,
                            int32_t new_len_upper_bound, void *hip_stream) {
     if (!kv || !base_lens_dev || !keep_dev) return PSD_ERR_NULL;
