@@ -28,9 +28,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kLoadsPerLane = 8;
 constexpr double kTieEps = 1e-5;
-constexpr int kMaxChunksE = 1024;     // draw-pass chunks per logits row (LDS table of the locating block)
-constexpr int kMaxChunkE = 8192;      // elements per draw-pass chunk
-constexpr int kWalk = 8;              // consecutive entries per thread and tile when a chunk is walked
+constexpr int kMaxChunksE = 256;      // draw-pass chunks per logits row: one per thread of the block that finishes a sequence
+constexpr int kGroup = 8;             // consecutive entries a thread of the draw kernel takes at a time
 
 template <typename T>
 __device__ __forceinline__ const T *logits_row(const AcceptArgs &a, int b, bool is_q, int j) {
@@ -38,12 +37,11 @@ __device__ __forceinline__ const T *logits_row(const AcceptArgs &a, int b, bool 
     return base + (int64_t)j * a.V;
 }
 
-// exp(x) for x <= 0 in fp64, a few ulp: x = k ln2 + r with |r| <= ln2/2, degree-13 Taylor polynomial
-// of exp(r) evaluated pairwise (short dependency chains), scaled by 2^k.  The draw only needs both
-// sides to agree to ~1e-15 relative, which leaves the flip probability at V * 1e-15.
-__device__ __forceinline__ double exp_nonpos(double x) {
-    if (!(x > -745.0)) return 0.0;
-    if (x > 709.0) return INFINITY;          // callers with x > 0 (the acceptance ratio) saturate
+// exp(x) in fp64, a few ulp: x = k ln2 + r with |r| <= ln2/2, degree-13 Taylor polynomial of exp(r)
+// evaluated pairwise (short dependency chains), scaled by 2^k.  The draw only needs both sides to agree
+// to ~1e-15 relative, which leaves the flip probability at V * 1e-15.  Straight-line code (the range
+// checks are selects), so that the exponentials of several entries interleave in one instruction stream.
+__device__ __forceinline__ double exp_core(double x) {        // -746 <= x <= 709
     const double kf = rint(x * 1.4426950408889634074);
     double r = fma(-kf, 6.93147180369123816490e-01, x);
     r = fma(-kf, 1.90821492927058770002e-10, r);
@@ -62,6 +60,13 @@ __device__ __forceinline__ double exp_nonpos(double x) {
     const double hi = fma(r4, pcd, q2);           // degree 8..13 (times r^8)
     return ldexp(fma(r8, hi, lo), (int)kf);
 }
+// x <= 0 up to rounding (a logit minus the row maximum); -inf and NaN give 0
+__device__ __forceinline__ double exp_nonpos(double x) {
+    const double v = exp_core(fmax(x, -746.0));
+    return x > -745.0 ? v : 0.0;
+}
+// any x (the logarithm of an acceptance ratio): saturates to +inf
+__device__ __forceinline__ double exp_any(double x) { return x > 709.0 ? INFINITY : exp_nonpos(x); }
 
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kThreads) void accept_stats_kernel(AcceptArgs a) {
@@ -193,7 +198,7 @@ __device__ __forceinline__ void decide(const AcceptArgs &a, int b, SeqStats *ss,
             if (lqx == -INFINITY) {
                 rho = INFINITY;             // q[x] = 0: the token could not have been drafted; accept
             } else {
-                rho = exp_nonpos((((double)lpx - (double)Mp) - ((double)lqx - (double)Mq)) / (double)a.temperature) * (Zq / Zp);
+                rho = exp_any((((double)lpx - (double)Mp) - ((double)lqx - (double)Mq)) / (double)a.temperature) * (Zq / Zp);
             }
             const int acc = u < fmin(1.0, rho) ? 1 : 0;
             const int tie = fabs(u - rho) < kTieEps ? 2 : 0;
@@ -228,11 +233,12 @@ __device__ __forceinline__ DrawRows draw_rows(const AcceptArgs &a, int n) {
 // The draw position of one sequence.  With a_i = exp(lp_i/T - mp), b_i = exp(lq_i/T - mq) (fp64) and
 // Zp = sum a, Zq = sum b, the residual weight of entry i is a_i/Zp - b_i/Zq where that is positive, i.e.
 // where d_i = (lp_i/T - mp) - (lq_i/T - mq) exceeds log(Zp/Zq).  The chunk pass runs before the fp64
-// Zp, Zq exist; it has the fp32 estimate of log(Zp/Zq) from the statistics pass (good to ~1e-6), so it
-// sums the entries with d_i above the estimate by more than kSignBand as surely positive, skips those
-// below it by more than that, and only counts the ones inside the band: their sign is settled with the
-// fp64 denominators by the block that finishes the sequence (a_i/Zp - b_i/Zq > 0, the definition).
-constexpr double kSignBand = 1e-5;
+// Zp, Zq exist; it decides the sign against the fp32 estimate `delta` of log(Zp/Zq) from the statistics
+// pass (t_i = d_i - delta > 0) and records, per chunk, the smallest positive and the largest non-positive
+// t_i.  The block that finishes the sequence knows eps = log(Zp/Zq) - delta; a chunk with no t_i between
+// 0 and eps was classified exactly as the fp64 residual would have been, any other chunk is summed again
+// with the sign taken from a_i/Zp - b_i/Zq itself.  Nothing rests on how good the estimate is.
+constexpr double kSignTol = 1e-11;      // rounding of t_i and of eps (|d_i| stays below ~1e3)
 
 template <typename T>
 struct DrawPos {
@@ -247,31 +253,57 @@ struct DrawPos {
         inv_t = 1.0 / (double)a.temperature;
         mp = (double)Mp * inv_t;
         mq = (double)Mq * inv_t;
-        delta = (double)logf((float)(Zp32 / Zq32));
+        const float est = logf((float)(Zp32 / Zq32));
+        delta = d.have_q && est == est ? (double)est : 0.0;       // any finite value will do
         have_q = d.have_q;
     }
-    // raw logits of entry i (q's is 0 when there is no q row): plain loads, so callers can issue many
-    __device__ __forceinline__ void load(int i, float *lp, float *lq) const {
-        *lp = load_elem(prow, i);
-        *lq = have_q ? load_elem(qrow, i) : 0.f;
-    }
-    // (a_i, b_i, class) from the raw logits; class 1: surely positive, 2: inside the band, 0: surely not
-    __device__ __forceinline__ void eval(float lp, float lq, double *ea, double *eb, int *cls) const {
-        const double xa = fma((double)lp, inv_t, -mp);
-        *ea = exp_nonpos(xa);
-        if (have_q) {
-            const double xb = fma((double)lq, inv_t, -mq);
-            *eb = exp_nonpos(xb);
-            const double t = (xa - xb) - delta;
-            *cls = t > kSignBand ? 1 : (t >= -kSignBand ? 2 : 0);
+    // raw logits of the kGroup consecutive entries i0 .. i0 + kGroup - 1 (those at or past i_end: entry i0 again,
+    // q's are 0 when there is no q row).  VEC: rows are 16-byte aligned, i0 and V are multiples of the elements
+    // per 16-byte load, so whole vectors are inside the row
+    template <bool VEC>
+    __device__ __forceinline__ void load_group(int i0, int i_end, float (&lp)[kGroup], float (&lq)[kGroup]) const {
+        if constexpr (VEC) {
+            constexpr int EPL = (int)(16 / sizeof(T)), NV = kGroup / EPL;
+            u32x4 rp[NV], rq[NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int i = i0 + v * EPL < i_end ? i0 + v * EPL : i0;
+                rp[v] = *reinterpret_cast<const u32x4 *>(prow + i);
+                rq[v] = have_q ? *reinterpret_cast<const u32x4 *>(qrow + i) : u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j) {
+                if constexpr (sizeof(T) == 2) {
+                    const uint32_t wp = rp[j / EPL][(j % EPL) >> 1], wq = rq[j / EPL][(j % EPL) >> 1];
+                    lp[j] = (j & 1) ? __uint_as_float(wp & 0xffff0000u) : __uint_as_float(wp << 16);
+                    lq[j] = (j & 1) ? __uint_as_float(wq & 0xffff0000u) : __uint_as_float(wq << 16);
+                } else {
+                    lp[j] = __uint_as_float(rp[j / EPL][j % EPL]);
+                    lq[j] = __uint_as_float(rq[j / EPL][j % EPL]);
+                }
+            }
         } else {
-            *eb = 0.0;
-            *cls = 1;
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j) {
+                const int i = i0 + j < i_end ? i0 + j : i0;
+                lp[j] = load_elem(prow, i);
+                lq[j] = have_q ? load_elem(qrow, i) : 0.f;
+            }
         }
+    }
+    // (a_i, b_i, t_i) from the raw logits; without a q row b_i = 0 and t_i = +inf (every entry counts)
+    __device__ __forceinline__ void eval(float lp, float lq, double *ea, double *eb, double *t) const {
+        const double xa = fma((double)lp, inv_t, -mp);
+        const double xb = fma((double)lq, inv_t, -mq);
+        *ea = exp_nonpos(xa);
+        const double e = exp_nonpos(xb);
+        *eb = have_q ? e : 0.0;
+        *t = have_q ? (xa - xb) - delta : INFINITY;
     }
 };
 
-// fixed-order block sum of NV doubles per thread: butterfly inside each wavefront, the four totals left to right
+// fixed-order block reductions of NV doubles per thread: butterfly inside each wavefront, then the four
+// wavefront results left to right
 template <int NV>
 __device__ __forceinline__ void block_sum(double (&v)[NV], double (*red)[kThreads / 64]) {
     const int tid = threadIdx.x;
@@ -285,21 +317,33 @@ __device__ __forceinline__ void block_sum(double (&v)[NV], double (*red)[kThread
 #pragma unroll
     for (int k = 0; k < NV; ++k) v[k] = ((red[k][0] + red[k][1]) + red[k][2]) + red[k][3];
 }
+__device__ __forceinline__ double wave_min_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ double wave_max_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, kWave));
+    return v;
+}
 
-constexpr int kPartStride = 6;      // doubles per (sequence, chunk): sum a, sum b, both over the surely positive
-                                    // entries, number of entries inside the sign band, unused
+// per (sequence, chunk): sum a, sum b, both over the entries with t_i > 0, the smallest positive t_i and the
+// largest non-positive t_i
+constexpr int kPartStride = 6;
 
 // Grid: rows x n_chunksE blocks.  Every block: first rejection of its sequence, fp64 sums of its chunk of
-// the draw position; the block that arrives last at the sequence's counter finishes the draw.
-template <typename T>
+// the draw position; the block that arrives last at the sequence's counter finishes the draw (thread k of
+// it owns chunk k: n_chunksE <= kThreads).
+template <typename T, bool VEC>
 __global__ __launch_bounds__(kThreads) void accept_draw_kernel(AcceptArgs a) {
     __shared__ SeqStats s_seq;
-    __shared__ double s_red[5][kThreads / 64];
+    __shared__ double s_red[6][kThreads / 64];
     __shared__ double s_scan[kThreads / 64];
-    __shared__ double s_w[kMaxChunksE];           // per-chunk weights of this sequence
-    __shared__ int s_und[kMaxChunksE];            // entries inside the sign band, per chunk
+
+    __shared__ int s_redo[kMaxChunksE];           // chunks whose sign classification has to be redone
     __shared__ int s_last, s_cstar, s_best, s_lastpos;
-    __shared__ double s_base, s_t;
+    __shared__ double s_base;
     const int nE = a.n_chunksE;
     const int b = blockIdx.x / nE, c = blockIdx.x % nE, tid = threadIdx.x;
     int n, flags;
@@ -315,33 +359,48 @@ __global__ __launch_bounds__(kThreads) void accept_draw_kernel(AcceptArgs a) {
     // ---- this block's chunk
     {
         const int e0 = c * a.chunkE, e1 = min(a.V, e0 + a.chunkE);
-        double acc[5] = {0.0, 0.0, 0.0, 0.0, 0.0};          // sum a, sum b, positive a, positive b, band count
-        for (int i0 = e0 + tid; i0 < e1; i0 += 4 * kThreads) {
-            float lp[4], lq[4];
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};               // sum a, sum b, positive a, positive b
+        double tpos = INFINITY, tneg = -INFINITY;
+        for (int i0 = e0 + tid * kGroup; i0 < e1; i0 += kGroup * kThreads) {
+            float lp[kGroup], lq[kGroup];
+            w.template load_group<VEC>(i0, e1, lp, lq);
+            double ea[kGroup], eb[kGroup], t[kGroup];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)            // all loads first (out-of-range lanes re-read entry e0)
-                w.load(i0 + u * kThreads < e1 ? i0 + u * kThreads : e0, &lp[u], &lq[u]);
-            double ea[4], eb[4];
-            int cls[4];
+            for (int j = 0; j < kGroup; ++j) w.eval(lp[j], lq[j], &ea[j], &eb[j], &t[j]);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) w.eval(lp[u], lq[u], &ea[u], &eb[u], &cls[u]);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (i0 + u * kThreads < e1) {
-                    acc[0] += ea[u];
-                    acc[1] += eb[u];
-                    if (cls[u] == 1) { acc[2] += ea[u]; acc[3] += eb[u]; }
-                    if (cls[u] == 2) acc[4] += 1.0;
+            for (int j = 0; j < kGroup; ++j) {
+                if (i0 + j < e1) {
+                    acc[0] += ea[j];
+                    acc[1] += eb[j];
+                    if (t[j] > 0.0) { acc[2] += ea[j]; acc[3] += eb[j]; tpos = fmin(tpos, t[j]); }
+                    if (t[j] <= 0.0) tneg = fmax(tneg, t[j]);
                 }
             }
         }
-        block_sum<5>(acc, s_red);
+        // one value per wavefront into LDS, thread 0 folds the four in wavefront order
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] = wave_sum(acc[k]);
+        tpos = wave_min_d(tpos);
+        tneg = wave_max_d(tneg);
+        if ((tid & 63) == 0) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s_red[k][tid >> 6] = acc[k];
+            s_red[4][tid >> 6] = tpos;
+            s_red[5][tid >> 6] = tneg;
+        }
+        __syncthreads();
         if (tid == 0) {
-            // hand the sums on as write-through stores, wait for them to be performed, then count this
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] = ((s_red[k][0] + s_red[k][1]) + s_red[k][2]) + s_red[k][3];
+            tpos = fmin(fmin(s_red[4][0], s_red[4][1]), fmin(s_red[4][2], s_red[4][3]));
+            tneg = fmax(fmax(s_red[5][0], s_red[5][1]), fmax(s_red[5][2], s_red[5][3]));
+            // hand the results on as write-through stores, wait for them to be performed, then count this
             // block in; whoever counts last reads all of them back with loads of the same scope
             double *dst = a.part + ((size_t)b * nE + c) * kPartStride;
 #pragma unroll
-            for (int k = 0; k < 5; ++k) __hip_atomic_store(dst + k, acc[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int k = 0; k < 4; ++k) __hip_atomic_store(dst + k, acc[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 4, tpos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 5, tneg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             const unsigned old = __hip_atomic_fetch_add(a.counter + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_last = old == (unsigned)nE - 1u;
@@ -350,124 +409,102 @@ __global__ __launch_bounds__(kThreads) void accept_draw_kernel(AcceptArgs a) {
         if (!s_last) return;
     }
 
-    // ---- the last block of the sequence: fp64 denominators, chunk weights, the crossing
-    const double *part = a.part + (size_t)b * nE * kPartStride;
-    auto part_at = [&](int k, int f) -> double {
-        return __hip_atomic_load(part + (size_t)k * kPartStride + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
+    // ---- the last block of the sequence: thread k takes chunk k's results (one round of loads)
+    double pk[kPartStride] = {0.0, 0.0, 0.0, 0.0, INFINITY, -INFINITY};
+    if (tid < nE) {
+        const double *src = a.part + ((size_t)b * nE + tid) * kPartStride;
+#pragma unroll
+        for (int k = 0; k < kPartStride; ++k) pk[k] = __hip_atomic_load(src + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     const double u = (double)a.u[(size_t)b * (a.gamma + 1) + a.gamma];
-    double zz[2] = {0.0, 0.0};
-    for (int k = tid; k < nE; k += kThreads) { zz[0] += part_at(k, 0); zz[1] += part_at(k, 1); }
+    double zz[2] = {pk[0], pk[1]};
     block_sum<2>(zz, s_red);
     const double inv_zp = 1.0 / zz[0], inv_zq = d.have_q ? 1.0 / zz[1] : 0.0;
-    for (int k = tid; k < nE; k += kThreads) {
-        s_w[k] = part_at(k, 2) * inv_zp - part_at(k, 3) * inv_zq;
-        s_und[k] = (int)part_at(k, 4);
-    }
-    __syncthreads();
-    // chunks with entries inside the sign band: their weight again, every entry's sign from the fp64 weights
+    double wk = pk[2] * inv_zp - pk[3] * inv_zq;                 // weight of chunk tid
     if (d.have_q) {
+        // chunks with a t_i between 0 and eps (or too close to tell): every entry's sign again, from the fp64 weights
+        const double eps = log(zz[0] / zz[1]) - w.delta;
+        const double lo = fmin(0.0, eps) - kSignTol, hi = fmax(0.0, eps) + kSignTol;
+        const bool redo = tid < nE && (!(eps == eps) || pk[5] >= lo || pk[4] <= hi);
+        if (tid < nE) s_redo[tid] = redo ? 1 : 0;
+        __syncthreads();
         for (int k = 0; k < nE; ++k) {
-            if (s_und[k] == 0) continue;
+            if (!s_redo[k]) continue;                            // the same for the whole block
             const int f0 = k * a.chunkE, f1 = min(a.V, f0 + a.chunkE);
             double pw[2] = {0.0, 0.0};
-            for (int i0 = f0 + tid; i0 < f1; i0 += kThreads) {
-                float lp, lq;
-                w.load(i0, &lp, &lq);
-                double ea, eb;
-                int cls;
-                w.eval(lp, lq, &ea, &eb, &cls);
-                if (ea * inv_zp - eb * inv_zq > 0.0) { pw[0] += ea; pw[1] += eb; }
+            for (int i0 = f0 + tid * kGroup; i0 < f1; i0 += kGroup * kThreads) {
+                float lp[kGroup], lq[kGroup];
+                w.template load_group<VEC>(i0, f1, lp, lq);
+#pragma unroll
+                for (int j = 0; j < kGroup; ++j) {
+                    double ea, eb, t;
+                    w.eval(lp[j], lq[j], &ea, &eb, &t);
+                    if (i0 + j < f1 && ea * inv_zp - eb * inv_zq > 0.0) { pw[0] += ea; pw[1] += eb; }
+                }
             }
             block_sum<2>(pw, s_red);
-            if (tid == 0) s_w[k] = pw[0] * inv_zp - pw[1] * inv_zq;
+            if (tid == k) wk = pw[0] * inv_zp - pw[1] * inv_zq;
         }
-        __syncthreads();
     }
-    double ms[1] = {0.0};
-    for (int k = tid; k < nE; k += kThreads) ms[0] += s_w[k];
+    double ms[1] = {wk};
     block_sum<1>(ms, s_red);
     double mass = ms[0];
     const bool fall_back_to_p = d.have_q && !(mass > 0.0);
     if (fall_back_to_p) {                         // residual mass 0: draw from p itself
         mass = 1.0;                               // sum of a_i / Zp
-        __syncthreads();
-        for (int k = tid; k < nE; k += kThreads) s_w[k] = part_at(k, 0) * inv_zp;
-        __syncthreads();
+        wk = pk[0] * inv_zp;
     }
-    // first chunk whose inclusive prefix exceeds t: each thread owns kMaxChunksE/256 consecutive chunks
+    // first chunk whose inclusive prefix exceeds t
+    const double t = u * mass;
     {
-        constexpr int CPT = kMaxChunksE / kThreads;
-        const double t = u * mass;
-        double cw[CPT], lsum = 0.0;
-#pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const int k = tid * CPT + j;
-            cw[j] = k < nE ? s_w[k] : 0.0;
-            lsum += cw[j];
-        }
-        double incl = lsum;
+        double incl = wk;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const double up = __shfl_up(incl, o, 64);
             if ((tid & 63) >= o) incl += up;
         }
         if (tid == 0) { s_best = 0x7fffffff; s_lastpos = -1; s_cstar = 0x7fffffff; }
+        __syncthreads();                          // s_scan: earlier readers are done
         if ((tid & 63) == 63) s_scan[tid >> 6] = incl;
         __syncthreads();
         double base = 0.0;
         for (int wvi = 0; wvi < (tid >> 6); ++wvi) base += s_scan[wvi];
-        base += incl - lsum;
-        int mine = 0x7fffffff, last_nonzero = -1;
-        double mybase = 0.0;
-#pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const int k = tid * CPT + j;
-            if (k < nE) {
-                if (cw[j] > 0.0) last_nonzero = k;
-                if (mine == 0x7fffffff && base + cw[j] > t) { mine = k; mybase = base; }
-                base += cw[j];
-            }
-        }
-        if (mine != 0x7fffffff) atomicMin(&s_cstar, mine);
-        if (last_nonzero >= 0) atomicMax(&s_lastpos, last_nonzero);
+        base += incl - wk;                        // weight in front of chunk tid
+        const bool mine = tid < nE && base + wk > t;
+        if (mine) atomicMin(&s_cstar, tid);
+        if (tid < nE && wk > 0.0) atomicMax(&s_lastpos, tid);
         __syncthreads();
         const int cstar = s_cstar;
-        if (cstar == 0x7fffffff) {                    // rounding left no crossing: last entry with weight
-            if (tid == 0) { s_cstar = max(s_lastpos, 0); s_t = INFINITY; s_base = 0.0; }
-        } else if (mine == cstar) {                   // exactly one thread owns the crossing chunk
-            s_t = t;
-            s_base = mybase;
+        if (cstar == 0x7fffffff) {                // rounding left no crossing: last chunk with weight
+            if (tid == 0) { s_cstar = max(s_lastpos, 0); s_base = -INFINITY; }
+        } else if (tid == cstar) {
+            s_base = base;
         }
         __syncthreads();
         if (tid == 0) s_lastpos = -1;
     }
     __syncthreads();
     const int cs = s_cstar;
-    const double t = s_t;
+    const bool no_crossing = s_base == -INFINITY;  // then the walk only looks for the last entry with weight
     const int f0 = cs * a.chunkE, f1 = min(a.V, f0 + a.chunkE);
-    // walk the chunk in tiles of 256 x kWalk entries, kWalk consecutive entries per thread, carrying the prefix
-    double before = s_base;                       // weight in front of the current tile
+    // walk the chunk in tiles of 256 x kGroup entries, kGroup consecutive entries per thread, carrying the prefix
+    double before = no_crossing ? 0.0 : s_base;    // weight in front of the current tile
     int found = 0x7fffffff, lastpos = -1;
-    for (int t0 = f0; t0 < f1; t0 += kThreads * kWalk) {
-        const int i0 = min(f1, t0 + tid * kWalk), i1 = min(f1, i0 + kWalk);
-        double wv[kWalk];
+    for (int t0 = f0; t0 < f1; t0 += kThreads * kGroup) {
+        const int g0 = t0 + tid * kGroup;
+        const bool active = g0 < f1;              // idle threads re-read the chunk's first group and count nothing
+        const int i0 = active ? g0 : f0, i1 = active ? min(f1, g0 + kGroup) : f0;
+        double wv[kGroup];
         double local = 0.0;
-        float lp[kWalk], lq[kWalk];
+        float lp[kGroup], lq[kGroup];
+        w.template load_group<VEC>(i0, active ? i1 : f1, lp, lq);
 #pragma unroll
-        for (int j = 0; j < kWalk; ++j)          // all loads first (idle slots re-read entry f0)
-            w.load(i0 + j < i1 ? i0 + j : f0, &lp[j], &lq[j]);
-#pragma unroll
-        for (int j = 0; j < kWalk; ++j) {
-            double ea, eb;
-            int cls;
-            w.eval(lp[j], lq[j], &ea, &eb, &cls);
-            wv[j] = 0.0;
-            if (i0 + j < i1) {
-                const double r = ea * inv_zp - eb * inv_zq;
-                if (fall_back_to_p) wv[j] = ea * inv_zp;
-                else if (r > 0.0) wv[j] = r;
-            }
+        for (int j = 0; j < kGroup; ++j) {
+            double ea, eb, tt;
+            w.eval(lp[j], lq[j], &ea, &eb, &tt);
+            const double r = ea * inv_zp - eb * inv_zq;
+            const double wj = fall_back_to_p ? ea * inv_zp : (r > 0.0 ? r : 0.0);
+            wv[j] = i0 + j < i1 ? wj : 0.0;
             local += wv[j];
         }
         // exclusive prefix of `local` over threads, in thread order
@@ -484,11 +521,11 @@ __global__ __launch_bounds__(kThreads) void accept_draw_kernel(AcceptArgs a) {
         for (int wvi = 0; wvi < (tid >> 6); ++wvi) run += s_scan[wvi];
         run += incl - local;
 #pragma unroll
-        for (int j = 0; j < kWalk; ++j) {
+        for (int j = 0; j < kGroup; ++j) {
             if (i0 + j < i1) {
                 if (wv[j] > 0.0) lastpos = i0 + j;
                 run += wv[j];
-                if (run > t && found == 0x7fffffff) found = i0 + j;
+                if (!no_crossing && run > t && found == 0x7fffffff) found = i0 + j;
             }
         }
         before += ((s_scan[0] + s_scan[1]) + s_scan[2]) + s_scan[3];
@@ -518,7 +555,7 @@ void accept_plan(int rows, int gamma, int n_p_rows, int V, int dtype, bool vec, 
     a->n_chunksA = (V + a->chunkA - 1) / a->chunkA;
     long want = ((long)V * (rows > 0 ? rows : 1) + 1023) / 1024;
     int ce = round_up((int)(want < 512 ? 512 : (want > 8192 ? 8192 : want)), 256);
-    if ((V + ce - 1) / ce > kMaxChunksE) ce = kMaxChunkE;
+    if ((V + ce - 1) / ce > kMaxChunksE) ce = round_up((V + kMaxChunksE - 1) / kMaxChunksE, 256);
     a->chunkE = ce;
     a->n_chunksE = (V + ce - 1) / ce;
 }
@@ -563,7 +600,8 @@ static void launch_accept_t(const AcceptArgs &a, bool vec_ok, hipStream_t stream
     }
     dim3 gridE((unsigned)a.rows * a.n_chunksE);
     ScopedProf sp(PSD_KIND_ACCEPT_DRAW, stream);
-    launch_kernel(accept_draw_kernel<T>, gridE, kThreads, 0, stream, a);
+    if (vec_ok) launch_kernel(accept_draw_kernel<T, true>, gridE, kThreads, 0, stream, a);
+    else launch_kernel(accept_draw_kernel<T, false>, gridE, kThreads, 0, stream, a);
 }
 
 void launch_accept(const AcceptArgs &a, bool vec_ok, hipStream_t stream) {
