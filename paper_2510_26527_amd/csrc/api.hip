@@ -264,8 +264,10 @@ namespace {
 struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
-    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, total;
-    bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
+    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, total;
+    bool folded;
+    bool fused_rope;              // the attention kernel reduces, rotates and appends q / k / v itself
+    bool qkv_one_slot;            // ... and the QKV projection then leaves one slot for it to read                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
 };
 
 ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound) {
@@ -283,7 +285,9 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
-    p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
+    p.fused_rope = attn_fuses_rope(d.dtype, n_new, d.n_q_heads, d.n_kv_heads, d.d_head);
+    p.qkv_one_slot = p.fused_rope && mdl->packed && !mdl->w4 && M <= kStreamMaxRows;
+    p.sk_qkv = p.qkv_one_slot ? 1 : splits(M, d.d_model, p.width_qkv, n_qkv, 3);
     p.sk_o = p.folded ? 1 : splits(M, hd, d.d_model, n_o, 1);
     p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
     p.sk_down = p.folded ? 1 : splits(M, d.d_ffn, d.d_model, n_o, 1);
@@ -306,6 +310,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.off_po = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * d.d_head * 4 : 0);
     p.off_pml = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * 2 * 4 : 0);
     p.off_sumsq = take(p.folded ? (size_t)(d.d_model / 16) * M * 4 : 0);
+    p.off_rope = take(p.fused_rope ? (size_t)M * (d.d_head / 2) * sizeof(float2) : 0);
     p.total = off;
     return p;
 }
@@ -374,6 +379,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
         g.M = rows; g.K = K; g.N = n0 + n1 + n2; g.partial = dst; g.splitk = sk; g.reduced = nullptr;
         g.pack_tiles = gemm_pack_tiles(g.n, g.nseg);
         g.w4 = m->w4;
+        g.one_slot = w2 && p.qkv_one_slot;
         launch_gemm(d.dtype, g, st);
     };
     // Folded mode: no RMSNorm kernel runs.  The projections that write the residual stream add into it and
@@ -398,16 +404,20 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
             launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, st);
         }
     };
+    RopeTable rt{};
+    if (p.fused_rope) rt = RopeTable{(float2 *)(ws + p.off_rope), kv->lens, n_new, d.d_head, d.rope_theta};
     launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, p.folded ? sumsq : nullptr, M, d.d_model,
-                      d.vocab, d.rms_eps, st);
+                      d.vocab, d.rms_eps, rt, st);
     rs.tiles = 1;
     for (int l = 0; l < d.n_layers; ++l) {
         gemm(act, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial,
              m->pack(l, P_QKV));
         char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
-        launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, rs, q, kl, vl, kv->lens, B, n_new, d.n_q_heads,
-                                  d.n_kv_heads, d.d_head, kv->max_len, d.rope_theta, st);
+        if (!p.fused_rope)
+            launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, rs, q, kl, vl, kv->lens, B, n_new, d.n_q_heads,
+                                      d.n_kv_heads, d.d_head, kv->max_len, d.rope_theta, st);
         AttnArgs a{};
+        if (p.fused_rope) { a.qkv_partial = partial; a.qkv_splits = p.sk_qkv; a.rs = rs; a.rope_cs = rt.cs; }
         a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn;
         a.B = B; a.R = n_new; a.h_q = d.n_q_heads; a.h_kv = d.n_kv_heads; a.d_h = d.d_head; a.max_len = kv->max_len;
         a.len_bound = len_bound; a.part_o = (float *)(ws + p.off_po); a.part_ml = (float *)(ws + p.off_pml);

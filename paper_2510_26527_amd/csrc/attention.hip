@@ -67,10 +67,49 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a, float scale
 constexpr int kKeysPerWaveIter = 64;
 constexpr int kKeysPerBlockIter = 256;
 
-template <int DH, int QT>
+// Sum over the S split-K slots (sstride floats apart) of NI pairs (src[it][0], src[it][second]) per thread.  The
+// loads of SPC slots of all pairs are issued together; the additions run in slot order, the order in which the
+// stand-alone rotation kernel adds them.
+template <int NI>
+__device__ __forceinline__ void sum_pairs(const float *const *src, size_t sstride, int S, int second, float *x1, float *x2) {
+    constexpr int SPC = 32 / NI;
+#pragma unroll
+    for (int it = 0; it < NI; ++it) x1[it] = x2[it] = 0.f;
+    for (int sp0 = 0; sp0 < S; sp0 += SPC) {
+        float t1[NI][SPC], t2[NI][SPC];
+#pragma unroll
+        for (int it = 0; it < NI; ++it)
+#pragma unroll
+            for (int u = 0; u < SPC; ++u) {
+                const size_t off = (size_t)min(sp0 + u, S - 1) * sstride;
+                t1[it][u] = src[it][off];
+                t2[it][u] = src[it][off + second];
+            }
+#pragma unroll
+        for (int it = 0; it < NI; ++it)
+#pragma unroll
+            for (int u = 0; u < SPC; ++u)
+                if (sp0 + u < S) { x1[it] += t1[it][u]; x2[it] += t2[it][u]; }
+    }
+}
+// the same for a number of pairs known at run time (the first ni of up to 8)
+__device__ __forceinline__ void sum_pairs_n(int ni, const float *const *src, size_t sstride, int S, int second, float *x1, float *x2) {
+    if (ni <= 1) sum_pairs<1>(src, sstride, S, second, x1, x2);
+    else if (ni <= 2) sum_pairs<2>(src, sstride, S, second, x1, x2);
+    else if (ni <= 4) sum_pairs<4>(src, sstride, S, second, x1, x2);
+    else sum_pairs<8>(src, sstride, S, second, x1, x2);
+}
+
+// FUSED: the block builds its operands itself from the QKV projection's split-K partial sums: row scale of the
+// folded RMSNorm, sum over the splits in split order, rotation with the (cos, sin) table of the step's positions.
+// Every block does that for its own query rows; the blocks of the last split also build the step's new keys and
+// values (<= 32 rows), keep them in LDS as one more 32-key tile, and the one with query chunk 0 appends them to
+// the cache.  Cache reads then stop at the old length, so no block reads what another one is writing.
+template <int DH, int QT, bool FUSED>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_log2, int range) {
     constexpr int KS = DH / 32;      // MFMA k-steps of S^T = K Q^T
     constexpr int DT = DH / 16;      // 16-row d tiles of O^T
+    constexpr int HALF = DH / 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int split = blockIdx.x, qchunk = blockIdx.y;
@@ -78,11 +117,189 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
     const int group = a.h_q / a.h_kv;
     const int NQ = group * a.R;
     const int S_b = a.lens[b];
-    const int n_keys = min(S_b + a.R, a.max_len);
+    const int n_keys = FUSED ? min(S_b, a.max_len) : min(S_b + a.R, a.max_len);      // keys read from the cache
     const int kb0 = split * range, kb1 = min(n_keys, kb0 + range);
     const size_t max_len = a.max_len;
     const uint16_t *Kc = (const uint16_t *)a.k + ((size_t)b * a.h_kv + hk) * max_len * DH;
     const uint16_t *Vt = (const uint16_t *)a.v + ((size_t)b * a.h_kv + hk) * DH * max_len;
+    const bool new_tile = FUSED && split == (int)gridDim.x - 1;       // this block also attends to the new rows
+
+    // LDS: the operand build (rotated queries, the new keys, the new values transposed) and, after the last tile,
+    // the merge of the four wavefronts use the same bytes
+    constexpr int NSLAB = QT == 1 ? 4 : 2;          // merge slabs: a wavefront each, or two wavefronts sharing one
+    constexpr size_t kBuildBytes = FUSED ? (size_t)QT * 16 * (DH + 4) * 4 + 32 * (DH + 8) * 2 + (size_t)DH * 40 * 2 : 0;
+    constexpr size_t kMergeBytes = (size_t)NSLAB * QT * 16 * (DH + 1) * 4 + 2 * NSLAB * QT * 16 * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kBuildBytes > kMergeBytes ? kBuildBytes : kMergeBytes];
+    float (*s_q)[DH + 4] = reinterpret_cast<float (*)[DH + 4]>(lds_raw);
+    uint16_t (*s_k)[DH + 8] = reinterpret_cast<uint16_t (*)[DH + 8]>(lds_raw + (size_t)QT * 16 * (DH + 4) * 4);
+    uint16_t (*s_vt)[40] = reinterpret_cast<uint16_t (*)[40]>(lds_raw + (size_t)QT * 16 * (DH + 4) * 4 + 32 * (DH + 8) * 2);
+    __shared__ float s_scale[32];
+    // the first 64-key tile of this wavefront is requested before anything else: its trip to HBM overlaps the
+    // operand build below
+    bf16x8 ka[2][2][KS];
+    bf16x8 va[2][DT];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            // a half that starts at or beyond kb1 is fully masked; clamp its address into the tile's first half
+            const int kb = (kt + sub * 32 < kb1) ? kt + sub * 32 : kt;
+            // K rows of the two 16-key score tiles: row i of tile t is key kb + 8*(i/4) + 4*t + i%4
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int key = kb + 8 * (i >> 2) + 4 * t + (i & 3);     // < max_len: kb + 32 <= max_len
+                const uint16_t *kp = Kc + (size_t)key * DH + g * (DH / 4);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) ka[sub][t][s] = *reinterpret_cast<const bf16x8 *>(kp + 8 * s);
+            }
+            // V^T rows d = dt*16 + i, keys kb + 8g .. kb + 8g + 7
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                va[sub][dt] = *reinterpret_cast<const bf16x8 *>(Vt + (size_t)(dt * 16 + i) * max_len + kb + 8 * g);
+        }
+    };
+    constexpr bool HOIST = QT == 1;            // two query tiles leave no registers to hold a tile across the build
+    const int kt_first = kb0 + wave * kKeysPerWaveIter;
+    if (HOIST && kt_first < kb1) load_tile(kt_first);
+
+    if constexpr (FUSED) {
+        const int tid = threadIdx.x;
+        const int W = (a.h_q + 2 * a.h_kv) * DH;
+        const size_t sstride = (size_t)a.B * a.R * W;
+        const int S = a.qkv_splits;
+        // Everything the build needs is requested before the first value is used: the sums of squares behind the
+        // row scales, the (cos, sin) pairs, then the partial sums themselves.
+        // RMSNorm scale of the step's rows of this sequence: one wavefront per row, the reduction order of the
+        // stand-alone rotation kernel (lane-strided sum, then the butterfly)
+        const bool few = a.R <= 8 && a.rs.tiles <= 256;            // then a lane holds all its terms at once
+        float raw[2][4];
+        if (a.rs.sumsq && few) {
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const int r = wave + 4 * rr, t = lane + 64 * tt;
+                    raw[rr][tt] = r < a.R && t < a.rs.tiles ? a.rs.sumsq[(size_t)t * (a.B * a.R) + b * a.R + r] : 0.f;
+                }
+        }
+        auto row_scales = [&]() {
+            for (int r = wave; r < a.R; r += 4) {
+                float sc = 1.0f;
+                if (a.rs.sumsq) {
+                    float ssq = 0.f;
+                    if (few) {
+#pragma unroll
+                        for (int tt = 0; tt < 4; ++tt) ssq += r < 4 ? raw[0][tt] : raw[1][tt];
+                    } else {
+                        for (int t = lane; t < a.rs.tiles; t += 64) ssq += a.rs.sumsq[(size_t)t * (a.B * a.R) + b * a.R + r];
+                    }
+                    sc = 1.0f / sqrtf(wave_sum(ssq) * a.rs.inv_d + a.rs.eps);
+                }
+                if (lane == 0) s_scale[r] = sc;
+            }
+        };
+        if (new_tile)                               // rows / columns past R of the new tile must read as zeros
+            for (int e = tid; e < DH * 40; e += 256) {
+                if (e < 32 * (DH + 8)) (&s_k[0][0])[e] = 0;
+                (&s_vt[0][0])[e] = 0;
+            }
+        // queries of this block: (query, rotation pair) items, consecutive threads on consecutive pairs
+        constexpr int NIQ = QT * 16 * HALF / 256;
+        {
+            const int nq = min(QT * 16, NQ - qchunk * QT * 16);       // queries of this block that exist
+            const int ni = (nq * HALF + 255) / 256;
+            const float *src[8];
+            float x1[8], x2[8];
+            float2 cs[NIQ];
+            int rloc[NIQ];
+#pragma unroll
+            for (int it = 0; it < NIQ; ++it) {
+                const int item = tid + it * 256, ql_ = item / HALF, pi = item % HALF;
+                const int qi = qchunk * QT * 16 + ql_;
+                const bool valid = qi < NQ;
+                const int hl = valid ? qi / a.R : 0, r = valid ? qi % a.R : 0;
+                rloc[it] = valid ? r : -1;
+                src[it] = a.qkv_partial + (size_t)(b * a.R + r) * W + (size_t)(hk * group + hl) * DH + pi;
+                cs[it] = a.rope_cs[(size_t)(b * a.R + r) * HALF + pi];
+            }
+            sum_pairs_n(ni, src, sstride, S, HALF, x1, x2);
+            row_scales();
+            __syncthreads();                        // s_scale
+#pragma unroll
+            for (int it = 0; it < NIQ; ++it) {
+                const int item = tid + it * 256, ql_ = item / HALF, pi = item % HALF;
+                float y1 = 0.f, y2 = 0.f;
+                if (rloc[it] >= 0) {
+                    const float sc = s_scale[rloc[it]];
+                    const float v1 = x1[it] * sc, v2 = x2[it] * sc;
+                    y1 = v1 * cs[it].x - v2 * cs[it].y;
+                    y2 = v2 * cs[it].x + v1 * cs[it].y;
+                }
+                s_q[ql_][pi] = y1;
+                s_q[ql_][pi + HALF] = y2;
+            }
+        }
+        if (new_tile) {
+            uint16_t *Kw = (uint16_t *)a.k + ((size_t)b * a.h_kv + hk) * max_len * DH;
+            uint16_t *Vw = (uint16_t *)a.v + ((size_t)b * a.h_kv + hk) * DH * max_len;
+            const bool writer = qchunk == 0;
+            // keys: (row, rotation pair) items; values: (row, element pair) items; up to 32 rows x HALF of each.
+            // With at most four items of each kind per thread both kinds are summed in one go.
+            const int nik = (a.R * HALF + 255) / 256;               // 1 .. 8
+            const bool both = nik <= 4;
+            for (int pass = 0; pass < (both ? 1 : 2); ++pass) {
+                const float *src[8];
+                float x1[8], x2[8];
+                float2 cs[8];
+                // slot `it` of this pass: key items first, then (in a combined pass) the value items
+                auto slot = [&](int it, bool *is_v, int *item) {
+                    *is_v = both ? it >= nik : pass == 1;
+                    *item = tid + (both && it >= nik ? it - nik : it) * 256;
+                };
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    bool is_v;
+                    int item;
+                    slot(it, &is_v, &item);
+                    const int r = min(item / HALF, a.R - 1), pi = item % HALF;
+                    const int col0 = (is_v ? a.h_q + a.h_kv + hk : a.h_q + hk) * DH;
+                    src[it] = a.qkv_partial + (size_t)(b * a.R + r) * W + col0 + pi;
+                    cs[it] = a.rope_cs[(size_t)(b * a.R + r) * HALF + pi];
+                }
+                sum_pairs_n(both ? 2 * nik : nik, src, sstride, S, HALF, x1, x2);
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    bool is_v;
+                    int item;
+                    slot(it, &is_v, &item);
+                    if (it >= (both ? 2 * nik : nik)) continue;
+                    const int r = item / HALF, pi = item % HALF;
+                    if (r >= a.R) continue;
+                    const int pos = S_b + r;
+                    const float sc = s_scale[r];
+                    const float v1 = x1[it] * sc, v2 = x2[it] * sc;
+                    if (!is_v) {
+                        const uint16_t k1 = (uint16_t)f32_to_bf16_bits(v1 * cs[it].x - v2 * cs[it].y);
+                        const uint16_t k2 = (uint16_t)f32_to_bf16_bits(v2 * cs[it].x + v1 * cs[it].y);
+                        s_k[r][pi] = k1;
+                        s_k[r][pi + HALF] = k2;
+                        if (writer && pos < a.max_len) {
+                            Kw[(size_t)pos * DH + pi] = k1;
+                            Kw[(size_t)pos * DH + pi + HALF] = k2;
+                        }
+                    } else {
+                        const uint16_t w1 = (uint16_t)f32_to_bf16_bits(v1), w2 = (uint16_t)f32_to_bf16_bits(v2);
+                        s_vt[pi][r] = w1;
+                        s_vt[pi + HALF][r] = w2;
+                        if (writer && pos < a.max_len) {
+                            Vw[(size_t)pi * max_len + pos] = w1;
+                            Vw[(size_t)(pi + HALF) * max_len + pos] = w2;
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
 
     // Q operand (B of S^T = K Q^T): column i of tile qt is query q0 + qt*16 + i; lane group g
     // holds d_head elements [g*DH/4, (g+1)*DH/4), k-step s the 8 starting at 8*s inside them.
@@ -94,7 +311,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         const bool valid = qi < NQ;
         const int hl = valid ? qi / a.R : 0, r = valid ? qi % a.R : 0;
         limit[qt] = valid ? S_b + r : -1;
-        const float *qp = a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
+        const float *qp = FUSED ? &s_q[qt * 16 + i][g * (DH / 4)]
+                                : a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             f32x8 v = load_f32x8(qp + 8 * s);
@@ -113,132 +331,136 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         for (int dt = 0; dt < DT; ++dt) o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int kt = kb0 + wave * kKeysPerWaveIter; kt < kb1; kt += kKeysPerBlockIter) {
-        // issue every K and V^T load of this 64-key tile before the first MFMA (two 32-key halves)
-        bf16x8 ka[2][2][KS];
-        bf16x8 va[2][DT];
+    // one 32-key sub-tile: keys kb .. kb + 31, of which those below n_end exist; ka / va are its operands
+    auto consume = [&](int kb, int n_end, bf16x8 (&ka)[2][KS], bf16x8 (&va)[DT]) {
+        if (kb + 32 > n_end) {          // stale cache rows may hold anything, even NaN: zero them
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            // a half that starts at or beyond kb1 is fully masked; clamp its address into the tile's first half
-            const int kb = (kt + sub * 32 < kb1) ? kt + sub * 32 : kt;
-            // K rows of the two 16-key score tiles: row i of tile t is key kb + 8*(i/4) + 4*t + i%4
+            for (int dt = 0; dt < DT; ++dt) {
+                u32x4 raw = __builtin_bit_cast(u32x4, va[dt]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int key = kb + 8 * (i >> 2) + 4 * t + (i & 3);     // < max_len: kb + 32 <= max_len
-                const uint16_t *kp = Kc + (size_t)key * DH + g * (DH / 4);
-#pragma unroll
-                for (int s = 0; s < KS; ++s) ka[sub][t][s] = *reinterpret_cast<const bf16x8 *>(kp + 8 * s);
+                for (int e = 0; e < 4; ++e) {
+                    const int key = kb + 8 * g + 2 * e;
+                    if (key >= n_end) raw[e] = 0u;
+                    else if (key + 1 >= n_end) raw[e] &= 0xffffu;
+                }
+                va[dt] = __builtin_bit_cast(bf16x8, raw);
             }
-            // V^T rows d = dt*16 + i, keys kb + 8g .. kb + 8g + 7
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                va[sub][dt] = *reinterpret_cast<const bf16x8 *>(Vt + (size_t)(dt * 16 + i) * max_len + kb + 8 * g);
         }
+        // scores of every query tile first, MFMAs interleaved over independent accumulators
+        f32x4 c[QT][2];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) c[qt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[qt][t], 0, 0, 0);
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[qt][t], 0, 0, 0);
+        }
+        bf16x8 ph[QT], pl[QT];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int key = kb + 8 * g + 4 * t + v;
+                    const float sc = key <= limit[qt] && key < n_end ? c[qt][t][v] * scale_log2 : -INFINITY;
+                    c[qt][t][v] = sc;
+                    tmax = fmaxf(tmax, sc);
+                }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float mnew = fmaxf(mrun[qt], tmax);
+            float p[8];
+            if (mnew > -INFINITY) {
+                const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+                float ps = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
+                    ps += p[e];
+                }
+                lrun[qt] = lrun[qt] * alpha + ps;
+                if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                }
+                mrun[qt] = mnew;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] = 0.f;
+            }
+            split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph[qt], &pl[qt]);
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph[qt], o[qt][dt], 0, 0, 0);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl[qt], o[qt][dt], 0, 0, 0);
+    };
+
+    for (int kt = kt_first; kt < kb1; kt += kKeysPerBlockIter) {
+        if (!HOIST || kt != kt_first) load_tile(kt); // every K and V^T load of the tile before its first MFMA
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = kt + sub * 32;
             if (kb >= kb1) break;
-            if (kb + 32 > n_keys) {          // stale cache rows may hold anything, even NaN: zero them
+            consume(kb, n_keys, ka[sub], va[sub]);
+        }
+    }
+    if constexpr (FUSED) {
+        if (new_tile && wave == 3) {
+            // the step's own rows as one more 32-key tile at positions S_b .. S_b + R - 1, operands from LDS
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    u32x4 raw = __builtin_bit_cast(u32x4, va[sub][dt]);
+            for (int t = 0; t < 2; ++t) {
+                const int key = 8 * (i >> 2) + 4 * t + (i & 3);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int key = kb + 8 * g + 2 * e;
-                        if (key >= n_keys) raw[e] = 0u;
-                        else if (key + 1 >= n_keys) raw[e] &= 0xffffu;
-                    }
-                    va[sub][dt] = __builtin_bit_cast(bf16x8, raw);
-                }
-            }
-            // scores of every query tile first, MFMAs interleaved over independent accumulators
-            f32x4 c[QT][2];
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) c[qt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], qh[qt][s], c[qt][t], 0, 0, 0);
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sub][t][s], ql[qt][s], c[qt][t], 0, 0, 0);
-            }
-            bf16x8 ph[QT], pl[QT];
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
-                float tmax = -INFINITY;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int key = kb + 8 * g + 4 * t + v;
-                        const float sc = key <= limit[qt] ? c[qt][t][v] * scale_log2 : -INFINITY;
-                        c[qt][t][v] = sc;
-                        tmax = fmaxf(tmax, sc);
-                    }
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-                const float mnew = fmaxf(mrun[qt], tmax);
-                float p[8];
-                if (mnew > -INFINITY) {
-                    const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
-                    float ps = 0.f;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
-                        ps += p[e];
-                    }
-                    lrun[qt] = lrun[qt] * alpha + ps;
-                    if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                    }
-                    mrun[qt] = mnew;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) p[e] = 0.f;
-                }
-                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph[qt], &pl[qt]);
+                for (int s = 0; s < KS; ++s) ka[0][t][s] = *reinterpret_cast<const bf16x8 *>(&s_k[key][g * (DH / 4) + 8 * s]);
             }
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], ph[qt], o[qt][dt], 0, 0, 0);
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[sub][dt], pl[qt], o[qt][dt], 0, 0, 0);
+            for (int dt = 0; dt < DT; ++dt) va[0][dt] = *reinterpret_cast<const bf16x8 *>(&s_vt[dt * 16 + i][8 * g]);
+            consume(S_b, S_b + a.R, ka[0], va[0]);
         }
     }
 
-    // ---- merge the four wavefronts in wavefront order through LDS
-    __shared__ float sm_o[QT * 16][DH + 1];
-    __shared__ float sm_m[QT * 16], sm_l[QT * 16];
+    // ---- merge the four wavefronts through LDS: wavefront w goes to slab w % NSLAB, in round w / NSLAB (a later
+    // round folds into what the slab holds); the slabs are combined in slab order when the result is written
+    float (*sm_o)[QT * 16][DH + 1] = reinterpret_cast<float (*)[QT * 16][DH + 1]>(lds_raw);
+    float (*sm_m)[QT * 16] = reinterpret_cast<float (*)[QT * 16]>(lds_raw + (size_t)NSLAB * QT * 16 * (DH + 1) * 4);
+    float (*sm_l)[QT * 16] = sm_m + NSLAB;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         lrun[qt] += __shfl_xor(lrun[qt], 16, 64);
         lrun[qt] += __shfl_xor(lrun[qt], 32, 64);
     }
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    __syncthreads();                                // every wavefront is done with the build's LDS
+    const int slab = wave % NSLAB;
+    for (int round = 0; round < 4 / NSLAB; ++round) {
+        if (wave / NSLAB == round) {
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
                 const int qc = qt * 16 + i;
                 float fo = 0.f, fn = 1.f, M = mrun[qt], L = lrun[qt];
-                if (w > 0) {
-                    const float mo = sm_m[qc], lo = sm_l[qc];
+                if (round > 0) {
+                    const float mo = sm_m[slab][qc], lo = sm_l[slab][qc];
                     M = fmaxf(mo, mrun[qt]);
                     fo = mo > -INFINITY ? __builtin_amdgcn_exp2f(mo - M) : 0.f;
                     fn = mrun[qt] > -INFINITY ? __builtin_amdgcn_exp2f(mrun[qt] - M) : 0.f;
@@ -250,10 +472,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                     for (int v = 0; v < 4; ++v) {
                         const int d = dt * 16 + 4 * g + v;
                         const float mine = o[qt][dt][v] * fn;
-                        sm_o[qc][d] = w > 0 ? sm_o[qc][d] * fo + mine : mine;
+                        sm_o[slab][qc][d] = round > 0 ? sm_o[slab][qc][d] * fo + mine : mine;
                     }
                 __builtin_amdgcn_wave_barrier();
-                if (g == 0) { sm_m[qc] = M; sm_l[qc] = L; }
+                if (g == 0) { sm_m[slab][qc] = M; sm_l[slab][qc] = L; }
             }
         }
         __syncthreads();
@@ -266,13 +488,24 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         if (qi >= NQ) continue;
         const int hl = qi / a.R, r = qi % a.R;
         const size_t row = ((size_t)(b * a.R + r)) * a.h_q + hk * group + hl;       // [B][R][h_q]
+        float M = sm_m[0][qc];
+#pragma unroll
+        for (int sl = 1; sl < NSLAB; ++sl) M = fmaxf(M, sm_m[sl][qc]);
+        float acc = 0.f, L = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < NSLAB; ++sl) {
+            const float ms = sm_m[sl][qc];
+            const float f = ms > -INFINITY ? __builtin_amdgcn_exp2f(ms - M) : 0.f;
+            acc += sm_o[sl][qc][d] * f;
+            L += sm_l[sl][qc] * f;
+        }
         if (a.splits == 1) {
-            a.out[row * DH + d] = sm_o[qc][d] / sm_l[qc];
+            a.out[row * DH + d] = acc / L;
         } else {
-            a.part_o[(row * a.splits + split) * DH + d] = sm_o[qc][d];
+            a.part_o[(row * a.splits + split) * DH + d] = acc;
             if (d == 0) {
-                a.part_ml[(row * a.splits + split) * 2] = sm_m[qc];
-                a.part_ml[(row * a.splits + split) * 2 + 1] = sm_l[qc];
+                a.part_ml[(row * a.splits + split) * 2] = M;
+                a.part_ml[(row * a.splits + split) * 2 + 1] = L;
             }
         }
     }
@@ -508,7 +741,7 @@ __global__ void attn_combine_kernel(AttnArgs a) {
 }
 
 // query tiles of 16 per block: bounded by registers (hi+lo query operands and fp32 outputs)
-inline int q_tiles(int NQ, int d_h) { return NQ <= 16 ? 1 : ((NQ <= 32 || d_h > 64) ? 2 : 4); }
+inline int q_tiles(int NQ) { return NQ <= 16 ? 1 : 2; }
 
 }  // namespace
 
@@ -516,10 +749,14 @@ inline int q_tiles(int NQ, int d_h) { return NQ <= 16 ? 1 : ((NQ <= 32 || d_h > 
 inline bool use_wide(int NQ) { return NQ > 32; }
 inline int wide_rows(int NQ) { return NQ <= 64 ? 64 : 128; }
 
+bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h) {
+    return dtype == PSD_BF16 && (d_h == 64 || d_h == 128) && R <= 32 && !use_wide((h_q / h_kv) * R);
+}
+
 int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound) {
     if (dtype != PSD_BF16) return 1;
     const int NQ = (h_q / h_kv) * R;
-    const int QT = q_tiles(NQ, d_h);
+    const int QT = q_tiles(NQ);
     const int chunks = use_wide(NQ) ? (NQ + wide_rows(NQ) - 1) / wide_rows(NQ) : (NQ + QT * 16 - 1) / (QT * 16);
     const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
     // the LDS-staged kernel loads its 64-128 query rows and writes as many partial rows per block: about one
@@ -534,7 +771,7 @@ int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int le
 template <int DH>
 static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     const int NQ = (a.h_q / a.h_kv) * a.R;
-    const int QT = q_tiles(NQ, DH);
+    const int QT = q_tiles(NQ);
     const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
     int range = (a.len_bound + a.splits - 1) / a.splits;
     range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
@@ -556,9 +793,13 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     dim3 grid(a.splits, chunks, a.B * a.h_kv);
     {
     ScopedProf sp(PSD_KIND_ATTN, stream);
-    if (QT == 1) launch_kernel(attn_mfma_kernel<DH, 1>, grid, 256, 0, stream, a, scale_log2, range);
-    else if (QT == 2) launch_kernel(attn_mfma_kernel<DH, 2>, grid, 256, 0, stream, a, scale_log2, range);
-    else if constexpr (DH <= 64) launch_kernel(attn_mfma_kernel<DH, 4>, grid, 256, 0, stream, a, scale_log2, range);
+    if (a.qkv_partial) {
+        if (QT == 1) launch_kernel(attn_mfma_kernel<DH, 1, true>, grid, 256, 0, stream, a, scale_log2, range);
+        else launch_kernel(attn_mfma_kernel<DH, 2, true>, grid, 256, 0, stream, a, scale_log2, range);
+    } else {
+        if (QT == 1) launch_kernel(attn_mfma_kernel<DH, 1, false>, grid, 256, 0, stream, a, scale_log2, range);
+        else launch_kernel(attn_mfma_kernel<DH, 2, false>, grid, 256, 0, stream, a, scale_log2, range);
+    }
     }
     if (a.splits > 1) {
         ScopedProf sp(PSD_KIND_ATTN_COMBINE, stream);

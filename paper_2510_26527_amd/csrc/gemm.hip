@@ -903,7 +903,7 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         else launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
         return;
     }
-    if (g.M <= kStreamMaxRows && g.wpack && gemm_use_stream(g.pack_tiles)) {
+    if (g.M <= kStreamMaxRows && g.wpack && !g.one_slot && gemm_use_stream(g.pack_tiles)) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
         const int grid = gemm_stream_grid(g.pack_tiles, g.K);
         launch_kernel(gemm_bf16_stream_kernel<1>, grid, 256, 0, stream, g);

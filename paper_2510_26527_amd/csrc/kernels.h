@@ -58,6 +58,8 @@ struct GemmArgs {
     int pack_tiles;               //   its number of 64-row tiles
     float *partial;               // [splitk][M][N] fp32: split s holds its share of the K sum
     int splitk;
+    bool one_slot;                // packed weights, M <= kStreamMaxRows: one block per 64-row tile over the whole K range
+                                  //   (splitk = 1) instead of the stream-K kernel, for consumers that read the slots directly
     float *reduced;               // if non-NULL: [M][N] <- sum over splits (logits), times the row scale if given
     // -- bf16, M <= kStreamMaxRows, packed weights only: RMSNorm folded into the projections around it -----------
     // rmsnorm(x) W^T = r_m * ((x * gain) W^T) with r_m = rsqrt(mean_k x[m][k]^2 + eps).  The one-slot column
@@ -105,14 +107,31 @@ struct AttnArgs {
     float *part_o;                // split scratch [B][h_q][R][splits][d_h]
     float *part_ml;               // [B][h_q][R][splits][2]
     int splits;
+    // Fused operand build (bf16, at most 32 query rows per KV head and at most 32 new rows): q is not read;
+    // the kernel takes q, k, v of the new rows from the QKV projection's split-K partial sums
+    // qkv_partial [qkv_splits][B*R][(h_q + 2 h_kv) d_h], applies the row scale rs and the rotation by
+    // rope_cs [B*R][d_h/2] = (cos, sin) of position lens[b] + r at frequency i, and appends k, v to the cache.
+    const float *qkv_partial;     // NULL: q holds the rotated queries and the cache already holds the new rows
+    int qkv_splits;
+    RowScale rs;
+    const float2 *rope_cs;
 };
+// whether launch_attention builds its operands itself for this shape (then no rotation / append kernel runs before it)
+bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h);
 int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound);
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- row-wise kernels (rowwise.hip)
+// optional by-product of the embedding kernel: cs[m][i] = (cos, sin) of (lens[m / R] + m % R) * theta^(-2i/d_h)
+struct RopeTable {
+    float2 *cs;                   // [M][d_h/2], NULL: not wanted
+    const int32_t *lens;
+    int R, d_h;
+    float theta;
+};
 // x = embed[token]; then xn = rmsnorm(x) * gain, or (sumsq_out non-NULL) xn = x * gain and sumsq_out[m] = sum_k x[m][k]^2
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       float *sumsq_out, int M, int d, int vocab, float eps, hipStream_t stream);
+                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, hipStream_t stream);
 // qkv = sum over splits of partial [S][M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended
 // to the cache (model dtype)
 void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,

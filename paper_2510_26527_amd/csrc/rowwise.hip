@@ -37,9 +37,20 @@ template <typename TW, bool EMBED>
 __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *embed, const int32_t *tokens, int vocab,
                                                                     const float *partial, int S, size_t split_stride,
                                                                     float *x, const TW *gain, float *xn, float *sumsq_out,
-                                                                    int d, float eps) {
+                                                                    int d, float eps, RopeTable rt) {
     __shared__ float red[4];
     const int m = blockIdx.x, tid = threadIdx.x, n4 = d >> 2;
+    if constexpr (EMBED) {
+        // (cos, sin) of this row's position at every rotation frequency, once per forward pass for all layers;
+        // the angle position * theta^(-2i/d_h) is evaluated in fp64
+        if (rt.cs && tid < rt.d_h / 2) {
+            const int pos = rt.lens[m / rt.R] + m % rt.R;
+            const double inv_freq = exp2(-2.0 * (double)tid / (double)rt.d_h * log2((double)rt.theta));
+            double sn, cs;
+            sincos((double)pos * inv_freq, &sn, &cs);
+            rt.cs[(size_t)m * (rt.d_h / 2) + tid] = make_float2((float)cs, (float)sn);
+        }
+    }
     f32x4 v[kMaxV4];
     float ss = 0.f;
     f32x4 *__restrict__ xrow = reinterpret_cast<f32x4 *>(x + (size_t)m * d);
@@ -216,14 +227,14 @@ __global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
 }  // namespace
 
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       float *sumsq_out, int M, int d, int vocab, float eps, hipStream_t stream) {
+                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_EMBED, stream);
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, true>, M, kRowThreads, 0, stream, (const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
-                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps);
+                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps, rt);
     else
         launch_kernel(residual_norm_kernel<float, true>, M, kRowThreads, 0, stream, (const float *)embed, tokens, vocab, nullptr, 0, 0, x,
-                                                                        (const float *)gain, xn, sumsq_out, d, eps);
+                                                                        (const float *)gain, xn, sumsq_out, d, eps, rt);
 }
 
 void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
@@ -232,10 +243,10 @@ void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *
     const size_t stride = (size_t)M * d;
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                            (const uint16_t *)gain, xn, nullptr, d, eps);
+                                                                            (const uint16_t *)gain, xn, nullptr, d, eps, RopeTable{});
     else
         launch_kernel(residual_norm_kernel<float, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                         (const float *)gain, xn, nullptr, d, eps);
+                                                                         (const float *)gain, xn, nullptr, d, eps, RopeTable{});
 }
 
 void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,
