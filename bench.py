@@ -50,6 +50,61 @@ def measured_traffic_bytes():
     return None
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
+
+
+def measure_ceilings(dev, quick=False):
+    """What the machine delivers on the two resources the kernels are bound by, from the library's two probe
+    kernels: a plain streaming read of 2 GiB (more than the 256 MB Infinity Cache; best of several grid sizes)
+    and a loop of nothing but 32x32x16 bf16 MFMAs on random operands.  Each figure is the best of the repeats."""
+    import torch
+    import paper_2510_26527_amd as psd
+    n_bytes = 1 << 31
+    src = torch.empty(n_bytes // 4, dtype=torch.int32, device=dev).random_(0, 1 << 30)
+    sink = torch.zeros(1 << 20, dtype=torch.float32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    read = {}
+    for blocks in ((2048,) if quick else (512, 1024, 2048, 4096, 8192)):
+        best = 0.0
+        for rep in range(3 if quick else 6):
+            e0.record()
+            psd.psd_probe_stream_read(src, sink, blocks)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep:
+                best = max(best, n_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        read[blocks] = best
+    del src
+    seed = torch.empty(1024, dtype=torch.float32, device=dev).normal_(0, 1).to(torch.bfloat16)
+    mfma = {}
+    iters = 4000 if quick else 20000
+    for blocks in ((512,) if quick else (256, 512, 1024)):
+        best = 0.0
+        for rep in range(3):
+            e0.record()
+            psd.psd_probe_mfma(seed, sink, blocks, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            flop = 2.0 * 32 * 32 * 16 * 4 * iters * 4 * blocks
+            if rep:
+                best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        mfma[blocks] = best
+    return {"stream_read_GB/s": max(read.values()), "stream_read_by_blocks": read,
+            "stream_read_frac_of_hbm_peak": max(read.values()) / HBM_PEAK_GBS,
+            "mfma_bf16_TFLOP/s": max(mfma.values()), "mfma_by_blocks": mfma,
+            "mfma_frac_of_published_peak": max(mfma.values()) / MFMA_BF16_PEAK_TFLOPS,
+            "how": "psd_probe_stream_read over 2 GiB (non-temporal 16-byte loads, 8 in flight per lane); psd_probe_mfma "
+                   "(32x32x16 bf16 on 4 accumulators per wavefront, random operands); best of the repeats"}
+
+
+def ceilings_workload(args, dev):
+    c = measure_ceilings(dev)
+    print(json.dumps({"metric": "measured ceilings of this MI355X", "unit": "GB/s and TFLOP/s", "n_gpus": 1,
+                      "data": "synthetic", "config": {"workload": "library probe kernels: streaming read, MFMA-only loop"},
+                      "published": {"hbm_GB/s": HBM_PEAK_GBS, "mfma_bf16_TFLOP/s": MFMA_BF16_PEAK_TFLOPS},
+                      "ceilings": c}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,11 +115,12 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten plain 1 GiB device-to-device copies (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
-    ap.add_argument("--workload", choices=["verify", "stress", "chain", "sweep"], default="verify",
+    ap.add_argument("--workload", choices=["verify", "stress", "chain", "sweep", "ceilings"], default="verify",
                     help="verify (default): configs[2] verify step + configs[1] acceptance, the headline line; "
                          "stress: configs[4], 16 sequences x 16 rows of a Qwen2-7B-shaped model; "
                          "chain: configs[3], the full-size three-level chain with the agreement harness; "
-                         "sweep: the projections of a LLaMA2-7B-shaped layer at 8 ... 4096 rows")
+                         "sweep: the projections of a LLaMA2-7B-shaped layer at 8 ... 4096 rows; "
+                         "ceilings: the measured streaming-read and MFMA-only rates of this GPU")
     ap.add_argument("--sigma", type=float, default=0.25, help="noise of the agreement harness (--workload chain)")
     ap.add_argument("--tokens", type=int, default=512, help="tokens to generate (--workload chain)")
     args = ap.parse_args()
@@ -99,10 +155,12 @@ def main():
         return chain_workload(args, dev)
     if args.workload == "sweep":
         return sweep_workload(args, dev)
+    if args.workload == "ceilings":
+        return ceilings_workload(args, dev)
 
     shape, gamma, ctx, max_len, temperature = synth.LLAMA2_7B, 8, 1024, 1088, 1.0
     w_cpu = synth.make_weights(shape, 3, torch.bfloat16)
-    model = runtime.Model(shape, w_cpu, dev).pack()      # streaming copy of the weights for the <= 64-row path
+    model = runtime.Model(shape, w_cpu, dev).pack()      # streaming copy of the weights for steps of <= 16 rows
     kv = runtime.KVCache(model, 1, max_len)
     ks, vs = synth.make_kv_fill(shape, 1, ctx, 4, torch.bfloat16)
     kv.load(ks, vs, ctx)
@@ -139,6 +197,40 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     accepted = int(out["n"].item())
 
+    # mean tokens committed per verify step (accepted + 1) over steps that differ only in their uniforms
+    n_draws = 32
+    kept = torch.zeros(n_draws, dtype=torch.int32, device=dev)
+    for i in range(n_draws):
+        u_i = synth.make_uniforms((1, gamma + 1), 1000 + i, dev)
+        runtime.forward(model, kv, tokens, logits_out=p_buf)
+        n_i, _, _ = acc(p_buf, q_logits, draft, u_i, temperature)
+        kept[i:i + 1].copy_(n_i)
+        psd.psd_kv_truncate_to(kv.handle, ctx)
+    mean_committed = float(kept.float().mean().item()) + 1.0
+
+    # the same step with the bonus row (n_new = gamma + 1: the x* row and the gamma draft tokens, as in the chain)
+    tokens9 = torch.from_numpy(synth.make_tokens(shape.vocab, (1, gamma + 1), 34)).to(dev)
+    p9 = torch.empty((1, gamma + 1, shape.vocab), dtype=torch.float32, device=dev)
+    runtime.forward(model, kv, tokens9, logits_out=p9)
+    psd.psd_kv_truncate_to(kv.handle, ctx)
+    q9, draft9 = synth.make_draft_from_target(p9[:, :gamma], 0.5, 8)
+
+    def step9():
+        runtime.forward(model, kv, tokens9, logits_out=p9)
+        n, tok, fl = acc(p9, q9, draft9, uniforms, temperature)
+        psd.psd_kv_truncate(kv.handle, base, n, 1, ctx + 1 + gamma)
+        psd.psd_kv_truncate_to(kv.handle, ctx)
+
+    for _ in range(3):
+        step9()
+    torch.cuda.synchronize()
+    t9 = time.perf_counter()
+    for _ in range(min(args.steps, 30)):
+        step9()
+    torch.cuda.synchronize()
+    ms9 = (time.perf_counter() - t9) * 1e3 / min(args.steps, 30)
+    ceilings = measure_ceilings(dev, quick=True)
+
     # same steps again with every launch bracketed by HIP events on its stream
     launches_per_step = 40 * shape.n_layers + 64
     prof_steps = min(args.steps, 20)
@@ -157,7 +249,9 @@ def main():
     roofline = {"kernel": "gemm_bf16_stream_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
                 "bytes_per_launch": stream_bytes * prof_steps / sk_n, "avg_launch_us": 1e3 * sk_ms / sk_n,
-                "launches_per_step": sk_n / prof_steps}
+                "launches_per_step": sk_n / prof_steps,
+                "measured_stream_read_GB/s": ceilings["stream_read_GB/s"],
+                "frac_of_measured_stream_read": achieved / ceilings["stream_read_GB/s"]}
     if "gemm_column" in prof and prof["gemm_column"][1]:
         c_ms, c_n = prof["gemm_column"]
         c_bytes = w_bytes - stream_bytes
@@ -168,6 +262,13 @@ def main():
         roofline["all_weight_streaming_GB/s"] = w_bytes * prof_steps / ((sk_ms + c_ms) * 1e-3) / 1e9
     kv_bytes = 2 * shape.n_layers * shape.n_kv_heads * (ctx + gamma) * shape.d_head * 2
     step_floor_ms = (w_bytes + kv_bytes) / (HBM_PEAK_GBS * 1e9) * 1e3
+    a_ms, a_n = prof["attn"]
+    cmb_ms = prof["attn_combine"][0] if "attn_combine" in prof else 0.0
+    attention = {"kernel": "attn_mfma_kernel (split over the KV length; builds q / k / v from the QKV partial sums)",
+                 "bytes_per_layer": kv_bytes / shape.n_layers, "avg_launch_us": 1e3 * a_ms / a_n,
+                 "GB/s": kv_bytes * prof_steps / (a_ms * 1e-3) / 1e9,
+                 "GB/s_with_combine": kv_bytes * prof_steps / ((a_ms + cmb_ms) * 1e-3) / 1e9,
+                 "frac_of_hbm_peak": kv_bytes * prof_steps / (a_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     # ---- the isolated acceptance workload (configs[1]): 64 x 8 x 32000 bf16, cold HBM
     sets = [synth.make_accept_inputs(64, 8, 32000, 100 + i, dtype=torch.bfloat16, device=dev) for i in range(6)]
@@ -238,7 +339,13 @@ def main():
                                "1024-token N(0,1) bf16 KV cache, forward + acceptance + KV rollback",
                    "gamma": gamma, "n_new": gamma, "kv_len": ctx, "batch": 1, "temperature": temperature},
         "accepted_this_step": accepted,
+        "mean_tokens_committed_per_step": mean_committed,
+        "expected_committed_tokens/s": mean_committed * 1e3 / ms_per_step,
+        "with_bonus_row": {"n_new": gamma + 1, "ms_per_step": ms9, "verified_tokens/s": gamma * 1e3 / ms9},
         "step_floor_ms_at_hbm_peak": step_floor_ms,
+        "step_floor_ms_at_measured_stream_read": (w_bytes + kv_bytes) / (ceilings["stream_read_GB/s"] * 1e9) * 1e3,
+        "ceilings": ceilings,
+        "attention": attention,
         "roofline": roofline, "cpu_baseline": cpu_baseline, "accept_kernel": accept, "kernels": kernels,
     }
     print(json.dumps(line))
@@ -294,6 +401,35 @@ def stress_workload(args, dev):
     psd.psd_profile_enable(0)
     kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * t / c, "ms_per_step": t / prof_steps}
                for k, (t, c) in prof.items() if c}
+    # the oracle on the host cores: ONE of the 16 sequences (its 16 rows against its 4096-token cache), forward +
+    # acceptance + rollback; the other fifteen would cost the same again each
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import accept as oacc
+        from oracle import forward as ofwd
+        from threadpoolctl import threadpool_info
+        b0 = 0
+        cfg = ofwd.ModelConfig(**shape.asdict())
+        w_host = {k: v.cpu() for k, v in w.items()}
+        okv = ofwd.KVCache(cfg, 1, max_len, np.float32)
+        for l in range(shape.n_layers):
+            okv.k[l][:, :, :ctx] = kv.k[l, b0:b0 + 1, :, :ctx].float().cpu().numpy()
+            okv.v[l][:, :, :ctx] = kv.v[l, b0:b0 + 1, :, :, :ctx].transpose(-1, -2).float().cpu().numpy()
+        okv.lens[:] = ctx
+        tok_host = tokens[b0:b0 + 1].cpu().numpy()
+        q_host, d_host = q_logits[b0:b0 + 1].cpu().double().numpy(), draft[b0:b0 + 1].cpu().numpy()
+        u_host = uniforms[b0:b0 + 1].cpu().double().numpy()
+        c0 = time.perf_counter()
+        ref = ofwd.forward(cfg, w_host, tok_host, okv)
+        oacc.spec_accept(ref, q_host, d_host, u_host, 1.0)
+        okv.truncate(ctx)
+        c1 = time.perf_counter()
+        threads = max([torch.get_num_threads()] + [p.get("num_threads", 1) for p in threadpool_info()])
+        cpu_baseline = {"value": gamma / (c1 - c0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                        "sample": "one of the 16 sequences (16 rows on a 4096-token cache: forward in numpy fp64, acceptance "
+                                  "in C fp64, rollback), %.1f s; the whole step is 16 of these" % (c1 - c0)}
+        del w_host, okv
     s = shape
     hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
     flops = 2.0 * B * gamma * (s.n_layers * (s.d_model * (hd + 2 * kvd) + hd * s.d_model + 3 * s.d_model * s.d_ffn)
@@ -316,7 +452,7 @@ def stress_workload(args, dev):
                      "note": "useful flops; activations enter as bf16 hi + lo pairs, so twice as many MFMAs are issued"},
         "attention": {"kernel": "attn_mfma_wide_kernel", "bytes_per_step": kv_bytes, "ms_per_step": a_ms,
                       "GB/s": kv_bytes / (a_ms * 1e-3) / 1e9},
-        "cpu_baseline": None, "kernels": kernels,
+        "cpu_baseline": cpu_baseline, "kernels": kernels,
     }
     print(json.dumps(line))
 
@@ -341,9 +477,11 @@ def chain_workload(args, dev):
     tapes = [synth.make_tape(14, 0, 3 * n_gen, 16), synth.make_tape(14, 1, 6 * n_gen, 16),
              synth.make_tape(14, 2, 30 * n_gen, 1)[:, 0]]
     g = shim.AgreementShimChain(levels, gammas, tapes, args.sigma, noise_seed=5, temperature=1.0, max_len=max_len, timed=True)
+    g.forward_log = []
     t0 = time.perf_counter()
     g.generate(prompt, n_gen)
     wall_ms = (time.perf_counter() - t0) * 1e3
+    cpu_baseline = None if args.no_cpu_baseline else chain_cpu_baseline(g, levels, [tw, mw, dw], n_prompt, max_len)
     rep = costmodel.chain_report(n_gen, [lv.forwards for lv in levels], [lv.time_ms for lv in levels], g.accept_ms)
     # the target decoding alone, one token per forward, same kernels and cache length
     tgt = levels[0]
@@ -371,9 +509,46 @@ def chain_workload(args, dev):
                         "untimed target peeks and the host loop are excluded",
         "report": rep, "tokens_per_target_forward": n_gen / rep["F"][0],
         "target_only_ms_per_token": t_ar, "speedup_vs_target_only": t_ar * n_gen / chain_ms,
-        "harness": {"peeks": g.peeks, "peek_ms": g.peek_ms, "wall_ms": wall_ms}, "cpu_baseline": None,
+        "harness": {"peeks": g.peeks, "peek_ms": g.peek_ms, "wall_ms": wall_ms}, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(line))
+
+
+def chain_cpu_baseline(g, levels, weights, n_prompt, max_len):
+    """The oracle's forwards over the chain's first target cycle: every forward the three models made from the end
+    of the prompt up to and including the target's first verification, replayed on the host cores from the same
+    cache state (the prompt's K/V are copied from the GPU caches; the harness's untimed target peeks are left out,
+    as they are from the GPU figure)."""
+    import numpy as np
+    import torch
+    from oracle import forward as ofwd
+    from threadpoolctl import threadpool_info
+    shapes = [lv.model.shape for lv in levels]
+    cfgs = [ofwd.ModelConfig(**sh.asdict()) for sh in shapes]
+    w_host = [{k: v.cpu() for k, v in w.items()} for w in weights]
+    okvs = []
+    for lv, cfg, sh in zip(levels, cfgs, shapes):
+        okv = ofwd.KVCache(cfg, 1, max_len, np.float32)
+        for l in range(sh.n_layers):
+            okv.k[l][:, :, :n_prompt - 1] = lv.kv.k[l, :, :, :n_prompt - 1].float().cpu().numpy()
+            okv.v[l][:, :, :n_prompt - 1] = lv.kv.v[l, :, :, :, :n_prompt - 1].transpose(-1, -2).float().cpu().numpy()
+        okv.lens[:] = n_prompt - 1
+        okvs.append(okv)
+    first = [k for k, ev in enumerate(g.forward_log) if ev[0] == 0 and ev[1] >= n_prompt - 1][0]
+    cycle = [ev for ev in g.forward_log[:first + 1] if ev[1] >= n_prompt - 1]
+    committed = len(cycle[-1][2]) - 1          # upper bound of what the cycle commits: its block + the extra token
+    c0 = time.perf_counter()
+    for i, start, toks in cycle:
+        if int(okvs[i].lens[0]) > start:
+            okvs[i].truncate(start)
+        ofwd.forward(cfgs[i], w_host[i], np.asarray([toks], np.int32), okvs[i])
+    c1 = time.perf_counter()
+    threads = max([torch.get_num_threads()] + [p.get("num_threads", 1) for p in threadpool_info()])
+    counts = [sum(1 for ev in cycle if ev[0] == i) for i in range(len(levels))]
+    return {"value": committed / (c1 - c0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "the forwards of the first target cycle (%d target, %d intermediate, %d draft forwards, at most %d "
+                      "tokens committed) in numpy fp64, %.1f s; acceptance calls left out (milliseconds)"
+                      % (counts[0], counts[1], counts[2], committed, c1 - c0)}
 
 
 def sweep_workload(args, dev):

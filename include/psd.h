@@ -254,6 +254,18 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 psd_status psd_profile_enable(int32_t max_launches);
 psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind);
 
+/* Two microkernels that measure what the machine delivers, so that a bench can state roofline fractions against
+ * measured ceilings beside the published peaks.  Each call enqueues ONE launch on the stream; the caller times it.
+ *   psd_probe_stream_read  reads `bytes` (a multiple of 16) of device memory at src_dev once, `blocks` blocks of
+ *                          256 threads each on an equal contiguous share, eight non-temporal 16-byte loads in
+ *                          flight per lane; sink_dev: device, >= 4 bytes (practically never written).
+ *   psd_probe_mfma         `blocks` blocks of four wavefronts, each wavefront issuing 4 * iters 32x32x16 bf16
+ *                          matrix-core instructions (2 * 32 * 32 * 16 flop each) on operands read from seed_dev
+ *                          (device, 1024 bf16 values); sink_dev: device fp32[blocks * 256].
+ * PSD_ERR_NULL / PSD_ERR_SHAPE on bad arguments, PSD_ERR_HIP if the launch fails. */
+psd_status psd_probe_stream_read(const void *src_dev, size_t bytes, void *sink_dev, int32_t blocks, void *hip_stream);
+psd_status psd_probe_mfma(const void *seed_dev, float *sink_dev, int32_t blocks, int32_t iters, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,8 @@ _SIGNATURES = {
                                       _vp, _vp]),
     "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "psd_kv_truncate_to": (_i32, [_vp, _i32, _vp]),
+    "psd_probe_stream_read": (_i32, [_vp, _sz, _vp, _i32, _vp]),
+    "psd_probe_mfma": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "psd_profile_enable": (_i32, [_i32]),
     "psd_profile_collect": (_i32, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]),
 }
@@ -202,6 +204,15 @@ def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, new_len_upper_boun
 
 def psd_kv_truncate_to(kv, new_len, stream=None):
     _check(lib().psd_kv_truncate_to(kv, new_len, _stream_ptr(stream)), "psd_kv_truncate_to")
+
+
+def psd_probe_stream_read(src_dev, sink_dev, blocks, stream=None):
+    _check(lib().psd_probe_stream_read(_ptr(src_dev), src_dev.numel() * src_dev.element_size(), _ptr(sink_dev), blocks,
+                                       _stream_ptr(stream)), "psd_probe_stream_read")
+
+
+def psd_probe_mfma(seed_dev, sink_dev, blocks, iters, stream=None):
+    _check(lib().psd_probe_mfma(_ptr(seed_dev), _ptr(sink_dev), blocks, iters, _stream_ptr(stream)), "psd_probe_mfma")
 
 
 def psd_profile_enable(max_launches):

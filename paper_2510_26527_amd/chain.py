@@ -67,6 +67,7 @@ class Chain:
         self.accept_lens = [[] for _ in range(self.n)]
         self.block_lens = [[] for _ in range(self.n)]
         self.accept_ms = 0.0
+        self.forward_log = None       # a list: every forward is recorded there as (level, first position, tokens)
 
     # -------------------------------------------------------------- one forward of level i
     def _forward(self, i, n_logit_rows, out_row):
@@ -86,6 +87,8 @@ class Chain:
         lvl.kv_len = self.seq_len
         lvl.forwards += 1
         self._rows_ready(i, dst, n_logit_rows)
+        if self.forward_log is not None:
+            self.forward_log.append((i, start, toks.cpu().tolist()))
         if self.trace:
             self._emit(("forward", i, start, toks.cpu().tolist(),
                                 None if dst is None else dst.detach().clone()))

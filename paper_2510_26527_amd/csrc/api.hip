@@ -594,6 +594,22 @@ psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind) {
     return PSD_OK;
 }
 
+psd_status psd_probe_stream_read(const void *src_dev, size_t bytes, void *sink_dev, int32_t blocks, void *hip_stream) {
+    if (!src_dev || !sink_dev) return PSD_ERR_NULL;
+    if (bytes == 0 || bytes % 16 || (uintptr_t)src_dev % 16 || blocks <= 0 || blocks > (1 << 20)) return PSD_ERR_SHAPE;
+    (void)hipGetLastError();
+    launch_probe_read(src_dev, bytes, sink_dev, blocks, (hipStream_t)hip_stream);
+    return check_launch();
+}
+
+psd_status psd_probe_mfma(const void *seed_dev, float *sink_dev, int32_t blocks, int32_t iters, void *hip_stream) {
+    if (!seed_dev || !sink_dev) return PSD_ERR_NULL;
+    if ((uintptr_t)seed_dev % 16 || blocks <= 0 || blocks > (1 << 20) || iters <= 0) return PSD_ERR_SHAPE;
+    (void)hipGetLastError();
+    launch_probe_mfma(seed_dev, sink_dev, blocks, iters, (hipStream_t)hip_stream);
+    return check_launch();
+}
+
 psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream) {
     if (!kv) return PSD_ERR_NULL;
     if (new_len < 0) return PSD_ERR_SHAPE;

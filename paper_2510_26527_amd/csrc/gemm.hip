@@ -415,7 +415,6 @@ __global__ __launch_bounds__(256) void gemm_pack_strip_kernel(const uint16_t *W,
 // integers 128 + q (bit pattern 0x4300 | q), and takes scale * (sum (128 + q) x - (128 + zero) sum x) per
 // group, so no weight is ever rounded.
 constexpr int kW4StripBytes = 1024 + 64;
-constexpr int kW4StripVec = kW4StripBytes / 16;
 
 __global__ __launch_bounds__(64) void gemm_pack_w4_kernel(const uint8_t *Q, const uint16_t *scale, const uint8_t *zero,
                                                           int N, int K, uint8_t *dst) {
@@ -558,11 +557,18 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 // One block per 64 output columns (four strips of the strip-major 4-bit layout) over the whole K range, eight
 // wavefronts on different K ranges, added through LDS in wavefront order; single owner per output, the same
 // epilogue as the column kernel (plain output, or residual add + gain-scaled copy + per-strip sums of squares).
-// 4-bit weights are a quarter of the bytes, so the activations (4 bytes each, re-read by every block) weigh
-// as much as the weights of a 64-row tile; a 16-row strip per block would read four times more of them.
+// 4-bit weights are a quarter of the bytes, so the fp32 activations a block reads from L2 weigh as much as its
+// weights already at 64 columns (and four times as much at 16): hence the wide tile.  Every wavefront keeps the
+// next K step's codes, scales and activations in flight while it multiplies the current one.
 // Per group of 128 K (one step): u = sum (128 + q) x on the matrix cores with the codes as exact bf16
 // integers, xs = sum x with an all-ones operand, then acc += scale * (u - (128 + zero) * xs) in fp32.
-constexpr int kW4Waves = 16, kW4Strips = 2, kW4Cols = 16 * kW4Strips;
+constexpr int kW4Waves = 8, kW4Strips = 4, kW4Cols = 16 * kW4Strips;
+
+struct W4Step {
+    u32x4 code[kW4Strips];          // this lane's 32 nibbles of each strip (dword q = its MFMA operand of K quarter q)
+    uint2 sc[kW4Strips], zr[kW4Strips];   // scales and 128 + zero of rows 4 gq .. 4 gq + 3 of each strip, as bf16
+    f32x8 x[4];                     // activations of token i, K offsets of quarter q
+};
 
 __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -580,57 +586,57 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
 #pragma unroll
     for (int s = 0; s < kW4Strips; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int D = 4;                                   // K steps per round: 8 KB of codes in flight per wavefront
-    for (int step = s0; step < s1; step += D) {
-        u32x4 a[D][kW4Strips];
-        uint2 sc[D][kW4Strips], zr[D][kW4Strips];
+    auto load_step = [&](W4Step &d, int step) {
 #pragma unroll
-        for (int j = 0; j < D; ++j)
-            if (step + j < s1) {
+        for (int s = 0; s < kW4Strips; ++s) {
+            const uint8_t *base = wq + s * strip_stride + (size_t)step * kW4StripBytes;
+            d.code[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + lane);
+            d.sc[s] = *reinterpret_cast<const uint2 *>(base + 1024 + gq * 8);     // rows 4 gq .. 4 gq + 3
+            d.zr[s] = *reinterpret_cast<const uint2 *>(base + 1056 + gq * 8);
+        }
 #pragma unroll
-                for (int s = 0; s < kW4Strips; ++s) {
-                    const uint8_t *base = wq + s * strip_stride + (size_t)(step + j) * kW4StripBytes;
-                    a[j][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + lane);
-                    sc[j][s] = *reinterpret_cast<const uint2 *>(base + 1024 + gq * 8);     // rows 4 gq .. 4 gq + 3
-                    zr[j][s] = *reinterpret_cast<const uint2 *>(base + 1056 + gq * 8);
-                }
-            }
+        for (int q = 0; q < 4; ++q)
+            d.x[q] = load_act8(xp, step * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid);
+    };
+    auto multiply = [&](const W4Step &d) {
+        f32x4 u[kW4Strips], xs = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < D; ++j) {
-            if (step + j >= s1) break;
-            f32x8 xv[4];
+        for (int s = 0; s < kW4Strips; ++s) u[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                xv[q] = load_act8(xp, (step + j) * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid);
-            f32x4 u[kW4Strips], xs = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < kW4Strips; ++s) u[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                bf16x8 bh, bl;
-                split_bf16(xv[q], &bh, &bl);
-#pragma unroll
-                for (int s = 0; s < kW4Strips; ++s) {
-                    const uint32_t w = a[j][s][q];
-                    const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
-                                           ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u};
-                    const bf16x8 aw = __builtin_bit_cast(bf16x8, wi);
-                    u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u[s], 0, 0, 0);
-                    u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u[s], 0, 0, 0);
-                }
-                xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh, xs, 0, 0, 0);       // sum of x over the group
-                xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl, xs, 0, 0, 0);
-            }
+        for (int q = 0; q < 4; ++q) {
+            bf16x8 bh, bl;
+            split_bf16(d.x[q], &bh, &bl);
 #pragma unroll
             for (int s = 0; s < kW4Strips; ++s) {
-                const float scl[4] = {__uint_as_float(sc[j][s].x << 16), __uint_as_float(sc[j][s].x & 0xffff0000u),
-                                      __uint_as_float(sc[j][s].y << 16), __uint_as_float(sc[j][s].y & 0xffff0000u)};
-                const float zpt[4] = {__uint_as_float(zr[j][s].x << 16), __uint_as_float(zr[j][s].x & 0xffff0000u),
-                                      __uint_as_float(zr[j][s].y << 16), __uint_as_float(zr[j][s].y & 0xffff0000u)};
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[s][v] += scl[v] * (u[s][v] - zpt[v] * xs[v]);
+                const uint32_t w = d.code[s][q];
+                const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
+                                       ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u};
+                const bf16x8 aw = __builtin_bit_cast(bf16x8, wi);
+                u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u[s], 0, 0, 0);
+                u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u[s], 0, 0, 0);
             }
+            xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh, xs, 0, 0, 0);       // sum of x over the group
+            xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl, xs, 0, 0, 0);
         }
+#pragma unroll
+        for (int s = 0; s < kW4Strips; ++s) {
+            const float scl[4] = {__uint_as_float(d.sc[s].x << 16), __uint_as_float(d.sc[s].x & 0xffff0000u),
+                                  __uint_as_float(d.sc[s].y << 16), __uint_as_float(d.sc[s].y & 0xffff0000u)};
+            const float zpt[4] = {__uint_as_float(d.zr[s].x << 16), __uint_as_float(d.zr[s].x & 0xffff0000u),
+                                  __uint_as_float(d.zr[s].y << 16), __uint_as_float(d.zr[s].y & 0xffff0000u)};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[s][v] += scl[v] * (u[s][v] - zpt[v] * xs[v]);
+        }
+    };
+
+    // two K steps per round, the second one and the next round's first always in flight
+    W4Step a, b;
+    if (s0 < s1) load_step(a, s0);
+    for (int step = s0; step < s1; step += 2) {
+        if (step + 1 < s1) load_step(b, step + 1);
+        multiply(a);
+        if (step + 2 < s1) load_step(a, step + 2);
+        if (step + 1 < s1) multiply(b);
     }
 
     // acc[s][v] = y[token i][tile column s*16 + 4*gq + v] over this wavefront's K steps
@@ -640,9 +646,10 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
 #pragma unroll
         for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][v];
     __syncthreads();
-    // thread t < 512: column n = t & 15 of strip t >> 8, token mm = (t >> 4) & 15
-    if (threadIdx.x < 256 * kW4Strips) {
-        const int en = threadIdx.x & 15, emm = (threadIdx.x >> 4) & 15, strip = threadIdx.x >> 8;
+    // thread t of pass p: column en = t & 15 of strip 2 p + (t >> 8), token emm = (t >> 4) & 15
+#pragma unroll
+    for (int pass = 0; pass < kW4Strips / 2; ++pass) {
+        const int en = threadIdx.x & 15, emm = (threadIdx.x >> 4) & 15, strip = 2 * pass + (threadIdx.x >> 8);
         const int col = blockIdx.x * kW4Cols + strip * 16 + en;
         float v = 0.f, sq = 0.f;
 #pragma unroll
@@ -921,13 +928,11 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         tiled_choice(g.M, g.K, g.n, g.nseg, &nb, &sk);
         if (sk != g.splitk) nb = 5;                       // the caller sized the partial slots for its own split
         dim3 grid(tiles_of(g.n, g.nseg, 32 * nb) * ((g.M + kBM - 1) / kBM), g.splitk);
-        static bool lds_ok[kMaxNB + 1] = {};              // opt in once per instantiation to more than 64 KB of dynamic LDS
         auto go = [&](auto kernel) {
-            if (!lds_ok[nb]) {
-                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)kTiledLds);
-                lds_ok[nb] = true;
-            }
+            // opt in to more than 64 KB of dynamic LDS: a property of the function on the current device, set before
+            // every launch (a cheap host call) so that no process-wide flag has to remember who set it where
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)kTiledLds);
             launch_kernel(kernel, grid, 256, kTiledLds, stream, g);
         };
         if (nb == 4) go(gemm_bf16_tiled_kernel<4>);

@@ -121,6 +121,10 @@ bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h);
 int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound);
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 
+// ---------------------------------------------------------------- measured ceilings (ceilings.hip)
+void launch_probe_read(const void *src, size_t bytes, void *sink, int blocks, hipStream_t stream);
+void launch_probe_mfma(const void *seed, void *sink, int blocks, int iters, hipStream_t stream);
+
 // ---------------------------------------------------------------- row-wise kernels (rowwise.hip)
 // optional by-product of the embedding kernel: cs[m][i] = (cos, sin) of (lens[m / R] + m % R) * theta^(-2i/d_h)
 struct RopeTable {

@@ -192,7 +192,7 @@ def test_workload4_full_three_level_chain(chain4_models, sigma):
               gchain.Level(chain4_models[2], max_len, 7)]
     prompt = synth.make_tokens(synth.LLAMA3_8B.vocab, (n_prompt,), 77).tolist()
     tapes = [synth.make_tape(14, 0, 3 * n_gen, 16), synth.make_tape(14, 1, 3 * n_gen, 16),
-             synth.make_tape(14, 2, 8 * n_gen, 1)[:, 0]]
+             synth.make_tape(14, 2, 12 * n_gen, 1)[:, 0]]
     st = {"accepts": [0, 0], "ties": 0, "samples": 0, "tested": [0, 0], "passed": [0, 0]}
 
     def sink(ev):

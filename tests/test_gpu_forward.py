@@ -209,6 +209,52 @@ def test_batched_verify_loop_with_per_sequence_rollback_only():
     p.close()
 
 
+def test_outputs_and_scratch_stay_inside_their_buffers():
+    """Canaries around everything the calls write: logits, the forward workspace (sized by the library's own
+    answer), the acceptance outputs and workspace.  A kernel that writes one element past its buffer flips one."""
+    dev = torch.device("cuda")
+    guard, mark = 1024, -12345.0
+    for shape, n_new, ctx, pack in ((SMALL_GQA, 8, 300, True), (SMALL_MHA, 11, 77, False), (SMALL_G7, 17, 520, True),
+                                    (SMALL_MHA, 70, 200, False)):
+        w = synth.make_weights(shape, 9, torch.bfloat16, std=0.05)
+        model = runtime.Model(shape, w)
+        if pack:
+            model.pack()
+        max_len = (ctx + n_new + 63) // 64 * 64
+        kv = runtime.KVCache(model, 1, max_len)
+        ks, vs = synth.make_kv_fill(shape, 1, ctx, 10, torch.bfloat16)
+        kv.load(ks, vs, ctx)
+        need = psd.psd_model_workspace_bytes(model.handle, 1, n_new, max_len)
+        ws_all = torch.full((need // 4 + 2 * guard,), mark, dtype=torch.float32, device=dev)
+        ws = ws_all[guard:guard + need // 4].view(torch.uint8)
+        assert ws.data_ptr() % 256 == 0
+        lg_all = torch.full((n_new * shape.vocab + 2 * guard,), mark, dtype=torch.float32, device=dev)
+        logits = lg_all[guard:guard + n_new * shape.vocab].view(1, n_new, shape.vocab)
+        toks = torch.from_numpy(synth.make_tokens(shape.vocab, (1, n_new), 5)).to(dev)
+        psd.psd_model_forward(model.handle, toks, n_new, kv.handle, logits, n_new, ws)
+        torch.cuda.synchronize()
+        for name, t, n in (("workspace", ws_all, need // 4), ("logits", lg_all, n_new * shape.vocab)):
+            assert bool((t[:guard] == mark).all()) and bool((t[guard + n:] == mark).all()), f"{name} guard touched ({shape}, {n_new})"
+        assert bool(torch.isfinite(logits).all())
+        # acceptance on these logits
+        gamma = n_new - 1
+        q, x = synth.make_draft_from_target(logits[:, :gamma], 0.5, 3)
+        u = synth.make_uniforms((1, gamma + 1), 4, dev)
+        a_need = psd.psd_spec_accept_workspace_bytes(1, gamma, n_new, shape.vocab)
+        aw_all = torch.full((a_need // 4 + 2 * guard,), mark, dtype=torch.float32, device=dev)
+        aw = aw_all[guard:guard + a_need // 4].view(torch.uint8)
+        out_all = torch.full((3 + 2 * 64,), -777, dtype=torch.int32, device=dev)
+        out = out_all[64:67]
+        psd.psd_spec_accept(logits, q, x, gamma, u, 1.0, out[0:1], out[1:2], 1, n_new, shape.vocab, psd.PSD_F32,
+                            n_new * shape.vocab, gamma * shape.vocab, out[2:3], aw)
+        torch.cuda.synchronize()
+        assert bool((aw_all[:guard] == mark).all()) and bool((aw_all[guard + a_need // 4:] == mark).all())
+        assert bool((out_all[:64] == -777).all()) and bool((out_all[67:] == -777).all())
+        assert 0 <= int(out[0]) <= gamma
+        kv.close()
+        model.close()
+
+
 def test_forward_is_deterministic():
     shape = SMALL_MHA
     w = synth.make_weights(shape, 3, torch.bfloat16, std=0.05)
