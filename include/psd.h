@@ -99,9 +99,10 @@ psd_status psd_model_destroy(psd_model *m);
  * [n][K/128] with values 0..15.  Embedding, norm gains, lm_head and the KV cache stay bf16; activations are
  * handled as in PSD_BF16 models; no weight is rounded: the codes enter the matrix cores as exact integers and
  * scale and zero point are applied per group in fp32.
- * Such a model must be packed (psd_model_pack) before its first forward, and a forward takes at most 16 rows
- * (batch * n_new <= 16; longer prompts are fed in several calls): otherwise PSD_ERR_UNIMPLEMENTED.
- * Further limit: n_kv_heads * d_head a multiple of 64. */
+ * Such a model must be packed (psd_model_pack) before its first forward (PSD_ERR_UNIMPLEMENTED otherwise).  Its
+ * projections exist for steps of at most 16 rows (batch * n_new <= 16): a longer step of ONE sequence (a prompt)
+ * is run by psd_model_forward as consecutive steps of 16 rows, which computes the same function; a longer step of
+ * several sequences is PSD_ERR_UNIMPLEMENTED.  Further limit: n_kv_heads * d_head a multiple of 64. */
 psd_status psd_model_create_w4(const psd_model_desc *desc, const void *const *weight_ptrs, int32_t n_ptrs,
                                const void *const *scale_ptrs, const void *const *zero_ptrs,
                                int32_t n_quant_ptrs, psd_model **out);
@@ -250,7 +251,8 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_ACCEPT_DRAW 12      /* first rejection + fp64 pass over the one position the draw reads */
 #define PSD_KIND_ACCEPT_LOCATE 13    /* greedy verification: the walk over the per-position argmax */
 #define PSD_KIND_GEMM_COLUMN 14      /* bf16 one-slot GEMM with the residual epilogue, M <= 16 */
-#define PSD_KIND_COUNT 15
+#define PSD_KIND_GEMM_W4 15          /* 4-bit weight-only GEMM, M <= 16 */
+#define PSD_KIND_COUNT 16
 psd_status psd_profile_enable(int32_t max_launches);
 psd_status psd_profile_collect(double *ms_by_kind, int64_t *launches_by_kind);
 

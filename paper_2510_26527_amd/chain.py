@@ -172,9 +172,8 @@ class Chain:
 
     def _forward_prefill(self, i):
         lvl = self.levels[i]
-        chunk = lvl.model.max_rows_per_call or (self.seq_len - lvl.kv_len)    # 4-bit models take 16 rows per call
-        while lvl.kv_len < self.seq_len:
-            n_new = min(chunk, self.seq_len - lvl.kv_len)
+        n_new = self.seq_len - lvl.kv_len
+        if n_new > 0:
             ws = lvl.model.workspace(1, n_new, lvl.kv.max_len)
             psd.psd_model_forward(lvl.model.handle, self.seq[lvl.kv_len:lvl.kv_len + n_new], n_new, lvl.kv.handle,
                                   None, 0, ws)

@@ -279,9 +279,11 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.width_qkv = hd + 2 * kvd;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
     const int Ml = batch * n_logit_rows;
-    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;        // 4-bit models: always (checked by the caller)
+    // 4-bit models run unfolded: their projections with N = d_model are split along K over several blocks, so no
+    // block owns an output column and the residual add + norm is the stand-alone kernel's
+    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows && !mdl->w4;
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
-        if (mdl->w4 && n != n_v) return 1;                  // the one-slot column kernel
+        if (mdl->w4 && n != n_v) return gemm_w4_splits(K, n, nseg);
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
@@ -329,6 +331,16 @@ extern "C" {
 
 size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_new, int32_t max_len) {
     if (!m || max_len <= 0 || !forward_shape_ok(m, batch, n_new)) return 0;
+    if (m->w4 && batch * n_new > kStreamMaxRows) {
+        // a longer step of one sequence runs as consecutive steps of at most kStreamMaxRows rows: the largest need of those
+        if (batch != 1) return 0;
+        size_t worst = 0;
+        for (int r = 1; r <= kStreamMaxRows; ++r) {
+            const size_t b = psd_model_workspace_bytes(m, 1, r, max_len);
+            worst = b > worst ? b : worst;
+        }
+        return worst;
+    }
     // split choices depend on the cache length bound and on how many rows get logits:
     // take the largest need over all of them
     size_t worst = 0;
@@ -341,18 +353,46 @@ size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_ne
     return worst;
 }
 
+static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
+                               float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
+                               void *hip_stream);
+
 psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
                              float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
                              void *hip_stream) {
     if (!m || !tokens_dev || !kv) return PSD_ERR_NULL;
     if (kv->m != m) return PSD_ERR_SHAPE;
-    const psd_model_desc &d = m->d;
     const int B = kv->batch;
     if (!forward_shape_ok(m, B, n_new)) return PSD_ERR_SHAPE;
     if (n_logit_rows < 0 || n_logit_rows > n_new) return PSD_ERR_SHAPE;
     if (n_logit_rows > 0 && !logits_out_dev) return PSD_ERR_NULL;
     if (kv->len_ub + n_new > kv->max_len) return PSD_ERR_CAPACITY;
-    if (m->w4 && (!m->packed || B * n_new > kStreamMaxRows)) return PSD_ERR_UNIMPLEMENTED;
+    if (m->w4 && !m->packed) return PSD_ERR_UNIMPLEMENTED;
+    if (m->w4 && B * n_new > kStreamMaxRows) {
+        // 4-bit projections exist for steps of up to kStreamMaxRows rows: a longer step of one sequence (a prompt)
+        // runs as consecutive steps of that size, which computes the same function (the cache carries the prefix)
+        if (B != 1) return PSD_ERR_UNIMPLEMENTED;
+        if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < psd_model_workspace_bytes(m, 1, n_new, kv->max_len))
+            return PSD_ERR_WORKSPACE;
+        const int first_logit = n_new - n_logit_rows;
+        for (int c0 = 0; c0 < n_new; c0 += kStreamMaxRows) {
+            const int c1 = c0 + kStreamMaxRows < n_new ? c0 + kStreamMaxRows : n_new;
+            const int from = c0 > first_logit ? c0 : first_logit;            // first row of this piece that wants logits
+            const int rows = c1 > from ? c1 - from : 0;
+            float *out = rows ? logits_out_dev + (size_t)(from - first_logit) * m->d.vocab : nullptr;
+            const psd_status s = forward_once(m, tokens_dev + c0, c1 - c0, kv, out, rows, workspace, ws_bytes, hip_stream);
+            if (s != PSD_OK) return s;      // pieces already enqueued stay enqueued: the cache then holds a prefix of the step
+        }
+        return PSD_OK;
+    }
+    return forward_once(m, tokens_dev, n_new, kv, logits_out_dev, n_logit_rows, workspace, ws_bytes, hip_stream);
+}
+
+static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
+                               float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
+                               void *hip_stream) {
+    const psd_model_desc &d = m->d;
+    const int B = kv->batch;
     const int len_bound = kv->len_ub + n_new;
     const ForwardPlan p = plan_forward(m, B, n_new, n_logit_rows, len_bound);
     if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < p.total) return PSD_ERR_WORKSPACE;

@@ -554,12 +554,14 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 }
 
 // ------------------------------------------------------------------------------ 4-bit weights, M <= 16
-// One block per 64 output columns (four strips of the strip-major 4-bit layout) over the whole K range, eight
-// wavefronts on different K ranges, added through LDS in wavefront order; single owner per output, the same
-// epilogue as the column kernel (plain output, or residual add + gain-scaled copy + per-strip sums of squares).
-// 4-bit weights are a quarter of the bytes, so the fp32 activations a block reads from L2 weigh as much as its
-// weights already at 64 columns (and four times as much at 16): hence the wide tile.  Every wavefront keeps the
-// next K step's codes, scales and activations in flight while it multiplies the current one.
+// Grid (64-column tiles, K splits): a block takes four strips of the strip-major 4-bit layout over its share of
+// the K range, its eight wavefronts on different parts of that share, added through LDS in wavefront order; the
+// block's sums go to partial slot blockIdx.y (the consumers add the slots in order, as for every other
+// projection).  4-bit weights are a quarter of the bytes, so the fp32 activations a block reads from L2 weigh as
+// much as its weights already at 64 columns (and four times as much at 16): hence the wide tile; and what one CU
+// can keep in flight bounds a block to a few tens of GB/s, hence the K split for projections with few tiles
+// (N = d_model), so that every projection spreads over the whole chip.  Every wavefront keeps the next K step's
+// codes, scales and activations in flight while it multiplies the current one.
 // Per group of 128 K (one step): u = sum (128 + q) x on the matrix cores with the codes as exact bf16
 // integers, xs = sum x with an all-ones operand, then acc += scale * (u - (128 + zero) * xs) in fp32.
 constexpr int kW4Waves = 8, kW4Strips = 4, kW4Cols = 16 * kW4Strips;
@@ -574,7 +576,8 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
     const int K = g.K, ns = K / kSkinnyStepK;
-    const int s0 = wave * ns / kW4Waves, s1 = (wave + 1) * ns / kW4Waves;
+    const int S = g.splitk * kW4Waves, slot = blockIdx.y * kW4Waves + wave;
+    const int s0 = (int)((long)slot * ns / S), s1 = (int)((long)(slot + 1) * ns / S);
     const bool xvalid = i < g.M;
     const float *xp = g.x + x_row(g, min(i, g.M - 1)) * K + gq * 16;
     const uint8_t *wq = (const uint8_t *)g.wpack + (size_t)blockIdx.x * kW4Strips * ns * kW4StripBytes;
@@ -646,30 +649,15 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
 #pragma unroll
         for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][v];
     __syncthreads();
-    // thread t of pass p: column en = t & 15 of strip 2 p + (t >> 8), token emm = (t >> 4) & 15
+    // thread t of pass p: column t & 63 of the tile, token (t >> 6) + 8 p
 #pragma unroll
-    for (int pass = 0; pass < kW4Strips / 2; ++pass) {
-        const int en = threadIdx.x & 15, emm = (threadIdx.x >> 4) & 15, strip = 2 * pass + (threadIdx.x >> 8);
-        const int col = blockIdx.x * kW4Cols + strip * 16 + en;
-        float v = 0.f, sq = 0.f;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int cn = threadIdx.x & 63, emm = (threadIdx.x >> 6) + 8 * pass;
+        const int col = blockIdx.x * kW4Cols + cn;
+        float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < kW4Waves; ++w) v += red[w][strip * 16 + en][emm];
-        if (emm < g.M && col < g.N) {
-            const size_t o = (size_t)emm * g.N + col;
-            if (g.x_resid) {
-                v += g.x_resid[o];
-                g.x_resid[o] = v;
-                if (g.xg_out) g.xg_out[o] = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
-                sq = v * v;
-            } else {
-                g.partial[o] = v;
-            }
-        }
-        sq += __shfl_xor(sq, 8, 64);
-        sq += __shfl_xor(sq, 4, 64);
-        sq += __shfl_xor(sq, 2, 64);
-        sq += __shfl_xor(sq, 1, 64);
-        if (en == 0 && emm < g.M && g.sumsq_out) g.sumsq_out[(size_t)(blockIdx.x * kW4Strips + strip) * g.M + emm] = sq;
+        for (int w = 0; w < kW4Waves; ++w) v += red[w][cn][emm];
+        if (emm < g.M && col < g.N) g.partial[((size_t)blockIdx.y * g.M + emm) * g.N + col] = v;
     }
 }
 
@@ -873,6 +861,16 @@ void launch_gemm_pack_w4(const void *const *q, const void *const *scale, const v
     }
 }
 
+// K splits of a 4-bit projection: enough blocks to cover the chip, at least one K step per wavefront
+int gemm_w4_splits(int K, const int *n, int nseg) {
+    const int tiles = tiles_of(n, nseg, kW4Cols), ns = K / kSkinnyStepK;
+    int want = (256 + tiles - 1) / tiles, cap = ns / kW4Waves;
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want > 8) want = 8;
+    return want < 1 ? 1 : want;
+}
+
 int gemm_packed_splits(int M, int K, const int *n, int nseg) {
     const int tiles = tiles_of(n, nseg, kSkinnyRows);
     if (gemm_use_stream(tiles)) return gemm_stream_slots(tiles, K);
@@ -903,11 +901,15 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         launch_kernel(gemm_f32_kernel, (g.N + 3) / 4, 256, 0, stream, g);
         return;
     }
-    if (g.M <= kStreamMaxRows && g.wpack && (g.x_resid || g.w4)) {
+    if (g.M <= kStreamMaxRows && g.wpack && g.w4) {
+        ScopedProf sp(PSD_KIND_GEMM_W4, stream);
+        launch_kernel(gemm_w4_tile_kernel, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
+        return;
+    }
+    if (g.M <= kStreamMaxRows && g.wpack && g.x_resid) {
         ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
         const int grid = g.N / 16;                        // every segment is a multiple of 64 wide; M <= 16: one row tile
-        if (g.w4) launch_kernel(gemm_w4_tile_kernel, g.N / kW4Cols, kW4Waves * 64, 0, stream, g);
-        else launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
+        launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
         return;
     }
     if (g.M <= kStreamMaxRows && g.wpack && !g.one_slot && gemm_use_stream(g.pack_tiles)) {

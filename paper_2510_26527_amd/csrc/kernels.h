@@ -72,8 +72,7 @@ struct GemmArgs {
     const void *gain;             // [N] bf16
     float *sumsq_out;             // [N/16][M]
     // -- 4-bit weights (W4A16, groups of 128 along K): wpack holds the strip-major 4-bit layout of
-    // launch_gemm_pack_w4 and every projection runs on the one-slot column kernel (S = 1 partial, or the
-    // residual epilogue above)
+    // launch_gemm_pack_w4; the projection writes `splitk` partial slots (gemm_w4_splits)
     bool w4;
     RowScale scale;               // applied when writing `reduced` (row = the source row of m)
     int scale_rows;               //   rows per tile slab of scale.sumsq
@@ -82,6 +81,7 @@ int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg);
 // repacked weights for the M <= kStreamMaxRows path
 int gemm_pack_tiles(const int *n, int nseg);
 size_t gemm_pack_bytes(const int *n, int nseg, int K);
+int gemm_w4_splits(int K, const int *n, int nseg);             // K splits (partial slots) of a 4-bit projection
 int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots (the splitk to use) with packed weights
 bool gemm_use_stream(int tiles);
 int gemm_stream_grid(int tiles, int K);

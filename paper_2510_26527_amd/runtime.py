@@ -36,7 +36,6 @@ class Model:
         self.shape = shape
         ptrs = [self.weights[n].data_ptr() for n in weight_order(shape.n_layers)]
         self.quant = None
-        self.max_rows_per_call = None
         if quant is None:
             self.handle = psd.psd_model_create(self.desc, ptrs)
         else:
@@ -44,7 +43,6 @@ class Model:
             names = [f"l{l}.{n}" for l in range(shape.n_layers) for n in _QUANT_WEIGHTS]
             self.handle = psd.psd_model_create_w4(self.desc, ptrs, [self.quant[n][0].data_ptr() for n in names],
                                                   [self.quant[n][1].data_ptr() for n in names])
-            self.max_rows_per_call = 16
         self._ws = None
         self.packed = None
 

@@ -237,15 +237,15 @@ def test_outputs_and_scratch_stay_inside_their_buffers():
             assert bool((t[:guard] == mark).all()) and bool((t[guard + n:] == mark).all()), f"{name} guard touched ({shape}, {n_new})"
         assert bool(torch.isfinite(logits).all())
         # acceptance on these logits
-        gamma = n_new - 1
+        gamma = min(n_new - 1, 16)
         q, x = synth.make_draft_from_target(logits[:, :gamma], 0.5, 3)
         u = synth.make_uniforms((1, gamma + 1), 4, dev)
-        a_need = psd.psd_spec_accept_workspace_bytes(1, gamma, n_new, shape.vocab)
+        a_need = psd.psd_spec_accept_workspace_bytes(1, gamma, gamma + 1, shape.vocab)
         aw_all = torch.full((a_need // 4 + 2 * guard,), mark, dtype=torch.float32, device=dev)
         aw = aw_all[guard:guard + a_need // 4].view(torch.uint8)
         out_all = torch.full((3 + 2 * 64,), -777, dtype=torch.int32, device=dev)
         out = out_all[64:67]
-        psd.psd_spec_accept(logits, q, x, gamma, u, 1.0, out[0:1], out[1:2], 1, n_new, shape.vocab, psd.PSD_F32,
+        psd.psd_spec_accept(logits, q, x, gamma, u, 1.0, out[0:1], out[1:2], 1, gamma + 1, shape.vocab, psd.PSD_F32,
                             n_new * shape.vocab, gamma * shape.vocab, out[2:3], aw)
         torch.cuda.synchronize()
         assert bool((aw_all[:guard] == mark).all()) and bool((aw_all[guard + a_need // 4:] == mark).all())
@@ -356,10 +356,29 @@ def test_w4_small_models(shape, steps, ctx):
         errs.append(p.step(toks[:, at:at + n], what=f"{n} rows"))
         at += n
     print("w4 rel err", errs)
-    with pytest.raises(psd.PsdError) as e:                 # more than 16 rows per call: not built for 4-bit models
-        runtime.forward(p.model, p.kv, torch.zeros((1, 17), dtype=torch.int32, device="cuda"))
-    assert e.value.status == psd.PSD_ERR_UNIMPLEMENTED
     p.close()
+
+
+def test_w4_long_step_of_one_sequence_and_its_limit():
+    """More than 16 rows in one call: the library runs a single sequence's step as consecutive 16-row steps (same
+    function: the oracle does it in one go), logits for the trailing rows only or for all of them; a long step of
+    several sequences is refused."""
+    shape = SMALL_GQA
+    p = Pair(shape, torch.bfloat16, 1, 256, seed=77, ctx=40, std=0.05, w4=True)
+    toks = synth.make_tokens(shape.vocab, (1, 70), 5)
+    e1 = p.step(toks[:, :37], what="37 rows, all logits")
+    e2 = p.step(toks[:, 37:70], n_logit_rows=21, what="33 rows, last 21 logits (crossing a piece boundary)")
+    print("w4 long steps rel err", e1, e2)
+    assert int(p.kv.lens[0]) == 110 and psd.psd_kv_len_upper_bound(p.kv.handle) == 110
+    p.close()
+    p2 = Pair(shape, torch.bfloat16, 2, 128, seed=78, ctx=10, std=0.05, w4=True)
+    assert psd.psd_model_workspace_bytes(p2.model.handle, 2, 9, 128) == 0
+    ws = p2.model.workspace(2, 8, 128)
+    with pytest.raises(psd.PsdError) as e:
+        psd.psd_model_forward(p2.model.handle, torch.zeros((2, 9), dtype=torch.int32, device="cuda"), 9, p2.kv.handle,
+                              None, 0, ws)
+    assert e.value.status == psd.PSD_ERR_UNIMPLEMENTED
+    p2.close()
 
 
 def test_w4_batch_of_sequences():
