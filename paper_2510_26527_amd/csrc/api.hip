@@ -265,6 +265,8 @@ struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
     size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, total;
+    size_t off_xn16, off_attn16, off_h16;
+    bool half_copies;             // M > kStreamMaxRows, bf16: the producers also leave fp16 copies for the tiled projections
     bool folded;
     bool fused_rope;              // the attention kernel reduces, rotates and appends q / k / v itself
     bool qkv_one_slot;            // ... and the QKV projection then leaves one slot for it to read                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
@@ -303,6 +305,10 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.off_q = take((size_t)M * hd * act);
     p.off_attn = take((size_t)M * hd * act);
     p.off_h = take((size_t)M * d.d_ffn * act);
+    p.half_copies = d.dtype == PSD_BF16 && M > kStreamMaxRows;
+    p.off_xn16 = take(p.half_copies ? (size_t)M * d.d_model * 2 : 0);
+    p.off_attn16 = take(p.half_copies ? (size_t)M * hd * 2 : 0);
+    p.off_h16 = take(p.half_copies ? (size_t)M * d.d_ffn * 2 : 0);
     size_t part = 0;
     auto need = [&](int sk, int rows, int N) { const size_t b = (size_t)sk * rows * N * 4; if (b > part) part = b; };
     need(p.sk_qkv, M, p.width_qkv); need(p.sk_o, M, d.d_model); need(p.sk_gu, M, 2 * d.d_ffn);
@@ -403,6 +409,9 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
     float *q = (float *)(ws + p.off_q);
     float *attn = (float *)(ws + p.off_attn);
     float *h = (float *)(ws + p.off_h);
+    uint16_t *xn16 = p.half_copies ? (uint16_t *)(ws + p.off_xn16) : nullptr;
+    uint16_t *attn16 = p.half_copies ? (uint16_t *)(ws + p.off_attn16) : nullptr;
+    uint16_t *h16 = p.half_copies ? (uint16_t *)(ws + p.off_h16) : nullptr;
     float *partial = (float *)(ws + p.off_partial);
     const int M = p.M, hd = d.n_q_heads * d.d_head, kvd = d.n_kv_heads * d.d_head;
     const size_t kv_layer = (size_t)B * d.n_kv_heads * kv->max_len * d.d_head * elem_size(d.dtype);
@@ -414,6 +423,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         GemmArgs g{};
         g.wpack = rows <= kStreamMaxRows ? wpack : nullptr;
         g.x = xin; g.x_rows_per_group = rows > 0 ? rows : 1; g.x_group_stride = 0; g.x_group_offset = 0;
+        g.x16 = xin == xn ? xn16 : (xin == attn ? attn16 : (xin == h ? h16 : nullptr));
         g.w[0] = w0; g.w[1] = w1; g.w[2] = w2; g.n[0] = n0; g.n[1] = n1; g.n[2] = n2;
         g.nseg = w2 ? 3 : (w1 ? 2 : 1);
         g.M = rows; g.K = K; g.N = n0 + n1 + n2; g.partial = dst; g.splitk = sk; g.reduced = nullptr;
@@ -441,13 +451,13 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
             rs.tiles = col_tiles;
         } else {
             gemm(xin, M, K, w, d.d_model, nullptr, 0, nullptr, 0, sk, partial, wpack);
-            launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, st);
+            launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, xn16, st);
         }
     };
     RopeTable rt{};
     if (p.fused_rope) rt = RopeTable{(float2 *)(ws + p.off_rope), kv->lens, n_new, d.d_head, d.rope_theta};
     launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, p.folded ? sumsq : nullptr, M, d.d_model,
-                      d.vocab, d.rms_eps, rt, st);
+                      d.vocab, d.rms_eps, rt, xn16, st);
     rs.tiles = 1;
     for (int l = 0; l < d.n_layers; ++l) {
         gemm(act, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial,
@@ -458,7 +468,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
                                       d.n_kv_heads, d.d_head, kv->max_len, d.rope_theta, st);
         AttnArgs a{};
         if (p.fused_rope) { a.qkv_partial = partial; a.qkv_splits = p.sk_qkv; a.rs = rs; a.rope_cs = rt.cs; }
-        a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn;
+        a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn; a.out16 = attn16;
         a.B = B; a.R = n_new; a.h_q = d.n_q_heads; a.h_kv = d.n_kv_heads; a.d_h = d.d_head; a.max_len = kv->max_len;
         a.len_bound = len_bound; a.part_o = (float *)(ws + p.off_po); a.part_ml = (float *)(ws + p.off_pml);
         a.splits = p.attn_splits;
@@ -467,13 +477,13 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         resid_gemm(attn, hd, m->layer(l, W_O), p.sk_o, m->pack(l, P_O), m->layer(l, W_FFN_NORM));
         gemm(act, M, d.d_model, m->layer(l, W_GATE), d.d_ffn, m->layer(l, W_UP), d.d_ffn, nullptr, 0, p.sk_gu, partial,
              m->pack(l, P_GU));
-        launch_reduce_swiglu(partial, p.sk_gu, rs, h, M, d.d_ffn, st);
+        launch_reduce_swiglu(partial, p.sk_gu, rs, h, M, d.d_ffn, h16, st);
         resid_gemm(h, d.d_ffn, m->layer(l, W_DOWN), p.sk_down, m->pack(l, P_DOWN), norm_gain(l + 1));
     }
     if (n_logit_rows > 0) {
         // lm_head on the last n_logit_rows rows of every sequence (unfolded: xn already holds the final norm)
         GemmArgs hg{};
-        hg.x = act; hg.x_rows_per_group = n_logit_rows; hg.x_group_stride = n_new; hg.x_group_offset = n_new - n_logit_rows;
+        hg.x = act; hg.x16 = xn16; hg.x_rows_per_group = n_logit_rows; hg.x_group_stride = n_new; hg.x_group_offset = n_new - n_logit_rows;
         hg.w[0] = m->lm_head(); hg.n[0] = d.vocab; hg.nseg = 1;
         hg.M = B * n_logit_rows; hg.K = d.d_model; hg.N = d.vocab;
         hg.wpack = hg.M <= kStreamMaxRows ? m->pack_head() : nullptr;

@@ -501,6 +501,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         }
         if (a.splits == 1) {
             a.out[row * DH + d] = acc / L;
+            if (a.out16) a.out16[row * DH + d] = f32_to_f16_bits(acc / L);
         } else {
             a.part_o[(row * a.splits + split) * DH + d] = acc;
             if (d == 0) {
@@ -709,7 +710,14 @@ __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float s
             const float inv = 1.0f / L;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
-                *reinterpret_cast<f32x4 *>(a.out + out_row[qt] * DH + dt * 16 + 4 * g) = o[qt][dt] * inv;
+            {
+                const f32x4 r = o[qt][dt] * inv;
+                *reinterpret_cast<f32x4 *>(a.out + out_row[qt] * DH + dt * 16 + 4 * g) = r;
+                if (a.out16)
+                    *reinterpret_cast<uint2 *>(a.out16 + out_row[qt] * DH + dt * 16 + 4 * g) =
+                        make_uint2(f32_to_f16_bits(r[0]) | ((uint32_t)f32_to_f16_bits(r[1]) << 16),
+                                   f32_to_f16_bits(r[2]) | ((uint32_t)f32_to_f16_bits(r[3]) << 16));
+            }
         } else {
             float *po = a.part_o + (out_row[qt] * a.splits + split) * DH;
 #pragma unroll
@@ -738,6 +746,7 @@ __global__ void attn_combine_kernel(AttnArgs a) {
         acc += a.part_o[(row * a.splits + s) * DH + d] * f;
     }
     a.out[row * DH + d] = acc / L;
+    if (a.out16) a.out16[row * DH + d] = f32_to_f16_bits(acc / L);
 }
 
 // query tiles of 16 per block: bounded by registers (hi+lo query operands and fp32 outputs)

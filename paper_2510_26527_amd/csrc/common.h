@@ -41,6 +41,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// round-to-nearest-even fp32 -> fp16 bit pattern
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+    const _Float16 h = (_Float16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
 // element loads / stores by storage type
 __device__ __forceinline__ float load_elem(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_elem(const uint16_t *p, size_t i) { return bf16_bits_to_f32(p[i]); }

@@ -18,7 +18,8 @@
 //   gemm_w4_tile_kernel      M <= 16, 4-bit weight-only quantised projections (groups of 128 along K): one
 //                            block per 32 output columns, the codes multiplied as exact bf16 integers, scale
 //                            and zero point applied per group in fp32, the same epilogue.
-//   gemm_bf16_tiled_kernel   M > 16.  128 x (128..224) x 64 LDS-staged tiles, 32x32x16 bf16 MFMA.
+//   gemm_f16_tiled_kernel    M > 16.  128 x (128, 192, 256) x 64 LDS-staged tiles, 32x32x16 fp16 MFMA (weights convert to
+//                            fp16 exactly, activations are rounded to fp16).
 // Activations are fp32 in memory in every case.  The bf16 kernels feed each activation to the
 // matrix cores as a pair of bf16 values hi + lo (two MFMAs against the same weight operand):
 // with plain bf16 activations the logits of the 7B-shaped random-init models are 3e-2 off the
@@ -661,81 +662,106 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
     }
 }
 
-// ------------------------------------------------------------------------------ bf16 tiled
-// Block tile 128 rows of activations x 32*NB rows of W x 64 of K; four wavefronts, each on 32 activation rows
-// x the whole tile width (1 x NB tiles of the 32x32x16 MFMA).  The activation tile is staged in LDS twice (hi
-// and lo bf16 parts): per 16-wide K step a wavefront reads 2 + NB operands for 2 NB MFMAs.  Rows are padded to
-// 72 elements (144 B): conflict-free 16-byte reads.  LDS is dynamic (at most 73.7 KB per block), two blocks
-// per CU: one block's staging and barriers overlap the other's MFMAs.
-// The tile width NB (4..8) and the K split are chosen per projection by the host so that the number of blocks
-// comes close to a multiple of the 512 block slots: with a fixed 256-wide tile the gate|up projection of a 7B
-// model at M = 256 has 296 blocks and leaves 42 % of the CUs idle.
-constexpr int kBM = 128, kBK = 64, kLdsStride = 72, kMaxNB = 8;
-constexpr size_t kTiledLds = (size_t)(2 * kBM + 32 * kMaxNB) * kLdsStride * sizeof(uint16_t);
+// ------------------------------------------------------------------------------ tiled (M > 16)
+// Block tile 128 or 256 rows of activations x 32*NB rows of W x 64 of K (NB = 4, 6, 8); wavefronts in a 2 x 2 or
+// 4 x 2 grid, each on 64 activation rows x 16*NB weight rows: 2 x NB/2 tiles of the 32x32x16 MFMA, so that per 16-wide K step
+// a wavefront reads 2 + NB/2 operands from LDS for NB MFMAs (with 1 x NB tiles per wavefront it would be 1 + NB
+// operands, and LDS reads, not the matrix cores, would set the pace).
+// Both operands enter the matrix cores as fp16, one product each: the bf16 weights convert to fp16 exactly
+// (8 significant bits into 11; only magnitudes below 7.6e-6 fall under the fp16 grid and are rounded to it, by at
+// most 3e-8), the fp32 activations are rounded to fp16 (11 significant bits, the error of bf16 divided by 8),
+// which keeps the logits of the 7B-shaped models within 2e-2 of the fp64 result at half the MFMA issue of a
+// bf16 high + low pair.  Activations beyond +-65504 would overflow; none of the decoder's normalised or gated
+// activations come near.  Rows are padded to 72 elements (144 B): conflict-free 16-byte reads.  LDS is dynamic,
+// two blocks per CU: one block's staging and barriers overlap the other's MFMAs.
+// The tile width and the K split are chosen per projection by the host so that the number of blocks comes
+// close to a multiple of the 512 block slots.
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+constexpr int kBK = 64, kLdsStride = 72, kMaxNB = 8;
+constexpr int kTallRows = 160;                           // from this many rows on: 256-row blocks
+constexpr size_t kTiledLds = (size_t)(256 + 32 * kMaxNB) * kLdsStride * sizeof(uint16_t);
+inline int tiled_block_rows(int M) { return M >= kTallRows ? 256 : 128; }
 
-template <int NB>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
-    constexpr int BN = 32 * NB;
-    constexpr int WCH = BN * 8 / 256;                       // 16-byte chunks of the W tile per thread (BN x 64 bf16)
+// 8 bf16 (as stored) -> 8 fp16, exact for every value the fp16 grid holds
+__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[e] << 16), __uint_as_float(w[e] & 0xffff0000u));
+        r[e] = __builtin_bit_cast(uint32_t, h);
+    }
+    return r;
+}
+// 8 fp32 -> 8 fp16, round to nearest even
+__device__ __forceinline__ u32x4 f32x8_to_f16x8(const f32x8 &x) {
+    const f16x8 h = __builtin_convertvector(x, f16x8);
+    return __builtin_bit_cast(u32x4, h);
+}
+
+// MW = wavefront rows of the block: 2 (128 activation rows, 256 threads, two blocks per CU) or 4 (256 rows, 512
+// threads, one block per CU: each weight tile then leaves L2 once for 256 rows instead of twice).
+template <int NB, int MW>
+__global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kernel(GemmArgs g) {
+    constexpr int BM = 64 * MW, BN = 32 * NB, NH = NB / 2, NT = MW * 128;
+    constexpr int XCH = BM * 8 / NT;                        // 16-byte chunks of the fp16 X tile per thread (BM x 64)
+    constexpr int WCH = BN * 8 / NT;                        // 16-byte chunks of the W tile per thread (BN x 64 bf16)
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_tiled[];
-    uint16_t *Xh = lds_tiled;                               // activation tile, hi parts
-    uint16_t *Xl = Xh + kBM * kLdsStride;                   // activation tile, lo parts
-    uint16_t *Ws = Xl + kBM * kLdsStride;
+    uint16_t *Xs = lds_tiled;                               // activation tile, fp16
+    uint16_t *Ws = Xs + BM * kLdsStride;                    // weight tile, fp16
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
-    const int m_tiles = (g.M + kBM - 1) / kBM;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * (BN / 2);   // this wavefront's corner of the block tile
+    const int m_tiles = (g.M + BM - 1) / BM;
     const int mt = blockIdx.x % m_tiles;                 // M tiles of one W tile are neighbours: W is re-read from L2
     const TileRef t = find_tile(g, blockIdx.x / m_tiles, BN);
     const int seg_rows = g.n[t.seg];
     const uint16_t *W = (const uint16_t *)g.w[t.seg];
-    const float *X = (const float *)g.x;
     const int K = g.K;
     const int nk = K / kBK;
     const int k0 = (int)((long)blockIdx.y * nk / g.splitk), k1 = (int)((long)(blockIdx.y + 1) * nk / g.splitk);
-    const int m_base = mt * kBM;
-    const int wm = wave * 32;                             // this wavefront's 32 activation rows
+    const int m_base = mt * BM;
 
-    // global -> register staging per K tile: 4 x 8 fp32 of X and NB x 8 bf16 of W per thread
-    const float *xg[4];
-    const uint16_t *wg[WCH];
-    int xoff[4], woff[WCH];
+    // global -> register staging per K tile: XCH x 8 activations (fp16 copy if there is one, else fp32 rounded
+    // here) and WCH x 8 bf16 of W per thread
+    uint32_t xsrc[XCH], wsrc[WCH];                       // element offsets from the matrices' first elements
+    int xoff[XCH], woff[WCH];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
-        xg[c] = X + x_row(g, min(m_base + row, g.M - 1)) * K + col;
+    for (int c = 0; c < XCH; ++c) {
+        const int chunk = tid + c * NT, row = chunk >> 3, col = (chunk & 7) * 8;
+        xsrc[c] = (uint32_t)(x_row(g, min(m_base + row, g.M - 1)) * K + col);
         xoff[c] = row * kLdsStride + col;
     }
 #pragma unroll
     for (int c = 0; c < WCH; ++c) {
-        const int chunk = tid + c * 256, row = chunk >> 3, col = (chunk & 7) * 8;
-        wg[c] = W + (size_t)min(t.row0 + row, seg_rows - 1) * K + col;
+        const int chunk = tid + c * NT, row = chunk >> 3, col = (chunk & 7) * 8;
+        wsrc[c] = (uint32_t)((size_t)min(t.row0 + row, seg_rows - 1) * K + col);
         woff[c] = row * kLdsStride + col;
     }
-    f32x8 xr[4];
-    u32x4 wr[WCH];
+    const bool have16 = g.x16 != nullptr;
+    u32x4 xr[XCH], wr[WCH];
     auto load_tiles = [&](int kt) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) xr[c] = load_f32x8(xg[c] + (size_t)kt * kBK);
+        for (int c = 0; c < XCH; ++c) {
+            if (have16) xr[c] = *reinterpret_cast<const u32x4 *>(g.x16 + xsrc[c] + kt * kBK);
+            else xr[c] = f32x8_to_f16x8(load_f32x8(g.x + xsrc[c] + kt * kBK));
+        }
 #pragma unroll
-        for (int c = 0; c < WCH; ++c) wr[c] = *reinterpret_cast<const u32x4 *>(wg[c] + (size_t)kt * kBK);
+        for (int c = 0; c < WCH; ++c) wr[c] = *reinterpret_cast<const u32x4 *>(W + wsrc[c] + kt * kBK);
     };
     auto store_tiles = [&]() {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            bf16x8 hi, lo;
-            split_bf16(xr[c], &hi, &lo);
-            *reinterpret_cast<bf16x8 *>(&Xh[xoff[c]]) = hi;
-            *reinterpret_cast<bf16x8 *>(&Xl[xoff[c]]) = lo;
-        }
+        for (int c = 0; c < XCH; ++c) *reinterpret_cast<u32x4 *>(&Xs[xoff[c]]) = xr[c];
 #pragma unroll
-        for (int c = 0; c < WCH; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = wr[c];
+        for (int c = 0; c < WCH; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = bf16x8_to_f16x8(wr[c]);
     };
 
-    f32x16 acc[NB];
+    f32x16 acc[2][NH];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+        for (int b = 0; b < NH; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     if (k0 < k1) {
         load_tiles(k0);
@@ -743,34 +769,38 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(GemmArgs g) {
     }
     __syncthreads();
     for (int kt = k0; kt < k1; ++kt) {
-        if (kt + 1 < k1) load_tiles(kt + 1);
+        if (kt + 1 < k1) load_tiles(kt + 1);             // in flight while this tile is multiplied
 #pragma unroll
         for (int ks = 0; ks < kBK / 16; ++ks) {
-            const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(&Xh[(wm + li) * kLdsStride + ks * 16 + lg * 8]);
-            const bf16x8 fl = *reinterpret_cast<const bf16x8 *>(&Xl[(wm + li) * kLdsStride + ks * 16 + lg * 8]);
-            bf16x8 fb[NB];
+            f16x8 fa[2], fb[NH];
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                fb[b] = *reinterpret_cast<const bf16x8 *>(&Ws[(b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
+            for (int a = 0; a < 2; ++a)
+                fa[a] = *reinterpret_cast<const f16x8 *>(&Xs[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[b], acc[b], 0, 0, 0);
+            for (int b = 0; b < NH; ++b)
+                fb[b] = *reinterpret_cast<const f16x8 *>(&Ws[(wn + b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[b], acc[b], 0, 0, 0);
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < NH; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
         __syncthreads();
         if (kt + 1 < k1) store_tiles();
         __syncthreads();
     }
-    // acc[b][v] = y[m_base + wm + 8*(v/4) + 4*lg + v%4][row0 + b*32 + li]
+    // acc[a][b][v] = y[m_base + wm + a*32 + 8*(v/4) + 4*lg + v%4][row0 + wn + b*32 + li]
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int row = t.row0 + b * 32 + li;
+    for (int b = 0; b < NH; ++b) {
+        const int row = t.row0 + wn + b * 32 + li;
         if (row >= seg_rows) continue;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = m_base + wm + 8 * (v >> 2) + 4 * lg + (v & 3);
-            if (m < g.M) store_out(g, blockIdx.y, m, t.col0 + row, acc[b][v]);
-        }
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m_base + wm + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                if (m < g.M) store_out(g, blockIdx.y, m, t.col0 + row, acc[a][b][v]);
+            }
     }
 }
 
@@ -787,22 +817,25 @@ int tiles_of(const int *n, int nseg, int rows) {
 // through LDS, and over blocks (gemm_bf16_skinny_kernel), which keeps the partial slots few.
 bool gemm_use_stream(int tiles) { return tiles >= 128; }
 
-// Tile width (NB x 32 columns) and K split of the tiled kernel: the pair with the least estimated time: rounds
-// of 512 resident blocks x K tiles per block x the MFMA time of one K tile of two co-resident blocks (512 NB
-// cycles at the 45 % issue rate the kernel reaches), plus writing and re-reading one fp32 partial slot of
+// Tile width (NB x 32 columns, NB = 4, 6, 8) and K split of the tiled kernel: the pair with the least estimated
+// time: rounds of 512 resident blocks x K tiles per block x the time of one K tile of two co-resident blocks,
+// which the LDS traffic sets (16 KB of activations and 4 NB KB of weights written, 4 (2 + NB/2) x 4 KB read, at
+// 128 B per clock, with a margin for what does not overlap), plus writing and re-reading one fp32 partial slot of
 // M x N per split at about 3 TB/s.
 static void tiled_choice(int M, int K, const int *n, int nseg, int *nb_out, int *sk_out) {
-    const int nk = K / kBK, m_tiles = (M + kBM - 1) / kBM;
+    const int bm = tiled_block_rows(M), nk = K / kBK, m_tiles = (M + bm - 1) / bm;
+    const int slots = bm == 256 ? 256 : 512;          // resident blocks: one 512-thread or two 256-thread blocks per CU
     long N = 0;
     for (int s = 0; s < nseg; ++s) N += n[s];
     const double slot_us = 2.0 * (double)M * (double)N * 4.0 / 3.0e6;
     double best = 1e300;
-    *nb_out = 5; *sk_out = 1;
-    for (int nb = 4; nb < kMaxNB; ++nb)               // the 256-wide tile runs out of registers: measured 2x slower
+    *nb_out = 6; *sk_out = 1;
+    for (int nb = 4; nb <= kMaxNB; nb += 2)
         for (int sk = 1; sk <= 16 && (sk == 1 || nk / sk >= 4); ++sk) {
             const long blocks = (long)tiles_of(n, nseg, 32 * nb) * m_tiles * sk;
-            const long rounds = (blocks + 511) / 512;
-            const double cost = rounds * (double)((nk + sk - 1) / sk) * 512.0 * nb / 2400.0 / 0.45 + sk * slot_us;
+            const long rounds = (blocks + slots - 1) / slots;
+            const double tile_clk = (48.0 + 12.0 * nb) * 8.0 * 1.3;     // per 128 rows
+            const double cost = rounds * (double)((nk + sk - 1) / sk) * 2.0 * tile_clk / 2400.0 + sk * slot_us;
             if (cost < best) { best = cost; *nb_out = nb; *sk_out = sk; }
         }
 }
@@ -928,20 +961,25 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         int nb, sk;
         tiled_choice(g.M, g.K, g.n, g.nseg, &nb, &sk);
-        if (sk != g.splitk) nb = 5;                       // the caller sized the partial slots for its own split
-        dim3 grid(tiles_of(g.n, g.nseg, 32 * nb) * ((g.M + kBM - 1) / kBM), g.splitk);
+        if (sk != g.splitk) nb = 6;                       // the caller sized the partial slots for its own split
+        const int bm = tiled_block_rows(g.M);
+        dim3 grid(tiles_of(g.n, g.nseg, 32 * nb) * ((g.M + bm - 1) / bm), g.splitk);
         auto go = [&](auto kernel) {
             // opt in to more than 64 KB of dynamic LDS: a property of the function on the current device, set before
             // every launch (a cheap host call) so that no process-wide flag has to remember who set it where
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)kTiledLds);
-            launch_kernel(kernel, grid, 256, kTiledLds, stream, g);
+            launch_kernel(kernel, grid, bm * 2, kTiledLds, stream, g);
         };
-        if (nb == 4) go(gemm_bf16_tiled_kernel<4>);
-        else if (nb == 5) go(gemm_bf16_tiled_kernel<5>);
-        else if (nb == 6) go(gemm_bf16_tiled_kernel<6>);
-        else if (nb == 7) go(gemm_bf16_tiled_kernel<7>);
-        else go(gemm_bf16_tiled_kernel<8>);
+        if (bm == 256) {
+            if (nb == 4) go(gemm_f16_tiled_kernel<4, 4>);
+            else if (nb == 6) go(gemm_f16_tiled_kernel<6, 4>);
+            else go(gemm_f16_tiled_kernel<8, 4>);
+        } else {
+            if (nb == 4) go(gemm_f16_tiled_kernel<4, 2>);
+            else if (nb == 6) go(gemm_f16_tiled_kernel<6, 2>);
+            else go(gemm_f16_tiled_kernel<8, 2>);
+        }
     }
     if (g.reduced) {
         const dim3 grid((unsigned)((g.N + 255) / 256), (unsigned)g.M);

@@ -49,6 +49,7 @@ struct RowScale {
 struct GemmArgs {
     const float *x;               // fp32 activations, K contiguous; row m is read from source row
                                   //   (m / x_rows_per_group) * x_group_stride + x_group_offset + m % x_rows_per_group
+    const uint16_t *x16;          // optional: the same matrix already rounded to fp16 (what the tiled kernel multiplies)
     int x_rows_per_group, x_group_stride, x_group_offset;
     const void *w[3];
     int n[3];
@@ -102,6 +103,7 @@ struct AttnArgs {
     const void *v;                // this layer's V cache [B][h_kv][d_h][max_len]
     const int32_t *lens;          // [B] valid positions BEFORE this forward
     float *out;                   // [B][R][h_q*d_h] fp32
+    uint16_t *out16;              // optional copy of `out` rounded to fp16 (the operand of the tiled O projection)
     int B, R, h_q, h_kv, d_h, max_len;
     int len_bound;                // host upper bound of lens[b] + R
     float *part_o;                // split scratch [B][h_q][R][splits][d_h]
@@ -135,17 +137,17 @@ struct RopeTable {
 };
 // x = embed[token]; then xn = rmsnorm(x) * gain, or (sumsq_out non-NULL) xn = x * gain and sumsq_out[m] = sum_k x[m][k]^2
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, hipStream_t stream);
+                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, uint16_t *xn16, hipStream_t stream);
 // qkv = sum over splits of partial [S][M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended
 // to the cache (model dtype)
 void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,
                                void *v_cache, const int32_t *lens, int B, int R, int h_q, int h_kv, int d_h,
                                int max_len, float theta, hipStream_t stream);
-// x += sum over splits of partial [S][M][d]; xn = rmsnorm(x) * gain
+// x += sum over splits of partial [S][M][d]; xn = rmsnorm(x) * gain (xn16, if given: the same rounded to fp16)
 void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
-                                 int M, int d, float eps, hipStream_t stream);
+                                 int M, int d, float eps, uint16_t *xn16, hipStream_t stream);
 // h = silu(g) * u with [g | u] = sum over splits of partial [S][M][2f]
-void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, hipStream_t stream);
+void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, uint16_t *h16, hipStream_t stream);
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream);
 void launch_truncate(int32_t *lens, const int32_t *base, const int32_t *keep, int offset, int cap, int B,
                      hipStream_t stream);

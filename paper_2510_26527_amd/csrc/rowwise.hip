@@ -37,7 +37,7 @@ template <typename TW, bool EMBED>
 __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *embed, const int32_t *tokens, int vocab,
                                                                     const float *partial, int S, size_t split_stride,
                                                                     float *x, const TW *gain, float *xn, float *sumsq_out,
-                                                                    int d, float eps, RopeTable rt) {
+                                                                    int d, float eps, RopeTable rt, uint16_t *xn16) {
     __shared__ float red[4];
     const int m = blockIdx.x, tid = threadIdx.x, n4 = d >> 2;
     if constexpr (EMBED) {
@@ -117,7 +117,14 @@ __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *em
 #pragma unroll
     for (int j = 0; j < kMaxV4; ++j) {
         const int i4 = tid + j * kRowThreads;
-        if (i4 < n4) orow[i4] = v[j] * scale * load_gain4(gain, i4);
+        if (i4 < n4) {
+            const f32x4 r = v[j] * scale * load_gain4(gain, i4);
+            orow[i4] = r;
+            if (xn16)              // the same row rounded to fp16: the operand of the tiled projections
+                reinterpret_cast<uint2 *>(xn16 + (size_t)m * d)[i4] =
+                    make_uint2(f32_to_f16_bits(r[0]) | ((uint32_t)f32_to_f16_bits(r[1]) << 16),
+                               f32_to_f16_bits(r[2]) | ((uint32_t)f32_to_f16_bits(r[3]) << 16));
+        }
     }
 }
 
@@ -185,7 +192,7 @@ __global__ __launch_bounds__(64) void reduce_rope_append_kernel(const float *par
 // h = silu(g) * u, four columns per thread, one row per blockIdx.y; [g | u] arrive as split-K partials of
 // the gate|up projection
 __global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float *partial, int S, size_t split_stride, RowScale rs,
-                                                            float *h, int M, int f) {
+                                                            float *h, int M, int f, uint16_t *h16) {
     __shared__ float red[4];
     const int m = blockIdx.y, f4 = f >> 2;
     float ssq = 0.f;
@@ -207,6 +214,10 @@ __global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float *partial
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
     reinterpret_cast<f32x4 *>(h + (size_t)m * f)[j4] = o;
+    if (h16)
+        reinterpret_cast<uint2 *>(h16 + (size_t)m * f)[j4] =
+            make_uint2(f32_to_f16_bits(o[0]) | ((uint32_t)f32_to_f16_bits(o[1]) << 16),
+                       f32_to_f16_bits(o[2]) | ((uint32_t)f32_to_f16_bits(o[3]) << 16));
 }
 
 __global__ void advance_lens_kernel(int32_t *lens, int B, int delta, int max_len) {
@@ -227,26 +238,26 @@ __global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
 }  // namespace
 
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, hipStream_t stream) {
+                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, uint16_t *xn16, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_EMBED, stream);
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, true>, M, kRowThreads, 0, stream, (const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
-                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps, rt);
+                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps, rt, xn16);
     else
         launch_kernel(residual_norm_kernel<float, true>, M, kRowThreads, 0, stream, (const float *)embed, tokens, vocab, nullptr, 0, 0, x,
-                                                                        (const float *)gain, xn, sumsq_out, d, eps, rt);
+                                                                        (const float *)gain, xn, sumsq_out, d, eps, rt, xn16);
 }
 
 void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
-                                 int M, int d, float eps, hipStream_t stream) {
+                                 int M, int d, float eps, uint16_t *xn16, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_RMSNORM, stream);
     const size_t stride = (size_t)M * d;
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                            (const uint16_t *)gain, xn, nullptr, d, eps, RopeTable{});
+                                                                            (const uint16_t *)gain, xn, nullptr, d, eps, RopeTable{}, xn16);
     else
         launch_kernel(residual_norm_kernel<float, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                         (const float *)gain, xn, nullptr, d, eps, RopeTable{});
+                                                                         (const float *)gain, xn, nullptr, d, eps, RopeTable{}, xn16);
 }
 
 void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,
@@ -263,10 +274,10 @@ void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale 
                                                                   lens, R, h_q, h_kv, d_h, max_len, theta);
 }
 
-void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, hipStream_t stream) {
+void launch_reduce_swiglu(const float *partial, int S, RowScale rs, float *h, int M, int f, uint16_t *h16, hipStream_t stream) {
     ScopedProf sp(PSD_KIND_SWIGLU, stream);
     const dim3 grid((unsigned)((f / 4 + 255) / 256), (unsigned)M);
-    launch_kernel(reduce_swiglu_kernel, grid, 256, 0, stream, partial, S, (size_t)M * 2 * f, rs, h, M, f);
+    launch_kernel(reduce_swiglu_kernel, grid, 256, 0, stream, partial, S, (size_t)M * 2 * f, rs, h, M, f, h16);
 }
 
 void launch_advance_lens(int32_t *lens, int B, int delta, int max_len, hipStream_t stream) {
