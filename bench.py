@@ -30,11 +30,16 @@ def weight_stream_bytes(shape):
 
 
 def stream_kernel_bytes(shape):
-    """The share of weight_stream_bytes read by gemm_bf16_stream_kernel: the QKV, gate|up and lm_head
-    projections (the O and down projections run on the one-slot column kernel)."""
+    """The share of weight_stream_bytes read by gemm_bf16_stream_kernel: the gate|up and lm_head projections
+    (QKV runs on the one-slot 16-column kernel, the O and down projections on the column kernel)."""
     s = shape
-    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
-    return 2 * (s.n_layers * (s.d_model * (hd + 2 * kvd) + 2 * s.d_model * s.d_ffn) + s.vocab * s.d_model)
+    return 2 * (s.n_layers * 2 * s.d_model * s.d_ffn + s.vocab * s.d_model)
+
+
+def slot_kernel_bytes(shape):
+    """The QKV projections' weights: read by gemm_bf16_skinny_kernel into one partial slot."""
+    s = shape
+    return 2 * s.n_layers * s.d_model * (s.n_q_heads + 2 * s.n_kv_heads) * s.d_head
 
 
 def measured_traffic_bytes():
@@ -232,7 +237,7 @@ def main():
     ceilings = measure_ceilings(dev, quick=True)
 
     # same steps again with every launch bracketed by HIP events on its stream
-    launches_per_step = 40 * shape.n_layers + 64
+    launches_per_step = 40 * shape.n_layers + 64          # room in the event buffer: more than any path launches
     prof_steps = min(args.steps, 20)
     psd.psd_profile_enable(launches_per_step * prof_steps)
     for _ in range(prof_steps):
@@ -241,7 +246,8 @@ def main():
     psd.psd_profile_enable(0)
     kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * ms / c, "ms_per_step": ms / prof_steps}
                for k, (ms, c) in prof.items() if c}
-    # dominant kernel: gemm_bf16_stream_kernel (QKV, gate|up and lm_head projections: 65 launches per step)
+    # dominant kernel: gemm_bf16_stream_kernel (gate|up and lm_head projections: 33 launches per step, 56 % of the
+    # step's bytes); the QKV projection (one-slot kernel) and the O / down projections (column kernel) beside it
     sk_ms, sk_n = prof["gemm_skinny"]
     w_bytes = weight_stream_bytes(shape)
     stream_bytes = stream_kernel_bytes(shape)
@@ -252,14 +258,19 @@ def main():
                 "launches_per_step": sk_n / prof_steps,
                 "measured_stream_read_GB/s": ceilings["stream_read_GB/s"],
                 "frac_of_measured_stream_read": achieved / ceilings["stream_read_GB/s"]}
-    if "gemm_column" in prof and prof["gemm_column"][1]:
-        c_ms, c_n = prof["gemm_column"]
-        c_bytes = w_bytes - stream_bytes
-        roofline["other_gemm"] = {"kernel": "gemm_bf16_column_kernel (O and down projections with the residual add)",
-                                  "achieved": c_bytes * prof_steps / (c_ms * 1e-3) / 1e9, "unit": "GB/s",
-                                  "bytes_per_launch": c_bytes * prof_steps / c_n, "avg_launch_us": 1e3 * c_ms / c_n,
-                                  "launches_per_step": c_n / prof_steps}
-        roofline["all_weight_streaming_GB/s"] = w_bytes * prof_steps / ((sk_ms + c_ms) * 1e-3) / 1e9
+    gemm_ms = sk_ms
+    others = (("gemm_slot", "gemm_bf16_skinny_kernel (QKV projection into one partial slot)", slot_kernel_bytes(shape)),
+              ("gemm_column", "gemm_bf16_column_kernel (O and down projections with the residual add)",
+               w_bytes - stream_bytes - slot_kernel_bytes(shape)))
+    roofline["other_gemms"] = []
+    for kind, label, nbytes in others:
+        if kind in prof and prof[kind][1]:
+            k_ms, k_n = prof[kind]
+            gemm_ms += k_ms
+            roofline["other_gemms"].append({"kernel": label, "achieved": nbytes * prof_steps / (k_ms * 1e-3) / 1e9,
+                                            "unit": "GB/s", "bytes_per_launch": nbytes * prof_steps / k_n,
+                                            "avg_launch_us": 1e3 * k_ms / k_n, "launches_per_step": k_n / prof_steps})
+    roofline["all_weight_streaming_GB/s"] = w_bytes * prof_steps / (gemm_ms * 1e-3) / 1e9
     kv_bytes = 2 * shape.n_layers * shape.n_kv_heads * (ctx + gamma) * shape.d_head * 2
     step_floor_ms = (w_bytes + kv_bytes) / (HBM_PEAK_GBS * 1e9) * 1e3
     a_ms, a_n = prof["attn"]
@@ -447,9 +458,9 @@ def stress_workload(args, dev):
                                "4096-token N(0,1) caches, forward + per-sequence acceptance + KV rollback",
                    "gamma": gamma, "n_new": gamma, "kv_len": ctx, "batch": B, "temperature": 1.0},
         "accepted_mean": float(out["n"].float().mean().item()),
-        "roofline": {"kernel": "gemm_bf16_tiled_kernel", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+        "roofline": {"kernel": "gemm_f16_tiled_kernel", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": tf / 2500.0, "traffic": None, "flop_per_step": flops, "ms_per_step": g_ms,
-                     "note": "useful flops; activations enter as bf16 hi + lo pairs, so twice as many MFMAs are issued"},
+                     "note": "bf16 weights and fp16-rounded activations multiplied by 32x32x16 f16 MFMAs, fp32 accumulation; one MFMA pass"},
         "attention": {"kernel": "attn_mfma_wide_kernel", "bytes_per_step": kv_bytes, "ms_per_step": a_ms,
                       "GB/s": kv_bytes / (a_ms * 1e-3) / 1e9},
         "cpu_baseline": cpu_baseline, "kernels": kernels,
@@ -582,7 +593,7 @@ def sweep_workload(args, dev):
         torch.cuda.synchronize()
         prof = psd.psd_profile_collect()
         psd.psd_profile_enable(0)
-        g_ms = sum(prof[k][0] for k in ("gemm_skinny", "gemm_column", "gemm_tiled")) / reps
+        g_ms = sum(prof[k][0] for k in ("gemm_skinny", "gemm_slot", "gemm_column", "gemm_tiled") if k in prof) / reps
         flops = 2.0 * M * params
         rows.append({"M": M, "gemm_ms": g_ms, "TFLOP/s": flops / (g_ms * 1e-3) / 1e12,
                      "frac_of_bf16_mfma_peak": flops / (g_ms * 1e-3) / 2.5e15,

@@ -58,7 +58,8 @@ _SIGNATURES = {
 }
 
 PSD_KIND_NAMES = ("embed", "rmsnorm", "gemm_f32", "gemm_skinny", "gemm_tiled", "gemm_reduce", "rope_append", "attn",
-                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_draw", "accept_locate", "gemm_column", "gemm_w4")
+                  "attn_combine", "swiglu", "lens", "accept_stats", "accept_draw", "accept_locate", "gemm_column", "gemm_w4",
+                  "gemm_slot")
 
 _lib = None
 

@@ -950,7 +950,7 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         const int grid = gemm_stream_grid(g.pack_tiles, g.K);
         launch_kernel(gemm_bf16_stream_kernel<1>, grid, 256, 0, stream, g);
     } else if (g.M <= kStreamMaxRows) {
-        ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
+        ScopedProf sp(PSD_KIND_GEMM_SLOT, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
         if (g.wpack) {
             launch_kernel(gemm_bf16_skinny_kernel<1, true>, grid, 256, 0, stream, g);
