@@ -30,25 +30,20 @@ def weight_stream_bytes(shape):
 
 
 def stream_kernel_bytes(shape):
-    """The share of weight_stream_bytes read by gemm_bf16_stream_kernel: the gate|up and lm_head projections
-    (QKV runs on the one-slot 16-column kernel, the O and down projections on the column kernel)."""
+    """The share of weight_stream_bytes read by gemm_bf16_unit_kernel: the QKV, gate|up and lm_head
+    projections (the O and down projections run on the one-slot column kernel)."""
     s = shape
-    return 2 * (s.n_layers * 2 * s.d_model * s.d_ffn + s.vocab * s.d_model)
-
-
-def slot_kernel_bytes(shape):
-    """The QKV projections' weights: read by gemm_bf16_skinny_kernel into one partial slot."""
-    s = shape
-    return 2 * s.n_layers * s.d_model * (s.n_q_heads + 2 * s.n_kv_heads) * s.d_head
+    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
+    return 2 * (s.n_layers * (s.d_model * (hd + 2 * kvd) + 2 * s.d_model * s.d_ffn) + s.vocab * s.d_model)
 
 
 def measured_traffic_bytes():
-    """HBM bytes per launch of gemm_bf16_stream_kernel as measured with rocprofv3 --pmc FETCH_SIZE /
+    """HBM bytes per launch of gemm_bf16_unit_kernel as measured with rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE (the committed summary under profiles/ records the commands); None if it is not there."""
     path = os.path.join(ROOT, "profiles", "bench_verify_step_llama2_7b_hbm_traffic.txt")
     try:
         for line in open(path):
-            if line.startswith("TRAFFIC_MB_PER_LAUNCH gemm_bf16_stream_kernel"):
+            if line.startswith("TRAFFIC_MB_PER_LAUNCH gemm_bf16_unit_kernel"):
                 return float(line.split("=")[1]) * 1e6
     except OSError:
         pass
@@ -246,22 +241,21 @@ def main():
     psd.psd_profile_enable(0)
     kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * ms / c, "ms_per_step": ms / prof_steps}
                for k, (ms, c) in prof.items() if c}
-    # dominant kernel: gemm_bf16_stream_kernel (gate|up and lm_head projections: 33 launches per step, 56 % of the
-    # step's bytes); the QKV projection (one-slot kernel) and the O / down projections (column kernel) beside it
+    # dominant kernel: gemm_bf16_unit_kernel (QKV, gate|up and lm_head projections: 65 launches per step, 82 % of the
+    # step's bytes); the O / down projections (column kernel) beside it
     sk_ms, sk_n = prof["gemm_skinny"]
     w_bytes = weight_stream_bytes(shape)
     stream_bytes = stream_kernel_bytes(shape)
     achieved = stream_bytes * prof_steps / (sk_ms * 1e-3) / 1e9
-    roofline = {"kernel": "gemm_bf16_stream_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+    roofline = {"kernel": "gemm_bf16_unit_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
                 "bytes_per_launch": stream_bytes * prof_steps / sk_n, "avg_launch_us": 1e3 * sk_ms / sk_n,
                 "launches_per_step": sk_n / prof_steps,
                 "measured_stream_read_GB/s": ceilings["stream_read_GB/s"],
                 "frac_of_measured_stream_read": achieved / ceilings["stream_read_GB/s"]}
     gemm_ms = sk_ms
-    others = (("gemm_slot", "gemm_bf16_skinny_kernel (QKV projection into one partial slot)", slot_kernel_bytes(shape)),
-              ("gemm_column", "gemm_bf16_column_kernel (O and down projections with the residual add)",
-               w_bytes - stream_bytes - slot_kernel_bytes(shape)))
+    others = (("gemm_column", "gemm_bf16_column_kernel (O and down projections with the residual add)",
+               w_bytes - stream_bytes),)
     roofline["other_gemms"] = []
     for kind, label, nbytes in others:
         if kind in prof and prof[kind][1]:

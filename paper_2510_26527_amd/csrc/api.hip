@@ -267,9 +267,8 @@ struct ForwardPlan {
     size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, total;
     size_t off_xn16, off_attn16, off_h16;
     bool half_copies;             // M > kStreamMaxRows, bf16: the producers also leave fp16 copies for the tiled projections
-    bool folded;
+    bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
     bool fused_rope;              // the attention kernel reduces, rotates and appends q / k / v itself
-    bool qkv_one_slot;            // ... and the QKV projection then leaves one slot for it to read                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
 };
 
 ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound) {
@@ -290,8 +289,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
     p.fused_rope = attn_fuses_rope(d.dtype, n_new, d.n_q_heads, d.n_kv_heads, d.d_head);
-    p.qkv_one_slot = p.fused_rope && mdl->packed && !mdl->w4 && M <= kStreamMaxRows;
-    p.sk_qkv = p.qkv_one_slot ? 1 : splits(M, d.d_model, p.width_qkv, n_qkv, 3);
+    p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
     p.sk_o = p.folded ? 1 : splits(M, hd, d.d_model, n_o, 1);
     p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
     p.sk_down = p.folded ? 1 : splits(M, d.d_ffn, d.d_model, n_o, 1);
@@ -429,7 +427,6 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         g.M = rows; g.K = K; g.N = n0 + n1 + n2; g.partial = dst; g.splitk = sk; g.reduced = nullptr;
         g.pack_tiles = gemm_pack_tiles(g.n, g.nseg);
         g.w4 = m->w4;
-        g.one_slot = w2 && p.qkv_one_slot;
         launch_gemm(d.dtype, g, st);
     };
     // Folded mode: no RMSNorm kernel runs.  The projections that write the residual stream add into it and

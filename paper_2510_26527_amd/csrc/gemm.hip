@@ -3,15 +3,15 @@
 // The kernels, chosen by model dtype and row count M (M = batch * n_new of a verify step):
 //   gemm_f32_kernel          fp32 weights, plain ALU dot products, one wavefront per output
 //                            column (the tiny fp32 chain; fp32 1e-4 parity, not speed).
-//   gemm_bf16_skinny_kernel  M <= 16.  HBM-bound weight streaming: W rows go straight from
-//                            global memory into MFMA A-operand registers with 16-byte loads
-//                            (no LDS), the few activation rows are the B operand, K is split
-//                            over the four wavefronts of a block and over blocks.
-//   gemm_bf16_stream_kernel  M <= 16 on weights repacked by gemm_pack_kernel: the same MFMA tiling,
-//                            but every 16 KB unit (64 rows x 128 k) is stored in exactly the order the
-//                            lanes load it, units of a GEMM are contiguous, and the grid is persistent:
-//                            each wavefront streams an equal, contiguous byte range of the weights
-//                            (stream-K) and writes one partial per tile it touches.
+//   gemm_bf16_skinny_kernel  M <= 16, weights as the caller stores them (row-major).  HBM-bound weight
+//                            streaming: W rows go straight from global memory into MFMA A-operand registers
+//                            with 16-byte loads (no LDS), the few activation rows are the B operand, K is
+//                            split over the four wavefronts of a block and over blocks.
+//   gemm_bf16_unit_kernel    M <= 16 on weights repacked by gemm_pack_kernel: the same MFMA tiling, but every
+//                            16 KB unit (64 rows x 128 k) is stored in exactly the order the lanes load it,
+//                            units of a GEMM are contiguous, and the grid is persistent: each block streams
+//                            an equal, contiguous range of units (stream-K), its four wavefronts on the four
+//                            K quarters of every unit, and writes one partial per tile it touches.
 //   gemm_bf16_column_kernel  M <= 16, the projections that write the residual stream: one block per 16
 //                            output columns over the whole K range; the residual add, the gain-scaled copy
 //                            and the RMSNorm statistics happen in its epilogue.
@@ -37,7 +37,7 @@ namespace psd {
 namespace {
 
 // source row of activation row m: rows may be a strided subset (the last rows of each sequence)
-__device__ __forceinline__ size_t x_row(const GemmArgs &g, int m) {
+__host__ __device__ __forceinline__ size_t x_row(const GemmArgs &g, int m) {
     return (size_t)(m / g.x_rows_per_group) * g.x_group_stride + g.x_group_offset + (m % g.x_rows_per_group);
 }
 
@@ -135,9 +135,9 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs g) {
 // cover 2 x 128 contiguous bytes; the activation operand uses the same permutation.
 constexpr int kSkinnyRows = 64;
 constexpr int kSkinnyStepK = 128;
-constexpr int kStreamBlocks = 512;                 // persistent grid of the stream-K kernel: 2 blocks per CU
+constexpr int kStreamBlocks = 512;                 // persistent grid of the unit kernel: 2 blocks per CU
 
-template <int MT, bool PACKED>
+template <int MT>
 __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
@@ -173,17 +173,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
         for (int mt = 0; mt < MT; ++mt) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     bf16x8 a_cur[4][4], a_nxt[4][4];
-    // packed weights: unit (tile, step) is 16 slots of 1 KB, slot strip*4+q holds this lane's operand
-    const bf16x8 *pk = reinterpret_cast<const bf16x8 *>(g.wpack) + (size_t)blockIdx.x * nsteps * 1024 + lane;
     auto load_a = [&](bf16x8 (&dst)[4][4], int step) {
         const int kk = step * kSkinnyStepK;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if constexpr (PACKED) dst[s][q] = __builtin_nontemporal_load(pk + (size_t)step * 1024 + (s * 4 + q) * 64);
-                else dst[s][q] = *reinterpret_cast<const bf16x8 *>(wp[s] + kk + (q >> 1) * 64 + (q & 1) * 8);
-            }
+            for (int q = 0; q < 4; ++q) dst[s][q] = *reinterpret_cast<const bf16x8 *>(wp[s] + kk + (q >> 1) * 64 + (q & 1) * 8);
     };
     if (s0 < s1) load_a(a_cur, s0);
     for (int step = s0; step < s1; ++step) {
@@ -242,11 +237,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(GemmArgs g) {
     }
 }
 
-// ------------------------------------------------------------------------------ bf16 stream-K on packed weights
+// ------------------------------------------------------------------------------ bf16 stream-K on packed weights (unit kernel)
 // Packed layout of one GEMM (all its weight matrices, in segment order): tiles of 64 rows, each
-// tile ns = K/128 units of 16 KB.  Unit = 16 slots of 1 KB; slot (strip, q) holds, for lane l =
-// (i = l & 15, gq = l >> 4), the 8 bf16 W[tile*64 + strip*16 + i][step*128 + (q>>1)*64 + gq*16 + (q&1)*8 ...].
-// Rows past the end of a matrix are stored as zeros.
+// tile ns = K/128 units of 16 KB.  Unit = 16 slots of 1 KB, slot index q*4 + strip; slot (q, strip) holds, for
+// lane l = (i = l & 15, gq = l >> 4), the 8 bf16 W[tile*64 + strip*16 + i][step*128 + (q>>1)*64 + gq*16 + (q&1)*8 ...]:
+// the 4 KB of K quarter q are contiguous.  Rows past the end of a matrix are stored as zeros.
 constexpr int kUnitBytes = kSkinnyRows * kSkinnyStepK * 2;
 constexpr int kUnitVec = kUnitBytes / 16;          // 16-byte vectors per unit
 
@@ -259,7 +254,7 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t *W, int N
     const size_t unit = vec / kUnitVec;
     const int within = (int)(vec % kUnitVec), slot = within >> 6, lane = within & 63;
     const int tile = (int)(unit / ns), step = (int)(unit % ns);
-    const int strip = slot >> 2, q = slot & 3, i = lane & 15, gq = lane >> 4;
+    const int q = slot >> 2, strip = slot & 3, i = lane & 15, gq = lane >> 4;
     const int row = tile * kSkinnyRows + strip * 16 + i;
     const int k = step * kSkinnyStepK + (q >> 1) * 64 + gq * 16 + (q & 1) * 8;
     u32x4 v = u32x4{0u, 0u, 0u, 0u};
@@ -267,114 +262,105 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t *W, int N
     dst[vec] = v;
 }
 
-// first unit of wavefront w when U units are dealt to P wavefronts in contiguous, near-equal ranges
-__host__ __device__ __forceinline__ long range_begin(long w, long U, long P) { return w * U / P; }
-// the wavefront whose range holds unit u
+// first unit of block b when U units are dealt to P blocks in contiguous, near-equal ranges
+__host__ __device__ __forceinline__ long range_begin(long b, long U, long P) { return b * U / P; }
+// the block whose range holds unit u
 __host__ __device__ __forceinline__ long range_owner(long u, long U, long P) { return ((u + 1) * P - 1) / U; }
 
-template <int MT>
-__global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+constexpr int kUnitRing = 2;                       // units in flight per wavefront (its 4 KB of each)
+
+// Block b streams the contiguous units [range_begin(b), range_begin(b + 1)); wavefront q multiplies the q-th 4 KB of
+// every unit (K offsets (q>>1)*64 + (q&1)*8 + 16 gq of the unit's 128), so the four wavefronts of a block read 16 KB
+// in one piece and the blocks of the grid adjacent ranges: the access pattern of a plain streaming read.  Weights
+// and the matching 8 activations per lane travel through a ring of kUnitRing register stages filled by buffer
+// loads: the block's range is the buffer, so the loads issued past its end return zeros without touching memory,
+// every wavefront runs the same straight-line loop, and a stage's data is waited for with the later stages still
+// in flight.  At the end of a tile (or of the range) the four K quarters are added through LDS in wavefront order
+// and the block writes ONE partial: slot = its index among the blocks that share the tile; the block that
+// finishes a tile zeroes the slots nobody writes.
+__global__ __launch_bounds__(256) void gemm_bf16_unit_kernel(GemmArgs g) {
+    constexpr int R = kUnitRing;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
-    const float *X = g.x;
     const int K = g.K, ns = K / kSkinnyStepK;
-    const long U = (long)g.pack_tiles * ns, P = (long)gridDim.x * 4;
-    const long w = (long)blockIdx.x * 4 + wave;
-    const long u0 = range_begin(w, U, P), u1 = range_begin(w + 1, U, P);
+    const long U = (long)g.pack_tiles * ns, P = gridDim.x;
+    const int u0 = (int)range_begin(blockIdx.x, U, P), u1 = (int)range_begin(blockIdx.x + 1, U, P);
     if (u0 >= u1) return;
+    const int n_my = u1 - u0;
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        (char *)const_cast<void *>(g.wpack) + (size_t)u0 * kUnitBytes, 0, n_my * kUnitBytes, 0x00020000);
+    // activations: offsets from the first row's source row; a row past M points past the buffer and reads zeros
+    const size_t row_first = x_row(g, 0);
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(g.x) + row_first * K, 0, 0x7ffffff0, 0x00020000);
+    const unsigned kq = (unsigned)((q >> 1) * 64 + gq * 16 + (q & 1) * 8) * 4u;
+    const unsigned xbase = i < g.M ? (unsigned)((x_row(g, i) - row_first) * K * 4) + kq : 0x80000000u;
 
-    const float *xp[MT];
-    bool xvalid[MT];
+    u32x4 A[R][4], X[R][2];
+    int step_issue = u0 % ns;
+    auto issue = [&](int j, int n) {                       // n = index of the unit inside the block's range
+        const unsigned woff = (unsigned)n * kUnitBytes + q * 4096u + lane * 16u;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int tok = mt * 16 + i;
-        xvalid[mt] = tok < g.M;
-        xp[mt] = X + x_row(g, min(tok, g.M - 1)) * K + gq * 16;
-    }
-    f32x4 acc[4][MT];
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const u32x4 *wbase = reinterpret_cast<const u32x4 *>(g.wpack) + lane;
-    u32x4 a_cur[16], a_nxt[16];
-    auto load_unit = [&](u32x4 (&dst)[16], long u) {
-        const u32x4 *p = wbase + u * kUnitVec;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) dst[j] = __builtin_nontemporal_load(p + j * 64);
+        for (int s = 0; s < 4; ++s) A[j][s] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff + s * 1024, 0, 2);   // 2: streaming
+        const unsigned xoff = n < n_my ? xbase + (unsigned)step_issue * (kSkinnyStepK * 4) : 0x80000000u;
+        X[j][0] = __builtin_amdgcn_raw_buffer_load_b128(rx, xoff, 0, 0);
+        X[j][1] = __builtin_amdgcn_raw_buffer_load_b128(rx, xoff + 16, 0, 0);
+        step_issue = step_issue + 1 == ns ? 0 : step_issue + 1;
     };
-    __shared__ float red[4][kSkinnyRows][17];      // per-wavefront transpose buffer for the partial stores
-
-    load_unit(a_cur, u0);
-    for (long u = u0; u < u1; ++u) {
-        if (u + 1 < u1) load_unit(a_nxt, u + 1);
-        const int tile = (int)(u / ns), step = (int)(u % ns);
-        const int kk = step * kSkinnyStepK;
+    f32x4 acc[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bf16x8 bh[MT], bl[MT];
+    for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __shared__ float red[4][kSkinnyRows][17];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int k = kk + (q >> 1) * 64 + (q & 1) * 8;
-                const f32x8 xv = load_act8(xp[mt], k, xvalid[mt]);
-                split_bf16(xv, &bh[mt], &bl[mt]);
-            }
+    for (int j = 0; j < R; ++j) issue(j, j);
+    int step_use = u0 % ns, tile = u0 / ns;
+    for (int base = 0; base < n_my; base += R) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[s * 4 + q]);
+        for (int j = 0; j < R; ++j) {
+            const int n = base + j;
+            f32x8 xv;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh[mt], acc[s][mt], 0, 0, 0);
-            }
+            for (int e = 0; e < 4; ++e) { xv[e] = __uint_as_float(X[j][0][e]); xv[4 + e] = __uint_as_float(X[j][1][e]); }
+            bf16x8 bh, bl;
+            split_bf16(xv, &bh, &bl);
+            // hi parts over all accumulators, then lo parts: no back-to-back MFMAs on one accumulator
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[s * 4 + q]);
+            for (int s = 0; s < 4; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[j][s]), bh, acc[s], 0, 0, 0);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl[mt], acc[s][mt], 0, 0, 0);
-            }
-        }
-        if (step == ns - 1 || u + 1 == u1) {
-            // ---- flush this wavefront's share of tile `tile` into its partial slot
-            const TileRef t = find_tile(g, tile, kSkinnyRows);
-            const int seg_rows = g.n[t.seg];
-            const long w_lo = range_owner((long)tile * ns, U, P);
-            const int slot = (int)(w - w_lo);
-            const int row = t.row0 + lane;                   // lane = row of the tile from here on
-            const bool row_ok = row < seg_rows;
-            const size_t col = (size_t)t.col0 + row;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
+            for (int s = 0; s < 4; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[j][s]), bl, acc[s], 0, 0, 0);
+            issue(j, n + R);
+            const bool tile_end = step_use + 1 == ns;
+            step_use = tile_end ? 0 : step_use + 1;
+            if (n < n_my && (tile_end || n + 1 == n_my)) {                  // the same for all four wavefronts
+                // acc[s][v] = y[token i][row s*16 + 4*gq + v of the tile] over this wavefront's K quarter
+                const TileRef t = find_tile(g, tile, kSkinnyRows);
+                const int slot = (int)(blockIdx.x - range_owner((long)tile * ns, U, P));
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][mt][v];
-                __builtin_amdgcn_wave_barrier();
-                if (row_ok) {
-                    for (int mm = 0; mm < 16; ++mm) {
-                        const int tok = mt * 16 + mm;
-                        if (tok < g.M) g.partial[((size_t)slot * g.M + tok) * g.N + col] = red[wave][lane][mm];
+                    for (int v = 0; v < 4; ++v) red[q][s * 16 + 4 * gq + v][i] = acc[s][v];
+                __syncthreads();
+                const int row = t.row0 + lane;                                  // lane = row of the tile from here on
+                if (row < g.n[t.seg]) {
+                    const size_t col = (size_t)t.col0 + row;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int tok = q + 4 * r;
+                        if (tok < g.M) {
+                            g.partial[((size_t)slot * g.M + tok) * g.N + col] =
+                                ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
+                            if (tile_end)
+                                for (int jj = slot + 1; jj < g.splitk; ++jj) g.partial[((size_t)jj * g.M + tok) * g.N + col] = 0.f;
+                        }
                     }
                 }
-                __builtin_amdgcn_wave_barrier();
+                __syncthreads();
 #pragma unroll
-                for (int s = 0; s < 4; ++s) acc[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-            if (step == ns - 1 && row_ok) {
-                // the wavefront that finishes a tile zeroes the slots no wavefront writes
-                const long w_hi = w;
-                for (int j = 0; j < g.splitk; ++j) {
-                    const long wj = w_lo + j;
-                    const bool written = wj <= w_hi && range_begin(wj, U, P) < range_begin(wj + 1, U, P);
-                    if (!written)
-                        for (int tok = 0; tok < g.M; ++tok) g.partial[((size_t)j * g.M + tok) * g.N + col] = 0.f;
-                }
-            }
-        }
-        if (u + 1 < u1) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) a_cur[j] = a_nxt[j];
+            if (tile_end) ++tile;
         }
     }
 }
@@ -812,11 +798,6 @@ int tiles_of(const int *n, int nseg, int rows) {
 
 }  // namespace
 
-// Stream-K pays off when there are many tiles: then few wavefronts share a tile.  With few tiles
-// (N = d_model projections) the K range of a tile is split over the four wavefronts of a block, added
-// through LDS, and over blocks (gemm_bf16_skinny_kernel), which keeps the partial slots few.
-bool gemm_use_stream(int tiles) { return tiles >= 128; }
-
 // Tile width (NB x 32 columns, NB = 4, 6, 8) and K split of the tiled kernel: the pair with the least estimated
 // time: rounds of 512 resident blocks x K tiles per block x the time of one K tile of two co-resident blocks,
 // which the LDS traffic sets (16 KB of activations and 4 NB KB of weights written, 4 (2 + NB/2) x 4 KB read, at
@@ -842,14 +823,12 @@ static void tiled_choice(int M, int K, const int *n, int nseg, int *nb_out, int 
 
 int gemm_stream_grid(int tiles, int K) {
     const long U = (long)tiles * (K / kSkinnyStepK);
-    long blocks = U / 4;                              // every wavefront gets at least one unit
-    if (blocks > kStreamBlocks) blocks = kStreamBlocks;
-    return blocks < 1 ? 1 : (int)blocks;
+    return (int)(U < kStreamBlocks ? (U < 1 ? 1 : U) : kStreamBlocks);
 }
 
-// largest number of wavefronts that share one tile, i.e. partial slots per output element
+// largest number of blocks that share one tile, i.e. partial slots per output element
 int gemm_stream_slots(int tiles, int K) {
-    const long ns = K / kSkinnyStepK, U = (long)tiles * ns, P = (long)gemm_stream_grid(tiles, K) * 4;
+    const long ns = K / kSkinnyStepK, U = (long)tiles * ns, P = gemm_stream_grid(tiles, K);
     long worst = 1;
     for (long t = 0; t < tiles; ++t) {
         const long span = range_owner((t + 1) * ns - 1, U, P) - range_owner(t * ns, U, P) + 1;
@@ -905,9 +884,8 @@ int gemm_w4_splits(int K, const int *n, int nseg) {
 }
 
 int gemm_packed_splits(int M, int K, const int *n, int nseg) {
-    const int tiles = tiles_of(n, nseg, kSkinnyRows);
-    if (gemm_use_stream(tiles)) return gemm_stream_slots(tiles, K);
-    return gemm_pick_splitk(PSD_BF16, M, K, 0, n, nseg);
+    (void)M;
+    return gemm_stream_slots(tiles_of(n, nseg, kSkinnyRows), K);
 }
 
 int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg) {
@@ -945,18 +923,15 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         launch_kernel(gemm_bf16_column_kernel<1, 16>, grid, 1024, 0, stream, g);
         return;
     }
-    if (g.M <= kStreamMaxRows && g.wpack && !g.one_slot && gemm_use_stream(g.pack_tiles)) {
+    // the unit kernel addresses the activation rows with 32-bit offsets from the first one
+    const bool x_near = (long)(x_row(g, g.M - 1) - x_row(g, 0) + 1) * g.K * 4 < 0x7fff0000L;
+    if (g.M <= kStreamMaxRows && g.wpack && x_near) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
-        const int grid = gemm_stream_grid(g.pack_tiles, g.K);
-        launch_kernel(gemm_bf16_stream_kernel<1>, grid, 256, 0, stream, g);
+        launch_kernel(gemm_bf16_unit_kernel, gemm_stream_grid(g.pack_tiles, g.K), 256, 0, stream, g);
     } else if (g.M <= kStreamMaxRows) {
         ScopedProf sp(PSD_KIND_GEMM_SLOT, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);
-        if (g.wpack) {
-            launch_kernel(gemm_bf16_skinny_kernel<1, true>, grid, 256, 0, stream, g);
-        } else {
-            launch_kernel(gemm_bf16_skinny_kernel<1, false>, grid, 256, 0, stream, g);
-        }
+        launch_kernel(gemm_bf16_skinny_kernel<1>, grid, 256, 0, stream, g);
     } else {
         ScopedProf sp(PSD_KIND_GEMM_TILED, stream);
         int nb, sk;

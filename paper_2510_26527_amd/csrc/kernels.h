@@ -59,8 +59,6 @@ struct GemmArgs {
     int pack_tiles;               //   its number of 64-row tiles
     float *partial;               // [splitk][M][N] fp32: split s holds its share of the K sum
     int splitk;
-    bool one_slot;                // packed weights, M <= kStreamMaxRows: one block per 64-row tile over the whole K range
-                                  //   (splitk = 1) instead of the stream-K kernel, for consumers that read the slots directly
     float *reduced;               // if non-NULL: [M][N] <- sum over splits (logits), times the row scale if given
     // -- bf16, M <= kStreamMaxRows, packed weights only: RMSNorm folded into the projections around it -----------
     // rmsnorm(x) W^T = r_m * ((x * gain) W^T) with r_m = rsqrt(mean_k x[m][k]^2 + eps).  The one-slot column
@@ -84,7 +82,6 @@ int gemm_pack_tiles(const int *n, int nseg);
 size_t gemm_pack_bytes(const int *n, int nseg, int K);
 int gemm_w4_splits(int K, const int *n, int nseg);             // K splits (partial slots) of a 4-bit projection
 int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots (the splitk to use) with packed weights
-bool gemm_use_stream(int tiles);
 int gemm_stream_grid(int tiles, int K);
 int gemm_stream_slots(int tiles, int K);
 // strip_major: the layout of the one-slot column kernel (projections with N = d_model)
