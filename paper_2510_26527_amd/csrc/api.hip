@@ -215,7 +215,7 @@ psd_status psd_model_pack(psd_model *m, void *packed_mem, size_t packed_bytes, v
         const int n_gu[2] = {d.d_ffn, d.d_ffn};
         launch_gemm_pack(gu, n_gu, 2, d.d_model, base + off[4 * l + P_GU], false, st);
         const void *dn[1] = {m->layer(l, W_DOWN)};
-        launch_gemm_pack(dn, n_o, 1, d.d_ffn, base + off[4 * l + P_DOWN], true, st);
+        launch_gemm_pack(dn, n_o, 1, d.d_ffn, base + off[4 * l + P_DOWN], false, st);
     }
     const void *hw[1] = {m->lm_head()};
     const int n_v[1] = {d.vocab};
@@ -264,7 +264,7 @@ namespace {
 struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
-    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, total;
+    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, off_tilectr, total;
     size_t off_xn16, off_attn16, off_h16;
     bool half_copies;             // M > kStreamMaxRows, bf16: the producers also leave fp16 copies for the tiled projections
     bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
@@ -292,7 +292,8 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
     p.sk_o = p.folded ? 1 : splits(M, hd, d.d_model, n_o, 1);
     p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
-    p.sk_down = p.folded ? 1 : splits(M, d.d_ffn, d.d_model, n_o, 1);
+    // folded: the down projection runs on the unit kernel with the residual epilogue, its partials in slots
+    p.sk_down = p.folded ? gemm_resid_slots(gemm_pack_tiles(n_o, 1), d.d_ffn) : splits(M, d.d_ffn, d.d_model, n_o, 1);
     p.sk_head = Ml > 0 ? splits(Ml, d.d_model, d.vocab, n_v, 1) : 1;
     p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
     const size_t act = 4;                                    // activations are fp32 for both dtypes
@@ -317,6 +318,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.off_pml = take(p.attn_splits > 1 ? (size_t)M * d.n_q_heads * p.attn_splits * 2 * 4 : 0);
     p.off_sumsq = take(p.folded ? (size_t)(d.d_model / 16) * M * 4 : 0);
     p.off_rope = take(p.fused_rope ? (size_t)M * (d.d_head / 2) * sizeof(float2) : 0);
+    p.off_tilectr = take(p.folded ? (size_t)gemm_pack_tiles(n_o, 1) * 4 : 0);
     p.total = off;
     return p;
 }
@@ -435,17 +437,21 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
     // their output multiply by the row scale rsqrt(mean x^2 + eps).
     float *sumsq = (float *)(ws + p.off_sumsq);
     const int col_tiles = d.d_model / 16;
+    const int n_o_fw[1] = {d.d_model};
     RowScale rs{nullptr, 0, 1.0f / (float)d.d_model, d.rms_eps};
     if (p.folded) rs.sumsq = sumsq;
     const float *act = xn;     // what QKV / gate|up / lm_head read: rmsnorm(x) * gain, or x * gain when folded
-    auto resid_gemm = [&](const float *xin, int K, const void *w, int sk, const void *wpack, const void *next_gain) {
+    unsigned *tile_ctr = p.folded ? (unsigned *)(ws + p.off_tilectr) : nullptr;
+    auto resid_gemm = [&](const float *xin, int K, const void *w, int sk, const void *wpack, const void *next_gain,
+                          bool by_units) {
         if (p.folded) {
             GemmArgs g{};
             g.wpack = wpack; g.x = xin; g.x_rows_per_group = M; g.w[0] = w; g.n[0] = d.d_model; g.nseg = 1;
-            g.M = M; g.K = K; g.N = d.d_model; g.splitk = 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
+            g.M = M; g.K = K; g.N = d.d_model; g.splitk = by_units ? sk : 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
             g.x_resid = x; g.xg_out = xn; g.gain = next_gain; g.sumsq_out = sumsq; g.w4 = m->w4;
+            if (by_units) { g.tile_counter = tile_ctr; g.partial = partial; }
             launch_gemm(d.dtype, g, st);
-            rs.tiles = col_tiles;
+            rs.tiles = by_units ? g.pack_tiles : col_tiles;
         } else {
             gemm(xin, M, K, w, d.d_model, nullptr, 0, nullptr, 0, sk, partial, wpack);
             launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, xn16, st);
@@ -454,7 +460,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
     RopeTable rt{};
     if (p.fused_rope) rt = RopeTable{(float2 *)(ws + p.off_rope), kv->lens, n_new, d.d_head, d.rope_theta};
     launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, p.folded ? sumsq : nullptr, M, d.d_model,
-                      d.vocab, d.rms_eps, rt, xn16, st);
+                      d.vocab, d.rms_eps, rt, xn16, ZeroFill{tile_ctr, p.folded ? gemm_pack_tiles(n_o_fw, 1) : 0}, st);
     rs.tiles = 1;
     for (int l = 0; l < d.n_layers; ++l) {
         gemm(act, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial,
@@ -471,11 +477,11 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         a.splits = p.attn_splits;
         launch_attention(d.dtype, a, st);
 
-        resid_gemm(attn, hd, m->layer(l, W_O), p.sk_o, m->pack(l, P_O), m->layer(l, W_FFN_NORM));
+        resid_gemm(attn, hd, m->layer(l, W_O), p.sk_o, m->pack(l, P_O), m->layer(l, W_FFN_NORM), false);
         gemm(act, M, d.d_model, m->layer(l, W_GATE), d.d_ffn, m->layer(l, W_UP), d.d_ffn, nullptr, 0, p.sk_gu, partial,
              m->pack(l, P_GU));
         launch_reduce_swiglu(partial, p.sk_gu, rs, h, M, d.d_ffn, h16, st);
-        resid_gemm(h, d.d_ffn, m->layer(l, W_DOWN), p.sk_down, m->pack(l, P_DOWN), norm_gain(l + 1));
+        resid_gemm(h, d.d_ffn, m->layer(l, W_DOWN), p.sk_down, m->pack(l, P_DOWN), norm_gain(l + 1), true);
     }
     if (n_logit_rows > 0) {
         // lm_head on the last n_logit_rows rows of every sequence (unfolded: xn already holds the final norm)

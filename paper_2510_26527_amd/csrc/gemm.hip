@@ -278,6 +278,14 @@ constexpr int kUnitRing = 2;                       // units in flight per wavefr
 // in flight.  At the end of a tile (or of the range) the four K quarters are added through LDS in wavefront order
 // and the block writes ONE partial: slot = its index among the blocks that share the tile; the block that
 // finishes a tile zeroes the slots nobody writes.
+//
+// RESID (the projections that write the residual stream, when a block per 16 columns would be the slower choice):
+// every output element still gets one owner, found at run time.  A block publishes its partial with agent-scope
+// stores, waits for them, and counts itself in on the tile's counter; whichever block arrives last adds the tile's
+// slots in slot order (so the sum does not depend on who that was) and runs the column kernel's epilogue on the
+// tile's 64 columns: residual add, gain-scaled copy, sum of squares per row into sumsq_out[tile][m].  It leaves the
+// counter at zero for the next launch.  No block waits for another.
+template <bool RESID>
 __global__ __launch_bounds__(256) void gemm_bf16_unit_kernel(GemmArgs g) {
     constexpr int R = kUnitRing;
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
@@ -311,6 +319,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_unit_kernel(GemmArgs g) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
     __shared__ float red[4][kSkinnyRows][17];
+    __shared__ int s_last;
 #pragma unroll
     for (int j = 0; j < R; ++j) issue(j, j);
     int step_use = u0 % ns, tile = u0 / ns;
@@ -343,8 +352,58 @@ __global__ __launch_bounds__(256) void gemm_bf16_unit_kernel(GemmArgs g) {
                     for (int v = 0; v < 4; ++v) red[q][s * 16 + 4 * gq + v][i] = acc[s][v];
                 __syncthreads();
                 const int row = t.row0 + lane;                                  // lane = row of the tile from here on
-                if (row < g.n[t.seg]) {
-                    const size_t col = (size_t)t.col0 + row;
+                const bool row_ok = row < g.n[t.seg];
+                const size_t col = (size_t)t.col0 + row;
+                if constexpr (RESID) {
+                    const int n_contrib = (int)(range_owner((long)tile * ns + ns - 1, U, P) - range_owner((long)tile * ns, U, P)) + 1;
+                    float mine[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int tok = q + 4 * r;
+                        mine[r] = ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
+                    }
+                    bool last = true;
+                    if (n_contrib > 1) {                                        // the same for the whole block
+                        if (row_ok)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                if (q + 4 * r < g.M)
+                                    __hip_atomic_store(&g.partial[((size_t)slot * g.M + q + 4 * r) * g.N + col], mine[r],
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                        __syncthreads();
+                        if (threadIdx.x == 0)
+                            s_last = __hip_atomic_fetch_add(&g.tile_counter[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                                     (unsigned)(n_contrib - 1);
+                        __syncthreads();
+                        last = s_last != 0;
+                    }
+                    if (last) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int tok = q + 4 * r;
+                            float v = 0.f, sq = 0.f;
+                            if (tok < g.M && row_ok) {
+                                if (n_contrib > 1) {
+                                    for (int sl = 0; sl < n_contrib; ++sl)
+                                        v += __hip_atomic_load(&g.partial[((size_t)sl * g.M + tok) * g.N + col], __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                                } else {
+                                    v = mine[r];
+                                }
+                                const size_t o = (size_t)tok * g.N + col;
+                                v += g.x_resid[o];
+                                g.x_resid[o] = v;
+                                if (g.xg_out) g.xg_out[o] = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
+                                sq = v * v;
+                            }
+                            sq = wave_sum(sq);                                  // the tile's 64 columns of row tok sit in this wavefront
+                            if (lane == 0 && tok < g.M && g.sumsq_out) g.sumsq_out[(size_t)tile * g.M + tok] = sq;
+                        }
+                        if (n_contrib > 1 && threadIdx.x == 0)
+                            __hip_atomic_store(&g.tile_counter[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                } else if (row_ok) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int tok = q + 4 * r;
@@ -826,9 +885,19 @@ int gemm_stream_grid(int tiles, int K) {
     return (int)(U < kStreamBlocks ? (U < 1 ? 1 : U) : kStreamBlocks);
 }
 
+// grid of the unit kernel with the residual epilogue: one block per CU, so that few blocks share a tile (the last of
+// them to arrive adds their partials)
+int gemm_resid_grid(int tiles, int K) {
+    const long U = (long)tiles * (K / kSkinnyStepK);
+    return (int)(U < kStreamBlocks / 2 ? (U < 1 ? 1 : U) : kStreamBlocks / 2);
+}
+
 // largest number of blocks that share one tile, i.e. partial slots per output element
-int gemm_stream_slots(int tiles, int K) {
-    const long ns = K / kSkinnyStepK, U = (long)tiles * ns, P = gemm_stream_grid(tiles, K);
+static int gemm_slots_of(int tiles, int K, int grid);
+int gemm_resid_slots(int tiles, int K) { return gemm_slots_of(tiles, K, gemm_resid_grid(tiles, K)); }
+int gemm_stream_slots(int tiles, int K) { return gemm_slots_of(tiles, K, gemm_stream_grid(tiles, K)); }
+static int gemm_slots_of(int tiles, int K, int grid) {
+    const long ns = K / kSkinnyStepK, U = (long)tiles * ns, P = grid;
     long worst = 1;
     for (long t = 0; t < tiles; ++t) {
         const long span = range_owner((t + 1) * ns - 1, U, P) - range_owner(t * ns, U, P) + 1;
@@ -917,6 +986,11 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         launch_kernel(gemm_w4_tile_kernel, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
         return;
     }
+    if (g.M <= kStreamMaxRows && g.wpack && g.x_resid && g.tile_counter) {
+        ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
+        launch_kernel(gemm_bf16_unit_kernel<true>, gemm_resid_grid(g.pack_tiles, g.K), 256, 0, stream, g);
+        return;
+    }
     if (g.M <= kStreamMaxRows && g.wpack && g.x_resid) {
         ScopedProf sp(PSD_KIND_GEMM_COLUMN, stream);
         const int grid = g.N / 16;                        // every segment is a multiple of 64 wide; M <= 16: one row tile
@@ -927,7 +1001,7 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
     const bool x_near = (long)(x_row(g, g.M - 1) - x_row(g, 0) + 1) * g.K * 4 < 0x7fff0000L;
     if (g.M <= kStreamMaxRows && g.wpack && x_near) {
         ScopedProf sp(PSD_KIND_GEMM_SKINNY, stream);
-        launch_kernel(gemm_bf16_unit_kernel, gemm_stream_grid(g.pack_tiles, g.K), 256, 0, stream, g);
+        launch_kernel(gemm_bf16_unit_kernel<false>, gemm_stream_grid(g.pack_tiles, g.K), 256, 0, stream, g);
     } else if (g.M <= kStreamMaxRows) {
         ScopedProf sp(PSD_KIND_GEMM_SLOT, stream);
         dim3 grid(tiles_of(g.n, g.nseg, kSkinnyRows), g.splitk);

@@ -69,7 +69,9 @@ struct GemmArgs {
     float *x_resid;
     float *xg_out;
     const void *gain;             // [N] bf16
-    float *sumsq_out;             // [N/16][M]
+    float *sumsq_out;             // [N/16][M] (column kernel) or [N/64][M] (unit kernel with the residual epilogue)
+    unsigned *tile_counter;       // non-NULL selects the unit kernel for this projection: [N/64] arrival counters, zero
+                                  //   before the launch and left at zero by it; `partial` then holds gemm_resid_slots() slots
     // -- 4-bit weights (W4A16, groups of 128 along K): wpack holds the strip-major 4-bit layout of
     // launch_gemm_pack_w4; the projection writes `splitk` partial slots (gemm_w4_splits)
     bool w4;
@@ -84,6 +86,8 @@ int gemm_w4_splits(int K, const int *n, int nseg);             // K splits (part
 int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots (the splitk to use) with packed weights
 int gemm_stream_grid(int tiles, int K);
 int gemm_stream_slots(int tiles, int K);
+int gemm_resid_grid(int tiles, int K);
+int gemm_resid_slots(int tiles, int K);                          // partial slots of a projection run with tile_counter
 // strip_major: the layout of the one-slot column kernel (projections with N = d_model)
 void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, bool strip_major, hipStream_t stream);
 // 4-bit weight-only quantised projections: q [n][K/2] bytes (low nibble = even k), scale bf16 [n][K/128],
@@ -132,9 +136,14 @@ struct RopeTable {
     int R, d_h;
     float theta;
 };
+struct ZeroFill {
+    unsigned *words;              // n 32-bit words set to zero by the first kernel of a forward pass (NULL / 0: none)
+    int n;
+};
 // x = embed[token]; then xn = rmsnorm(x) * gain, or (sumsq_out non-NULL) xn = x * gain and sumsq_out[m] = sum_k x[m][k]^2
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, uint16_t *xn16, hipStream_t stream);
+                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, uint16_t *xn16, ZeroFill zf,
+                       hipStream_t stream);
 // qkv = sum over splits of partial [S][M][(h_q+2h_kv) d_h] -> rotated q (fp32), rotated k and v appended
 // to the cache (model dtype)
 void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,

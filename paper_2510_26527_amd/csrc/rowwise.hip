@@ -37,10 +37,14 @@ template <typename TW, bool EMBED>
 __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *embed, const int32_t *tokens, int vocab,
                                                                     const float *partial, int S, size_t split_stride,
                                                                     float *x, const TW *gain, float *xn, float *sumsq_out,
-                                                                    int d, float eps, RopeTable rt, uint16_t *xn16) {
+                                                                    int d, float eps, RopeTable rt, uint16_t *xn16,
+                                                                    ZeroFill zf) {
     __shared__ float red[4];
     const int m = blockIdx.x, tid = threadIdx.x, n4 = d >> 2;
     if constexpr (EMBED) {
+        // counters that later kernels of this forward pass expect at zero
+        if (m == 0)
+            for (int j = tid; j < zf.n; j += kRowThreads) zf.words[j] = 0u;
         // (cos, sin) of this row's position at every rotation frequency, once per forward pass for all layers;
         // the angle position * theta^(-2i/d_h) is evaluated in fp64
         if (rt.cs && tid < rt.d_h / 2) {
@@ -238,14 +242,15 @@ __global__ void truncate_to_kernel(int32_t *lens, int new_len, int B) {
 }  // namespace
 
 void launch_embed_norm(int dtype, const void *embed, const int32_t *tokens, float *x, const void *gain, float *xn,
-                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, uint16_t *xn16, hipStream_t stream) {
+                       float *sumsq_out, int M, int d, int vocab, float eps, RopeTable rt, uint16_t *xn16, ZeroFill zf,
+                       hipStream_t stream) {
     ScopedProf sp(PSD_KIND_EMBED, stream);
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, true>, M, kRowThreads, 0, stream, (const uint16_t *)embed, tokens, vocab, nullptr, 0, 0,
-                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps, rt, xn16);
+                                                                           x, (const uint16_t *)gain, xn, sumsq_out, d, eps, rt, xn16, zf);
     else
         launch_kernel(residual_norm_kernel<float, true>, M, kRowThreads, 0, stream, (const float *)embed, tokens, vocab, nullptr, 0, 0, x,
-                                                                        (const float *)gain, xn, sumsq_out, d, eps, rt, xn16);
+                                                                        (const float *)gain, xn, sumsq_out, d, eps, rt, xn16, zf);
 }
 
 void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *x, const void *gain, float *xn,
@@ -254,10 +259,10 @@ void launch_reduce_residual_norm(int dtype, const float *partial, int S, float *
     const size_t stride = (size_t)M * d;
     if (dtype == PSD_BF16)
         launch_kernel(residual_norm_kernel<uint16_t, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                            (const uint16_t *)gain, xn, nullptr, d, eps, RopeTable{}, xn16);
+                                                                            (const uint16_t *)gain, xn, nullptr, d, eps, RopeTable{}, xn16, ZeroFill{});
     else
         launch_kernel(residual_norm_kernel<float, false>, M, kRowThreads, 0, stream, nullptr, nullptr, 0, partial, S, stride, x,
-                                                                         (const float *)gain, xn, nullptr, d, eps, RopeTable{}, xn16);
+                                                                         (const float *)gain, xn, nullptr, d, eps, RopeTable{}, xn16, ZeroFill{});
 }
 
 void launch_reduce_rope_append(int dtype, const float *partial, int S, RowScale rs, float *q_out, void *k_cache,
