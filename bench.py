@@ -31,7 +31,7 @@ def weight_stream_bytes(shape):
 
 def stream_kernel_bytes(shape):
     """The share of weight_stream_bytes read by gemm_bf16_unit_kernel: the QKV, gate|up and lm_head
-    projections (the O and down projections run on the one-slot column kernel)."""
+    projections (O runs on the column kernel, down on the unit kernel with the residual epilogue)."""
     s = shape
     hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
     return 2 * (s.n_layers * (s.d_model * (hd + 2 * kvd) + 2 * s.d_model * s.d_ffn) + s.vocab * s.d_model)
@@ -254,7 +254,7 @@ def main():
                 "measured_stream_read_GB/s": ceilings["stream_read_GB/s"],
                 "frac_of_measured_stream_read": achieved / ceilings["stream_read_GB/s"]}
     gemm_ms = sk_ms
-    others = (("gemm_column", "gemm_bf16_column_kernel (O and down projections with the residual add)",
+    others = (("gemm_column", "gemm_bf16_column_kernel (O) and gemm_bf16_unit_kernel<true> (down): the projections with the residual add",
                w_bytes - stream_bytes),)
     roofline["other_gemms"] = []
     for kind, label, nbytes in others:

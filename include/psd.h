@@ -240,7 +240,7 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_RMSNORM 1
 #define PSD_KIND_GEMM_F32 2
 #define PSD_KIND_GEMM_SKINNY 3       /* bf16 weight-streaming GEMM over packed 16 KB units, M <= 16 */
-#define PSD_KIND_GEMM_TILED 4        /* bf16 LDS-tiled GEMM, M > 16 */
+#define PSD_KIND_GEMM_TILED 4        /* LDS-tiled GEMM of bf16 models (fp16 MFMA), M > 16 */
 #define PSD_KIND_GEMM_REDUCE 5       /* split-K reduction */
 #define PSD_KIND_ROPE_APPEND 6
 #define PSD_KIND_ATTN 7
@@ -250,7 +250,7 @@ psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 #define PSD_KIND_ACCEPT_STATS 11
 #define PSD_KIND_ACCEPT_DRAW 12      /* first rejection + fp64 pass over the one position the draw reads */
 #define PSD_KIND_ACCEPT_LOCATE 13    /* greedy verification: the walk over the per-position argmax */
-#define PSD_KIND_GEMM_COLUMN 14      /* bf16 one-slot GEMM with the residual epilogue, M <= 16 */
+#define PSD_KIND_GEMM_COLUMN 14      /* bf16 GEMM with the residual epilogue (O, down), M <= 16 */
 #define PSD_KIND_GEMM_W4 15          /* 4-bit weight-only GEMM, M <= 16 */
 #define PSD_KIND_GEMM_SLOT 16        /* bf16 GEMM on 16-column tiles x K splits, M <= 16 (one partial slot, or unpacked weights) */
 #define PSD_KIND_COUNT 17

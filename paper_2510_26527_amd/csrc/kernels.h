@@ -61,11 +61,11 @@ struct GemmArgs {
     int splitk;
     float *reduced;               // if non-NULL: [M][N] <- sum over splits (logits), times the row scale if given
     // -- bf16, M <= kStreamMaxRows, packed weights only: RMSNorm folded into the projections around it -----------
-    // rmsnorm(x) W^T = r_m * ((x * gain) W^T) with r_m = rsqrt(mean_k x[m][k]^2 + eps).  The one-slot column
-    // kernel (selected by x_resid) adds its output into the residual stream x_resid [M][N], writes
+    // rmsnorm(x) W^T = r_m * ((x * gain) W^T) with r_m = rsqrt(mean_k x[m][k]^2 + eps).  A projection with x_resid
+    // set adds its output into the residual stream x_resid [M][N], writes
     // xg_out[m][n] = x_resid[m][n] * gain[n] (the operand of the next projection; gain = the next norm's)
-    // and sumsq_out[n / 16][m] = sum of x_resid[m][n]^2 over the block's 16 columns; the consumer of the next
-    // projection's output multiplies by r_m (RowScale).
+    // and sumsq_out[strip or tile][m] = sum of x_resid[m][n]^2 over the 16 (column kernel) or 64 (unit kernel)
+    // columns one block finishes; the consumer of the next projection's output multiplies by r_m (RowScale).
     float *x_resid;
     float *xg_out;
     const void *gain;             // [N] bf16
@@ -88,7 +88,7 @@ int gemm_stream_grid(int tiles, int K);
 int gemm_stream_slots(int tiles, int K);
 int gemm_resid_grid(int tiles, int K);
 int gemm_resid_slots(int tiles, int K);                          // partial slots of a projection run with tile_counter
-// strip_major: the layout of the one-slot column kernel (projections with N = d_model)
+// strip_major: the layout of the column kernel (the O projection)
 void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void *dst, bool strip_major, hipStream_t stream);
 // 4-bit weight-only quantised projections: q [n][K/2] bytes (low nibble = even k), scale bf16 [n][K/128],
 // zero u8 [n][K/128]; w = scale * (q - zero).  Each n[s] a multiple of 64.

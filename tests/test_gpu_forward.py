@@ -137,7 +137,7 @@ SMALL_G7 = synth.Shape(1, 896, 7, 1, 128, 1152, 2048, 1.0e6)          # Qwen2-li
 ])
 @pytest.mark.parametrize("pack", [False, True], ids=["rowmajor", "packed"])
 def test_bf16_small_models(shape, n_new, ctx, pack):
-    """Both weight layouts of the M <= 64 path (row-major split-K kernel, packed stream-K kernel).
+    """Both weight layouts of the M <= 16 path (row-major split-K kernel, packed stream-K kernels).
     Covers the skinny GEMM at 1-3 row tiles, the tiled GEMM (70, 130 rows), ragged N and M,
     attention with 1, 2 and 4 query tiles, several query chunks (7 x 17 rows), split counts from
     1 to 17 and a prefill with an empty cache.  std 0.05 keeps the signal above bf16 noise."""
