@@ -141,3 +141,102 @@ def forward(cfg: ModelConfig, weights: dict, tokens, kv: KVCache):
     kv.lens = kv.lens + R
     n = rmsnorm(x, widen(weights["final_norm"]), cfg.rms_eps)
     return n @ widen(weights["lm_head"]).T
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Token trees (Related Work, "Verification Mechanisms"; Sec. 4.6): one forward pass over every node of a drafted
+# tree.  Node 0 is the root (the last committed token); parents[i] < i is node i's parent.  A node sees the cache
+# and its own ancestors (itself included), and sits at position lens[b] + depth(node): exactly what an ordinary
+# forward pass over the root-to-node path would give it.
+
+def tree_depths(parents):
+    parents = list(parents)
+    if not parents or parents[0] != -1:
+        raise ValueError("node 0 is the root: parents[0] = -1")
+    depth = [0] * len(parents)
+    for i in range(1, len(parents)):
+        if not 0 <= parents[i] < i:
+            raise ValueError("parents must precede their children")
+        depth[i] = depth[parents[i]] + 1
+    return depth
+
+
+def tree_ancestors(parents):
+    """visible[i][j] = node j is node i or one of its ancestors."""
+    n = len(parents)
+    tree_depths(parents)
+    visible = np.zeros((n, n), bool)
+    for i in range(n):
+        j = i
+        while j >= 0:
+            visible[i, j] = True
+            j = parents[j]
+    return visible
+
+
+def attention_tree(q, k, v, n_past, visible):
+    """Attention of the R tree nodes of one sequence: node r reads the n_past cached positions and the new rows j
+    with visible[r][j].  q [R, h_q, d_h]; k, v [h_kv, n_past + R, d_h] with new row j at index n_past + j."""
+    R, h_q, d_h = q.shape
+    group = h_q // k.shape[0]
+    out = np.empty_like(q)
+    scale = 1.0 / np.sqrt(float(d_h))
+    for h in range(h_q):
+        kh, vh = k[h // group], v[h // group]
+        for r in range(R):
+            keys = np.concatenate([np.arange(n_past), n_past + np.nonzero(visible[r])[0]])
+            s = (kh[keys] @ q[r, h]) * scale
+            w = np.exp(s - np.max(s))
+            w = w / np.sum(w)
+            out[r, h] = w @ vh[keys]
+    return out
+
+
+def forward_tree(cfg: ModelConfig, weights: dict, tokens, parents, kv: KVCache):
+    """One forward pass over the nodes tokens [B, R] of a tree with the same shape for every sequence.  Node r's
+    K/V go to cache slot lens[b] + r (rotated for position lens[b] + depth(r)); lens advance by R; returns fp64
+    logits [B, R, V].  KVCache.compact_tree then keeps an accepted path."""
+    tokens = np.asarray(tokens)
+    B, R = tokens.shape
+    if len(parents) != R:
+        raise ValueError("one parent per node")
+    if np.any(kv.lens + R > kv.max_len):
+        raise ValueError("KV cache capacity exceeded")
+    depth = np.asarray(tree_depths(parents))
+    visible = tree_ancestors(parents)
+    h_q, h_kv, d_h = cfg.n_q_heads, cfg.n_kv_heads, cfg.d_head
+    x = widen(weights["embed"][tokens.reshape(-1).astype(np.int64)]).reshape(B, R, cfg.d_model)
+    for l in range(cfg.n_layers):
+        w = lambda name: widen(weights[f"l{l}.{name}"])
+        n = rmsnorm(x, w("attn_norm"), cfg.rms_eps)
+        q = (n @ w("wq").T).reshape(B, R, h_q, d_h)
+        k = (n @ w("wk").T).reshape(B, R, h_kv, d_h)
+        v = (n @ w("wv").T).reshape(B, R, h_kv, d_h)
+        a = np.empty((B, R, h_q, d_h))
+        for b in range(B):
+            s0 = int(kv.lens[b])
+            pos = s0 + depth
+            qb = rope(q[b], pos, cfg.rope_theta)
+            kb = rope(k[b], pos, cfg.rope_theta)
+            kv.k[l][b, :, s0:s0 + R] = kb.transpose(1, 0, 2)
+            kv.v[l][b, :, s0:s0 + R] = v[b].transpose(1, 0, 2)
+            a[b] = attention_tree(qb, widen(kv.k[l][b, :, :s0 + R]), widen(kv.v[l][b, :, :s0 + R]), s0, visible)
+        x = x + a.reshape(B, R, h_q * d_h) @ w("wo").T
+        n = rmsnorm(x, w("ffn_norm"), cfg.rms_eps)
+        x = x + (silu(n @ w("w_gate").T) * (n @ w("w_up").T)) @ w("w_down").T
+    kv.lens = kv.lens + R
+    n = rmsnorm(x, widen(weights["final_norm"]), cfg.rms_eps)
+    return n @ widen(weights["lm_head"]).T
+
+
+def compact_tree(kv: KVCache, base_lens, paths):
+    """After a tree forward that started at base_lens: keep the root and the accepted nodes paths[b] (root first,
+    root excluded) of every sequence as consecutive positions, drop the rest.  lens[b] = base + 1 + len(path)."""
+    base_lens = np.asarray(base_lens, np.int64)
+    for b, path in enumerate(paths):
+        s0 = int(base_lens[b])
+        for j, node in enumerate(path):
+            for l in range(len(kv.k)):
+                kv.k[l][b, :, s0 + 1 + j] = kv.k[l][b, :, s0 + node]
+                kv.v[l][b, :, s0 + 1 + j] = kv.v[l][b, :, s0 + node]
+    kv.lens = base_lens + 1 + np.asarray([len(p) for p in paths], np.int64)

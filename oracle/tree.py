@@ -36,7 +36,7 @@ def _draw(weights, u):
     return last
 
 
-def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0):
+def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0, tie_eps=1e-5, return_flags=False):
     """One verification of a drafted token tree.
 
     Nodes are numbered 0..n-1 in an order in which every parent precedes its children; node 0 is the root (the
@@ -48,7 +48,8 @@ def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0):
       tokens   [n]     drafted token of each node (tokens[0] is ignored)
       uniforms [n + 1] u[i] decides node i when it is tried (i >= 1; u[0] is unused), u[n] drives the one draw
     Returns (path, token): the accepted nodes from the root downwards (root excluded) and the token emitted after
-    them.  The step commits tokens[path[0]], ..., tokens[path[-1]], token."""
+    them.  The step commits tokens[path[0]], ..., tokens[path[-1]], token.  With return_flags a third value: bit 0
+    set when some tested uniform lay within tie_eps of its acceptance probability (a decision rounding could flip)."""
     p_logits = np.asarray(p_logits, np.float64)
     q_logits = np.asarray(q_logits, np.float64)
     n = p_logits.shape[0]
@@ -57,7 +58,7 @@ def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0):
         if not 0 <= parents[i] < i:
             raise ValueError("parents must precede their children")
         children[parents[i]].append(i)
-    path, node = [], 0
+    path, node, flags = [], 0, 0
     while True:
         r = _softmax(p_logits[node], temperature)          # what is left of the verifier's distribution here
         q = _softmax(q_logits[node], temperature)
@@ -65,6 +66,8 @@ def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0):
         for c in children[node]:
             x = int(tokens[c])
             ratio = np.inf if q[x] == 0.0 else r[x] / q[x]
+            if abs(uniforms[c] - min(1.0, ratio)) < tie_eps:
+                flags |= 1
             if uniforms[c] < min(1.0, ratio):
                 path.append(c)
                 node = c
@@ -75,4 +78,26 @@ def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0):
             if mass > 0.0:
                 r = rest / mass                            # (mass 0 means r == q, where no refusal can happen)
         if not descended:
-            return path, _draw(r, uniforms[n])
+            token = _draw(r, uniforms[n])
+            return (path, token, flags) if return_flags else (path, token)
+
+
+def tree_greedy_accept(p_logits, tokens, parents):
+    """Greedy matching on a tree (Related Work, "Verification Mechanisms"): at every node the verifier's most likely
+    token (lowest index among equals) is compared with the children's tokens; the first child that carries it is
+    descended into, and where none does that token is emitted.  Returns (path, token)."""
+    p_logits = np.asarray(p_logits, np.float64)
+    n = p_logits.shape[0]
+    children = [[] for _ in range(n)]
+    for i in range(1, n):
+        if not 0 <= parents[i] < i:
+            raise ValueError("parents must precede their children")
+        children[parents[i]].append(i)
+    path, node = [], 0
+    while True:
+        best = int(np.argmax(p_logits[node]))
+        nxt = next((c for c in children[node] if int(tokens[c]) == best), None)
+        if nxt is None:
+            return path, best
+        path.append(nxt)
+        node = nxt

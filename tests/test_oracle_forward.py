@@ -168,3 +168,72 @@ def test_gqa_equals_mha_with_repeated_kv_heads():
 def test_bf16_bit_patterns_are_widened_exactly():
     t = torch.randn(257, generator=torch.Generator().manual_seed(0)).to(torch.bfloat16)
     np.testing.assert_array_equal(fwd.widen(synth.as_numpy(t)), t.double().numpy())
+
+
+# ---- token trees: a node's row must be what an ordinary pass over its root-to-node path gives (pinned to forward(),
+# which is itself pinned to the library recompute above)
+
+TREES = {
+    "chain": [-1, 0, 1, 2, 3],
+    "binary": [-1, 0, 0, 1, 1, 2, 2],
+    "wide_then_deep": [-1, 0, 0, 0, 2, 4, 4, 5],
+}
+
+
+def _path(parents, node):
+    p = []
+    while node >= 0:
+        p.append(node)
+        node = parents[node]
+    return p[::-1]
+
+
+@pytest.mark.parametrize("name", list(TREES))
+def test_tree_forward_rows_equal_ordinary_forward_over_each_path(name):
+    parents = TREES[name]
+    cfg, w = _model(SMALL, seed=11)
+    past = synth.make_tokens(SMALL.vocab, (2, 6), 12)
+    nodes = synth.make_tokens(SMALL.vocab, (2, len(parents)), 13)
+    kv = fwd.KVCache(cfg, 2, 32)
+    fwd.forward(cfg, w, past[:, :6], kv)
+    kv.truncate([6, 4])                                           # ragged lengths
+    kv_tree = fwd.KVCache(cfg, 2, 32)
+    for l in range(cfg.n_layers):
+        kv_tree.k[l][:], kv_tree.v[l][:] = kv.k[l], kv.v[l]
+    kv_tree.lens = kv.lens.copy()
+    out = fwd.forward_tree(cfg, w, nodes, parents, kv_tree)
+    assert list(kv_tree.lens) == [6 + len(parents), 4 + len(parents)]
+    for node in range(len(parents)):
+        path = _path(parents, node)
+        fresh = fwd.KVCache(cfg, 2, 32)
+        for l in range(cfg.n_layers):
+            fresh.k[l][:], fresh.v[l][:] = kv.k[l], kv.v[l]
+        fresh.lens = kv.lens.copy()
+        ref = fwd.forward(cfg, w, nodes[:, path], fresh)[:, -1]
+        np.testing.assert_allclose(out[:, node], ref, atol=1e-11)
+    if name == "chain":                                           # one child per node: the ordinary pass itself
+        ref = fwd.forward(cfg, w, nodes, kv)
+        np.testing.assert_allclose(out, ref, atol=1e-12)
+
+
+def test_compacted_tree_cache_equals_the_cache_of_the_accepted_path():
+    parents = TREES["wide_then_deep"]
+    cfg, w = _model(SMALL, seed=14)
+    past = synth.make_tokens(SMALL.vocab, (2, 5), 15)
+    nodes = synth.make_tokens(SMALL.vocab, (2, len(parents)), 16)
+    nxt = synth.make_tokens(SMALL.vocab, (2, 3), 17)
+    paths = [[2, 4, 6], [3]]                                      # accepted nodes per sequence, root first, root excluded
+    kv = fwd.KVCache(cfg, 2, 32)
+    fwd.forward(cfg, w, past, kv)
+    base = kv.lens.copy()
+    fwd.forward_tree(cfg, w, nodes, parents, kv)
+    fwd.compact_tree(kv, base, paths)
+    assert list(kv.lens) == [5 + 4, 5 + 2]
+    out = fwd.forward(cfg, w, nxt, kv)
+    for b, path in enumerate(paths):
+        ref_kv = fwd.KVCache(cfg, 1, 32)
+        seq = np.concatenate([past[b], nodes[b, [0] + path], nxt[b]])
+        ref = fwd.forward(cfg, w, seq[None], ref_kv)[0, -3:]
+        np.testing.assert_allclose(out[b], ref, atol=1e-10)
+    with pytest.raises(ValueError):
+        fwd.forward_tree(cfg, w, nodes, [-1, 0, 3, 1, 1, 2, 2, 2], kv)   # a parent after its child

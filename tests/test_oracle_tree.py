@@ -135,3 +135,29 @@ def test_stream_decoded_by_tree_steps_follows_the_verifiers_markov_law():
     df = V * (V - 1)
     assert stats.chi2.sf(chi_p, df) > 1e-4, chi_p
     assert stats.chi2.sf(chi_q, df) < 1e-6, chi_q
+
+
+def test_greedy_tree_walk_is_greedy_decoding_and_reduces_to_the_linear_rule():
+    """Every accepted node carries its parent's most likely token, the emitted token is the most likely one at the
+    last node reached and no child there carries it; on a chain it is the linear greedy rule of oracle/accept.c."""
+    rng = np.random.default_rng(21)
+    V = 6
+    parents = [-1, 0, 0, 1, 1, 2, 2, 3]
+    for _ in range(300):
+        lp = rng.normal(0, 1, (8, V))
+        toks = rng.integers(0, V, 8)
+        path, tok = tree.tree_greedy_accept(lp, toks, parents)
+        node = 0
+        for c in path:
+            assert parents[c] == node and toks[c] == np.argmax(lp[node])
+            assert all(toks[d] != np.argmax(lp[node]) for d in range(1, c) if parents[d] == node)   # the first such child
+            node = c
+        assert tok == np.argmax(lp[node])
+        assert all(toks[d] != tok for d in range(1, 8) if parents[d] == node)
+    gamma = 5
+    for _ in range(200):
+        lp = rng.normal(0, 1, (gamma + 1, V))
+        x = rng.integers(0, V, gamma)
+        n, tok = accept.greedy_accept(lp[None], x[None])
+        path, t = tree.tree_greedy_accept(lp, np.concatenate([[0], x]), [-1] + list(range(gamma)))
+        assert path == list(range(1, n[0] + 1)) and t == tok[0]
