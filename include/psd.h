@@ -227,6 +227,50 @@ psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32
  * upper bound to new_len. */
 psd_status psd_kv_truncate_to(psd_kv *kv, int32_t new_len, void *hip_stream);
 
+/* ---- Token-tree verification (Related Work, "Verification Mechanisms": token-tree-based verification; Sec. 4.6:
+ * deeper / wider drafting).  A tree has n_nodes nodes numbered so that every parent precedes its children; node 0 is
+ * the root = the last committed token, not yet in the cache (the x* row of a linear step); parents_host is a HOST
+ * int32[n_nodes] with parents_host[0] = -1 and 0 <= parents_host[i] < i.  Every sequence of a call has the same shape.
+ *
+ * psd_model_forward_tree: psd_model_forward over the tree's nodes in one pass: node r reads the cache and its own
+ *   ancestors (itself included) among the new rows and sits at position lens[b] + depth(r), so its logits row is what
+ *   an ordinary pass over its root-to-node path would give.  tokens_dev: device int32[batch][n_nodes];
+ *   logits_out_dev: device fp32[batch][n_nodes][vocab] (every node gets a row).  Node r's K/V go to cache slot
+ *   lens[b] + r and the lengths advance by n_nodes: follow with psd_kv_compact_tree.  Workspace as for
+ *   psd_model_forward(batch, n_nodes).  Limits: n_nodes <= 32, a bf16 model with d_head 64 or 128 and
+ *   (n_q_heads / n_kv_heads) * n_nodes <= 32 (the attention kernel that builds its own operands); anything else
+ *   PSD_ERR_UNIMPLEMENTED; a malformed parents array PSD_ERR_SHAPE.
+ *
+ * psd_tree_accept: one verification of the tree per sequence.  The tokens of a node's children are taken to be
+ *   independent draws from softmax(q_logits[node] / T); at a node the children are tried in index order, child c with
+ *   token x accepted iff uniforms[c] < min(1, r[x] / q[x]) where r starts as softmax(p_logits[node] / T) and becomes
+ *   norm(max(0, r - q)) after every refusal; the first accepted child is descended into; where none is accepted (or
+ *   at a leaf) one token is drawn from r by inverse CDF in index order with uniforms[n_nodes].  With one child per
+ *   node this is psd_spec_accept.  temperature = 0: greedy matching (the first child that carries the verifier's most
+ *   likely token, lowest index among equals; q_logits and uniforms are not read).
+ *   p_logits / q_logits: device [rows][n_nodes][vocab] of `dtype` (strides in elements per sequence);
+ *   tokens_dev device int32[rows][n_nodes] (entry 0 unused); uniforms device fp32[rows][n_nodes + 1] (entry 0 unused).
+ *   Outputs (device): out_path_len[rows]; out_path[rows][n_nodes]: the accepted nodes root first, root excluded
+ *   (entries past the length are not written); out_token[rows]; out_flags[rows] or NULL (PSD_FLAG_NEAR_TIE as in
+ *   psd_spec_accept).  Everything that decides a token runs in fp64.  One block per sequence: a correctness-first
+ *   kernel, several passes over two logits rows per visited node.  Limits: n_nodes <= 64.  Needs no workspace.
+ *
+ * psd_kv_compact_tree: after the acceptance, for every sequence b with base = base_lens_dev[b] (the length before the
+ *   tree pass): the K/V rows of the accepted nodes move to slots base + 1 .. base + path_len[b] (the root stays at
+ *   base), and lens[b] <- min(lens[b], base + 1 + path_len[b], new_len_upper_bound).  path_dev: device
+ *   int32[batch][path_stride] as written by psd_tree_accept (path_stride >= n_nodes - 1); base_lens_dev must not be
+ *   the cache's own length array.  new_len_upper_bound as in psd_kv_truncate. */
+psd_status psd_model_forward_tree(psd_model *m, const int32_t *tokens_dev, int32_t n_nodes, const int32_t *parents_host,
+                                  psd_kv *kv, float *logits_out_dev, void *workspace, size_t ws_bytes, void *hip_stream);
+psd_status psd_tree_accept(const void *p_logits, const void *q_logits, const int32_t *tokens_dev,
+                           const int32_t *parents_host, int32_t n_nodes, const float *uniforms, float temperature,
+                           int32_t *out_path_len, int32_t *out_path, int32_t *out_token,
+                           int32_t rows, int32_t vocab, int32_t dtype, int64_t p_seq_stride, int64_t q_seq_stride,
+                           int32_t *out_flags, void *hip_stream);
+psd_status psd_kv_compact_tree(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *path_dev,
+                               const int32_t *path_len_dev, int32_t path_stride, int32_t n_nodes,
+                               int32_t new_len_upper_bound, void *hip_stream);
+
 /* ---- measurement aid (not part of the decoding path) -------------------------------------
  * Per-kernel timing with a start and a stop HIP event attached to each kernel dispatch (they
  * time the kernel itself, on the stream it is launched on), so that a bench can state each

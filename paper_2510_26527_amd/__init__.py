@@ -51,6 +51,9 @@ _SIGNATURES = {
                                       _vp, _vp]),
     "psd_kv_truncate": (_i32, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "psd_kv_truncate_to": (_i32, [_vp, _i32, _vp]),
+    "psd_model_forward_tree": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "psd_tree_accept": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _f32, _vp, _vp, _vp, _i32, _i32, _i32, _i64, _i64, _vp, _vp]),
+    "psd_kv_compact_tree": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp]),
     "psd_probe_stream_read": (_i32, [_vp, _sz, _vp, _i32, _vp]),
     "psd_probe_mfma": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "psd_profile_enable": (_i32, [_i32]),
@@ -205,6 +208,33 @@ def psd_kv_truncate(kv, base_lens_dev, keep_dev, keep_offset, new_len_upper_boun
 
 def psd_kv_truncate_to(kv, new_len, stream=None):
     _check(lib().psd_kv_truncate_to(kv, new_len, _stream_ptr(stream)), "psd_kv_truncate_to")
+
+
+def _host_i32(values):
+    """A host int32 array for a `*_host` argument (the caller keeps it alive for the call)."""
+    return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+
+
+def psd_model_forward_tree(model, tokens_dev, n_nodes, parents, kv, logits_out_dev, workspace, stream=None):
+    par = _host_i32(parents)
+    _check(lib().psd_model_forward_tree(model, _ptr(tokens_dev), n_nodes, ctypes.cast(par, ctypes.c_void_p), kv,
+                                        _ptr(logits_out_dev), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream_ptr(stream)), "psd_model_forward_tree")
+
+
+def psd_tree_accept(p_logits, q_logits, tokens_dev, parents, n_nodes, uniforms, temperature, out_path_len, out_path,
+                    out_token, rows, vocab, dtype, p_seq_stride, q_seq_stride, out_flags, stream=None):
+    par = _host_i32(parents)
+    _check(lib().psd_tree_accept(_ptr(p_logits), _ptr(q_logits), _ptr(tokens_dev), ctypes.cast(par, ctypes.c_void_p), n_nodes,
+                                 _ptr(uniforms), float(temperature), _ptr(out_path_len), _ptr(out_path), _ptr(out_token),
+                                 rows, vocab, dtype, p_seq_stride, q_seq_stride, _ptr(out_flags), _stream_ptr(stream)),
+           "psd_tree_accept")
+
+
+def psd_kv_compact_tree(kv, base_lens_dev, path_dev, path_len_dev, path_stride, n_nodes, new_len_upper_bound=-1,
+                        stream=None):
+    _check(lib().psd_kv_compact_tree(kv, _ptr(base_lens_dev), _ptr(path_dev), _ptr(path_len_dev), path_stride, n_nodes,
+                                     new_len_upper_bound, _stream_ptr(stream)), "psd_kv_compact_tree")
 
 
 def psd_probe_stream_read(src_dev, sink_dev, blocks, stream=None):

@@ -264,7 +264,7 @@ namespace {
 struct ForwardPlan {
     int M, width_qkv;
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
-    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, off_tilectr, total;
+    size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, off_tilectr, off_tree, total;
     size_t off_xn16, off_attn16, off_h16;
     bool half_copies;             // M > kStreamMaxRows, bf16: the producers also leave fp16 copies for the tiled projections
     bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
@@ -319,6 +319,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.off_sumsq = take(p.folded ? (size_t)(d.d_model / 16) * M * 4 : 0);
     p.off_rope = take(p.fused_rope ? (size_t)M * (d.d_head / 2) * sizeof(float2) : 0);
     p.off_tilectr = take(p.folded ? (size_t)gemm_pack_tiles(n_o, 1) * 4 : 0);
+    p.off_tree = take(p.fused_rope ? (size_t)kTreeMaxNodes * 8 : 0);      // ancestor masks and depths of a tree pass
     p.total = off;
     return p;
 }
@@ -361,7 +362,7 @@ size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_ne
 
 static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
                                float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
-                               void *hip_stream);
+                               void *hip_stream, const TreeShape *tree = nullptr);
 
 psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
                              float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
@@ -396,7 +397,7 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
 
 static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t n_new, psd_kv *kv,
                                float *logits_out_dev, int32_t n_logit_rows, void *workspace, size_t ws_bytes,
-                               void *hip_stream) {
+                               void *hip_stream, const TreeShape *tree) {
     const psd_model_desc &d = m->d;
     const int B = kv->batch;
     const int len_bound = kv->len_ub + n_new;
@@ -458,7 +459,17 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         }
     };
     RopeTable rt{};
-    if (p.fused_rope) rt = RopeTable{(float2 *)(ws + p.off_rope), kv->lens, n_new, d.d_head, d.rope_theta};
+    if (p.fused_rope) rt = RopeTable{(float2 *)(ws + p.off_rope), kv->lens, n_new, d.d_head, d.rope_theta, nullptr};
+    const uint32_t *tree_anc = nullptr;
+    if (tree) {
+        // a token tree: positions by depth, visibility by ancestry (both only exist in the fused attention build)
+        if (!p.fused_rope) return PSD_ERR_UNIMPLEMENTED;
+        uint32_t *anc = (uint32_t *)(ws + p.off_tree);
+        int32_t *depth = (int32_t *)(anc + kTreeMaxNodes);
+        launch_tree_setup(*tree, anc, depth, st);
+        rt.depth = depth;
+        tree_anc = anc;
+    }
     launch_embed_norm(d.dtype, m->embed(), tokens_dev, x, norm_gain(0), xn, p.folded ? sumsq : nullptr, M, d.d_model,
                       d.vocab, d.rms_eps, rt, xn16, ZeroFill{tile_ctr, p.folded ? gemm_pack_tiles(n_o_fw, 1) : 0}, st);
     rs.tiles = 1;
@@ -470,7 +481,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
             launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, rs, q, kl, vl, kv->lens, B, n_new, d.n_q_heads,
                                       d.n_kv_heads, d.d_head, kv->max_len, d.rope_theta, st);
         AttnArgs a{};
-        if (p.fused_rope) { a.qkv_partial = partial; a.qkv_splits = p.sk_qkv; a.rs = rs; a.rope_cs = rt.cs; }
+        if (p.fused_rope) { a.qkv_partial = partial; a.qkv_splits = p.sk_qkv; a.rs = rs; a.rope_cs = rt.cs; a.tree_anc = tree_anc; }
         a.q = q; a.k = kl; a.v = vl; a.lens = kv->lens; a.out = attn; a.out16 = attn16;
         a.B = B; a.R = n_new; a.h_q = d.n_q_heads; a.h_kv = d.n_kv_heads; a.d_h = d.d_head; a.max_len = kv->max_len;
         a.len_bound = len_bound; a.part_o = (float *)(ws + p.off_po); a.part_ml = (float *)(ws + p.off_pml);
@@ -603,6 +614,75 @@ psd_status psd_kv_truncate(psd_kv *kv, const int32_t *base_lens_dev, const int32
     const int cap = new_len_upper_bound < 0 || new_len_upper_bound > kv->len_ub ? kv->len_ub : new_len_upper_bound;
     (void)hipGetLastError();
     launch_truncate(kv->lens, base_lens_dev, keep_dev, keep_offset, cap, kv->batch, (hipStream_t)hip_stream);
+    const psd_status s = check_launch();
+    if (s == PSD_OK) kv->len_ub = cap;
+    return s;
+}
+
+// host-side check of a tree's parent array and its ancestor masks / depths
+static bool tree_shape_from_parents(const int32_t *parents, int n, int max_nodes, TreeShape *ts) {
+    if (!parents || n < 1 || n > max_nodes || parents[0] != -1) return false;
+    for (int i = 1; i < n; ++i)
+        if (parents[i] < 0 || parents[i] >= i) return false;
+    if (ts) {
+        ts->n = n;
+        for (int i = 0; i < n; ++i) {
+            ts->anc[i] = (i ? ts->anc[parents[i]] : 0u) | (1u << i);
+            ts->depth[i] = i ? ts->depth[parents[i]] + 1 : 0;
+        }
+    }
+    return true;
+}
+
+psd_status psd_model_forward_tree(psd_model *m, const int32_t *tokens_dev, int32_t n_nodes, const int32_t *parents_host,
+                                  psd_kv *kv, float *logits_out_dev, void *workspace, size_t ws_bytes, void *hip_stream) {
+    if (!m || !tokens_dev || !kv || !logits_out_dev || !parents_host) return PSD_ERR_NULL;
+    if (kv->m != m) return PSD_ERR_SHAPE;
+    const int B = kv->batch;
+    TreeShape ts{};
+    if (!forward_shape_ok(m, B, n_nodes) || !tree_shape_from_parents(parents_host, n_nodes, kTreeMaxNodes, &ts)) return PSD_ERR_SHAPE;
+    if (kv->len_ub + n_nodes > kv->max_len) return PSD_ERR_CAPACITY;
+    if (m->w4 && (!m->packed || B * n_nodes > kStreamMaxRows)) return PSD_ERR_UNIMPLEMENTED;
+    return forward_once(m, tokens_dev, n_nodes, kv, logits_out_dev, n_nodes, workspace, ws_bytes, hip_stream, &ts);
+}
+
+psd_status psd_tree_accept(const void *p_logits, const void *q_logits, const int32_t *tokens_dev, const int32_t *parents_host,
+                           int32_t n_nodes, const float *uniforms, float temperature, int32_t *out_path_len,
+                           int32_t *out_path, int32_t *out_token, int32_t rows, int32_t vocab, int32_t dtype,
+                           int64_t p_seq_stride, int64_t q_seq_stride, int32_t *out_flags, void *hip_stream) {
+    if (dtype != PSD_F32 && dtype != PSD_BF16) return PSD_ERR_DTYPE;
+    if (rows < 0 || vocab <= 0 || vocab > (1 << 23)) return PSD_ERR_SHAPE;
+    if (!tree_shape_from_parents(parents_host, n_nodes, kTreeMaxAcceptNodes, nullptr)) return PSD_ERR_SHAPE;
+    if (!(temperature >= 0.f) || !std::isfinite(temperature)) return PSD_ERR_TEMPERATURE;
+    const bool greedy = temperature == 0.f;
+    if (rows == 0) return PSD_OK;
+    if (!p_logits || !tokens_dev || !out_path_len || !out_path || !out_token) return PSD_ERR_NULL;
+    if (!greedy && (!q_logits || !uniforms)) return PSD_ERR_NULL;
+    if (greedy) { q_logits = p_logits; q_seq_stride = p_seq_stride; }        // never read
+    if (p_seq_stride < (int64_t)n_nodes * vocab || q_seq_stride < (int64_t)n_nodes * vocab) return PSD_ERR_SHAPE;
+    const size_t es = elem_size(dtype);
+    if ((uintptr_t)p_logits % es || (uintptr_t)q_logits % es) return PSD_ERR_SHAPE;
+    TreeAcceptArgs a{};
+    a.p = p_logits; a.q = q_logits; a.p_stride = p_seq_stride; a.q_stride = q_seq_stride;
+    a.tokens = tokens_dev; a.uniforms = uniforms; a.temperature = temperature;
+    a.out_path_len = out_path_len; a.out_path = out_path; a.out_token = out_token; a.out_flags = out_flags;
+    a.rows = rows; a.n_nodes = n_nodes; a.vocab = vocab;
+    for (int i = 0; i < n_nodes; ++i) a.parents[i] = parents_host[i];
+    (void)hipGetLastError();
+    launch_tree_accept(dtype, a, (hipStream_t)hip_stream);
+    return check_launch();
+}
+
+psd_status psd_kv_compact_tree(psd_kv *kv, const int32_t *base_lens_dev, const int32_t *path_dev, const int32_t *path_len_dev,
+                               int32_t path_stride, int32_t n_nodes, int32_t new_len_upper_bound, void *hip_stream) {
+    if (!kv || !base_lens_dev || !path_dev || !path_len_dev) return PSD_ERR_NULL;
+    if (n_nodes < 1 || n_nodes > kTreeMaxNodes || path_stride < n_nodes - 1) return PSD_ERR_SHAPE;
+    if (base_lens_dev == kv->lens) return PSD_ERR_SHAPE;                       // the lengths are rewritten while blocks read the base
+    const psd_model_desc &d = kv->m->d;
+    const int cap = new_len_upper_bound < 0 || new_len_upper_bound > kv->len_ub ? kv->len_ub : new_len_upper_bound;
+    (void)hipGetLastError();
+    launch_kv_compact_tree(d.dtype, kv->k, kv->v, kv->lens, base_lens_dev, path_dev, path_len_dev, path_stride, n_nodes,
+                           d.n_layers, kv->batch, d.n_kv_heads, d.d_head, kv->max_len, cap, (hipStream_t)hip_stream);
     const psd_status s = check_launch();
     if (s == PSD_OK) kv->len_ub = cap;
     return s;

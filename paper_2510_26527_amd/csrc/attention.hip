@@ -20,6 +20,7 @@
 // the second MFMA needs (keys are numbered kb + 8g + 4t + v so that the two 16-key score tiles
 // of a lane are 8 consecutive keys).
 #include <cstdlib>
+#include <type_traits>
 #include "common.h"
 #include "kernels.h"
 #include "prof.h"
@@ -305,12 +306,22 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
     // holds d_head elements [g*DH/4, (g+1)*DH/4), k-step s the 8 starting at 8*s inside them.
     bf16x8 qh[QT][KS], ql[QT][KS];
     int limit[QT];                   // last key this lane's query may see, -1 for a padding column
+    uint32_t own_rows[QT];           // token tree: which rows of this step the query sees (bit j = row j); else unused
+    uint32_t new_mask[QT];           // the mask in force for the tile being consumed: zero for cache tiles
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const int qi = (qchunk * QT + qt) * 16 + i;
         const bool valid = qi < NQ;
         const int hl = valid ? qi / a.R : 0, r = valid ? qi % a.R : 0;
         limit[qt] = valid ? S_b + r : -1;
+        own_rows[qt] = 0u;
+        new_mask[qt] = 0u;
+        if constexpr (FUSED) {
+            if (a.tree_anc) {        // a node sees the cache and its ancestors among the step's rows
+                limit[qt] = valid ? S_b - 1 : -1;
+                own_rows[qt] = valid ? a.tree_anc[r] : 0u;
+            }
+        }
         const float *qp = FUSED ? &s_q[qt * 16 + i][g * (DH / 4)]
                                 : a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
 #pragma unroll
@@ -332,7 +343,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
     }
 
     // one 32-key sub-tile: keys kb .. kb + 31, of which those below n_end exist; ka / va are its operands
-    auto consume = [&](int kb, int n_end, bf16x8 (&ka)[2][KS], bf16x8 (&va)[DT]) {
+    // (own_tile: the step's own rows, where a token tree's ancestor mask applies; a compile-time flag so that the
+    // loop over the cache keeps the plain causal test)
+    auto consume = [&](auto own_tile, int kb, int n_end, bf16x8 (&ka)[2][KS], bf16x8 (&va)[DT]) {
         if (kb + 32 > n_end) {          // stale cache rows may hold anything, even NaN: zero them
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
@@ -375,7 +388,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int key = kb + 8 * g + 4 * t + v;
-                    const float sc = key <= limit[qt] && key < n_end ? c[qt][t][v] * scale_log2 : -INFINITY;
+                    bool seen = key <= limit[qt];
+                    if constexpr (decltype(own_tile)::value) seen = seen || ((new_mask[qt] >> ((key - kb) & 31)) & 1u);
+                    const float sc = seen && key < n_end ? c[qt][t][v] * scale_log2 : -INFINITY;
                     c[qt][t][v] = sc;
                     tmax = fmaxf(tmax, sc);
                 }
@@ -423,7 +438,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = kt + sub * 32;
             if (kb >= kb1) break;
-            consume(kb, n_keys, ka[sub], va[sub]);
+            consume(std::false_type{}, kb, n_keys, ka[sub], va[sub]);
         }
     }
     if constexpr (FUSED) {
@@ -437,7 +452,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
             }
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) va[0][dt] = *reinterpret_cast<const bf16x8 *>(&s_vt[dt * 16 + i][8 * g]);
-            consume(S_b, S_b + a.R, ka[0], va[0]);
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) new_mask[qt] = own_rows[qt];
+            consume(std::true_type{}, S_b, S_b + a.R, ka[0], va[0]);
         }
     }
 

@@ -118,23 +118,51 @@ struct AttnArgs {
     int qkv_splits;
     RowScale rs;
     const float2 *rope_cs;
+    // Token tree (fused build only): tree_anc[r] has bit j set when row j of the step is row r itself or one of its
+    // ancestors; row r then sees the cache and exactly those rows.  NULL: rows see the rows before them.
+    const uint32_t *tree_anc;
 };
 // whether launch_attention builds its operands itself for this shape (then no rotation / append kernel runs before it)
 bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h);
 int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound);
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 
+// ---------------------------------------------------------------- token trees (tree.hip)
+constexpr int kTreeMaxNodes = 32;          // nodes of a tree forward pass (root included): one 32-key tile of new rows
+constexpr int kTreeMaxAcceptNodes = 64;    // nodes of a tree acceptance call
+struct TreeShape {
+    uint32_t anc[kTreeMaxNodes];  // bit j of anc[r]: node j is node r or one of its ancestors
+    int32_t depth[kTreeMaxNodes];
+    int n;
+};
+void launch_tree_setup(const TreeShape &ts, uint32_t *anc, int32_t *depth, hipStream_t stream);
+struct TreeAcceptArgs {
+    const void *p, *q;            // [rows][n_nodes][vocab] logits (strides in elements per sequence), q unused when greedy
+    int64_t p_stride, q_stride;
+    const int32_t *tokens;        // [rows][n_nodes], tokens[.][0] unused
+    const float *uniforms;        // [rows][n_nodes + 1]
+    float temperature;            // 0: greedy matching
+    int32_t *out_path_len, *out_path, *out_token, *out_flags;   // [rows], [rows][n_nodes], [rows], [rows] or NULL
+    int rows, n_nodes, vocab;
+    int32_t parents[kTreeMaxAcceptNodes];
+};
+void launch_tree_accept(int dtype, const TreeAcceptArgs &a, hipStream_t stream);
+void launch_kv_compact_tree(int dtype, void *k, void *v, int32_t *lens, const int32_t *base, const int32_t *path,
+                            const int32_t *path_len, int path_stride, int n_nodes, int L, int B, int h_kv, int d_h,
+                            int max_len, int cap, hipStream_t stream);
+
 // ---------------------------------------------------------------- measured ceilings (ceilings.hip)
 void launch_probe_read(const void *src, size_t bytes, void *sink, int blocks, hipStream_t stream);
 void launch_probe_mfma(const void *seed, void *sink, int blocks, int iters, hipStream_t stream);
 
 // ---------------------------------------------------------------- row-wise kernels (rowwise.hip)
-// optional by-product of the embedding kernel: cs[m][i] = (cos, sin) of (lens[m / R] + m % R) * theta^(-2i/d_h)
+// optional by-product of the embedding kernel: cs[m][i] = (cos, sin) of (the position of row m) * theta^(-2i/d_h)
 struct RopeTable {
     float2 *cs;                   // [M][d_h/2], NULL: not wanted
     const int32_t *lens;
     int R, d_h;
     float theta;
+    const int32_t *depth;         // token tree: row r sits at position lens[b] + depth[r]; NULL: lens[b] + r
 };
 struct ZeroFill {
     unsigned *words;              // n 32-bit words set to zero by the first kernel of a forward pass (NULL / 0: none)

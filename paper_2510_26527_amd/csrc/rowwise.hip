@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kRowThreads) void residual_norm_kernel(const TW *em
         // (cos, sin) of this row's position at every rotation frequency, once per forward pass for all layers;
         // the angle position * theta^(-2i/d_h) is evaluated in fp64
         if (rt.cs && tid < rt.d_h / 2) {
-            const int pos = rt.lens[m / rt.R] + m % rt.R;
+            const int pos = rt.lens[m / rt.R] + (rt.depth ? rt.depth[m % rt.R] : m % rt.R);
             const double inv_freq = exp2(-2.0 * (double)tid / (double)rt.d_h * log2((double)rt.theta));
             double sn, cs;
             sincos((double)pos * inv_freq, &sn, &cs);

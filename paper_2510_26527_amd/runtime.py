@@ -121,6 +121,32 @@ def forward(model: Model, kv: KVCache, tokens, n_logit_rows=None, logits_out=Non
     return logits_out
 
 
+def forward_tree(model: Model, kv: KVCache, tokens, parents, logits_out=None, stream=None):
+    """tokens int32 [B, n_nodes] on the device, parents a host sequence (parents[0] = -1, parents[i] < i) ->
+    fp32 logits [B, n_nodes, V]."""
+    B, n = tokens.shape
+    if logits_out is None:
+        logits_out = torch.empty((B, n, model.shape.vocab), dtype=torch.float32, device=model.device)
+    ws = model.workspace(B, n, kv.max_len)
+    psd.psd_model_forward_tree(model.handle, tokens, n, parents, kv.handle, logits_out, ws, stream)
+    return logits_out
+
+
+def tree_accept(p_logits, q_logits, tokens, parents, uniforms, temperature=1.0, stream=None):
+    """p, q [rows, n_nodes, V] (same dtype; q may be None when temperature is 0), tokens int32 [rows, n_nodes],
+    uniforms fp32 [rows, n_nodes + 1] -> (path_len [rows], path [rows, n_nodes], token [rows], flags [rows]) int32."""
+    rows, n, V = p_logits.shape
+    dev = p_logits.device
+    out_len = torch.empty(rows, dtype=torch.int32, device=dev)
+    out_path = torch.full((rows, n), -1, dtype=torch.int32, device=dev)
+    out_tok = torch.empty(rows, dtype=torch.int32, device=dev)
+    out_flags = torch.empty(rows, dtype=torch.int32, device=dev)
+    psd.psd_tree_accept(p_logits, q_logits, tokens, parents, n, uniforms, temperature, out_len, out_path, out_tok, rows, V,
+                        psd.dtype_code(p_logits.dtype), p_logits.stride(0), q_logits.stride(0) if q_logits is not None else 0,
+                        out_flags, stream)
+    return out_len, out_path, out_tok, out_flags
+
+
 class Acceptor:
     """Output tensors and workspace of psd_spec_accept, reused across calls."""
 
