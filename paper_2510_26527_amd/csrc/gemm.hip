@@ -28,6 +28,7 @@
 // (splitk >= 1); the consumer
 // (the fused row-wise kernels, or gemm_splitk_reduce_kernel for the logits) adds them in split
 // order, so results are bit-reproducible.
+#include <type_traits>
 #include "common.h"
 #include "kernels.h"
 #include "prof.h"
@@ -724,7 +725,6 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 constexpr int kBK = 64, kLdsStride = 72, kMaxNB = 8;
 constexpr int kTallRows = 160;                           // from this many rows on: 256-row blocks
-constexpr size_t kTiledLds = (size_t)(256 + 32 * kMaxNB) * kLdsStride * sizeof(uint16_t);
 inline int tiled_block_rows(int M) { return M >= kTallRows ? 256 : 128; }
 
 // 8 bf16 (as stored) -> 8 fp16, exact for every value the fp16 grid holds
@@ -750,9 +750,12 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
     constexpr int BM = 64 * MW, BN = 32 * NB, NH = NB / 2, NT = MW * 128;
     constexpr int XCH = BM * 8 / NT;                        // 16-byte chunks of the fp16 X tile per thread (BM x 64)
     constexpr int WCH = BN * 8 / NT;                        // 16-byte chunks of the W tile per thread (BN x 64 bf16)
+    // MW == 4 has the CU to itself and LDS for two sets of tiles: the next K tile is stored into the other set in
+    // the middle of this tile's MFMAs (one barrier per K tile, no phase in which the matrix cores wait for the
+    // stores).  MW == 2 keeps one set: two blocks share the CU and overlap each other's barriers.
+    constexpr bool DB = MW == 4;
+    constexpr int kSet = (BM + BN) * kLdsStride;            // elements of one set of tiles
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_tiled[];
-    uint16_t *Xs = lds_tiled;                               // activation tile, fp16
-    uint16_t *Ws = Xs + BM * kLdsStride;                    // weight tile, fp16
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * (BN / 2);   // this wavefront's corner of the block tile
@@ -783,22 +786,31 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
         woff[c] = row * kLdsStride + col;
     }
     const bool have16 = g.x16 != nullptr;
-    u32x4 xr[XCH], wr[WCH];
-    auto load_tiles = [&](int kt) {
+    // Register stages of the global -> LDS path.  What one CU keeps in flight bounds its load rate (bytes in flight /
+    // latency), and one K tile per block is too little of it: with two sets of LDS tiles the block also keeps two
+    // K tiles in flight in registers (stage = tile parity), except at the widest tile where the registers run out.
+    constexpr int NST = (DB && NB <= 6) ? 2 : 1;
+    u32x4 xr[NST][XCH], wr[NST][WCH];
+    auto load_tiles = [&](auto stage, int kt) {
+        constexpr int st = decltype(stage)::value;
 #pragma unroll
         for (int c = 0; c < XCH; ++c) {
-            if (have16) xr[c] = *reinterpret_cast<const u32x4 *>(g.x16 + xsrc[c] + kt * kBK);
-            else xr[c] = f32x8_to_f16x8(load_f32x8(g.x + xsrc[c] + kt * kBK));
+            if (have16) xr[st][c] = *reinterpret_cast<const u32x4 *>(g.x16 + xsrc[c] + kt * kBK);
+            else xr[st][c] = f32x8_to_f16x8(load_f32x8(g.x + xsrc[c] + kt * kBK));
         }
 #pragma unroll
-        for (int c = 0; c < WCH; ++c) wr[c] = *reinterpret_cast<const u32x4 *>(W + wsrc[c] + kt * kBK);
+        for (int c = 0; c < WCH; ++c) wr[st][c] = *reinterpret_cast<const u32x4 *>(W + wsrc[c] + kt * kBK);
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](auto stage, int set) {
+        constexpr int st = decltype(stage)::value;
+        uint16_t *Xs = lds_tiled + set * kSet, *Ws = Xs + BM * kLdsStride;     // activation tile, weight tile (fp16)
 #pragma unroll
-        for (int c = 0; c < XCH; ++c) *reinterpret_cast<u32x4 *>(&Xs[xoff[c]]) = xr[c];
+        for (int c = 0; c < XCH; ++c) *reinterpret_cast<u32x4 *>(&Xs[xoff[c]]) = xr[st][c];
 #pragma unroll
-        for (int c = 0; c < WCH; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = bf16x8_to_f16x8(wr[c]);
+        for (int c = 0; c < WCH; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = bf16x8_to_f16x8(wr[st][c]);
     };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, NST - 1>;      // the second stage, or the only one
 
     f32x16 acc[2][NH];
 #pragma unroll
@@ -808,31 +820,61 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    if (k0 < k1) {
-        load_tiles(k0);
-        store_tiles();
-    }
-    __syncthreads();
-    for (int kt = k0; kt < k1; ++kt) {
-        if (kt + 1 < k1) load_tiles(kt + 1);             // in flight while this tile is multiplied
+    auto multiply = [&](int set, int ks) {
+        const uint16_t *Xs = lds_tiled + set * kSet, *Ws = Xs + BM * kLdsStride;
+        f16x8 fa[2], fb[NH];
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            f16x8 fa[2], fb[NH];
+        for (int a = 0; a < 2; ++a)
+            fa[a] = *reinterpret_cast<const f16x8 *>(&Xs[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-                fa[a] = *reinterpret_cast<const f16x8 *>(&Xs[(wm + a * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
+        for (int b = 0; b < NH; ++b)
+            fb[b] = *reinterpret_cast<const f16x8 *>(&Ws[(wn + b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int b = 0; b < NH; ++b)
-                fb[b] = *reinterpret_cast<const f16x8 *>(&Ws[(wn + b * 32 + li) * kLdsStride + ks * 16 + lg * 8]);
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < NH; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    };
+    if (k0 < k1) {
+        load_tiles(S0{}, k0);
+        store_tiles(S0{}, 0);
+        if constexpr (NST == 2) {
+            // tile t travels in stage (t - k0) & 1
+            if (k0 + 1 < k1) load_tiles(S1{}, k0 + 1);
+            if (k0 + 2 < k1) load_tiles(S0{}, k0 + 2);
+        } else if (DB && k0 + 1 < k1) {
+            load_tiles(S0{}, k0 + 1);
         }
-        __syncthreads();
-        if (kt + 1 < k1) store_tiles();
-        __syncthreads();
+    }
+    __syncthreads();
+    if constexpr (DB) {
+        // one K tile: half its MFMAs, the next tile from its registers into the other LDS set, the registers refilled
+        // with the tile NST ahead, the other half, one barrier (tile kt + 1 visible; this set free for tile kt + 2)
+        auto k_tile = [&](auto next_stage, int kt) {
+            const int set = (kt - k0) & 1;
+            multiply(set, 0);
+            multiply(set, 1);
+            if (kt + 1 < k1) store_tiles(next_stage, set ^ 1);
+            if (kt + 1 + NST < k1) load_tiles(next_stage, kt + 1 + NST);
+            multiply(set, 2);
+            multiply(set, 3);
+            __syncthreads();
+        };
+        int kt = k0;
+        for (; kt + 1 < k1; kt += 2) {
+            k_tile(S1{}, kt);                                // tile kt + 1 has odd parity
+            k_tile(S0{}, kt + 1);
+        }
+        if (kt < k1) k_tile(S1{}, kt);
+    } else {
+        for (int kt = k0; kt < k1; ++kt) {
+            if (kt + 1 < k1) load_tiles(S0{}, kt + 1);       // in flight while this tile is multiplied
+#pragma unroll
+            for (int ks = 0; ks < kBK / 16; ++ks) multiply(0, ks);
+            __syncthreads();
+            if (kt + 1 < k1) store_tiles(S0{}, 0);
+            __syncthreads();
+        }
     }
     // acc[a][b][v] = y[m_base + wm + a*32 + 8*(v/4) + 4*lg + v%4][row0 + wn + b*32 + li]
 #pragma unroll
@@ -1016,9 +1058,10 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         auto go = [&](auto kernel) {
             // opt in to more than 64 KB of dynamic LDS: a property of the function on the current device, set before
             // every launch (a cheap host call) so that no process-wide flag has to remember who set it where
+            const size_t lds = (size_t)(bm + 32 * nb) * kLdsStride * sizeof(uint16_t) * (bm == 256 ? 2 : 1);
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)kTiledLds);
-            launch_kernel(kernel, grid, bm * 2, kTiledLds, stream, g);
+                                      (int)lds);
+            launch_kernel(kernel, grid, bm * 2, lds, stream, g);
         };
         if (bm == 256) {
             if (nb == 4) go(gemm_f16_tiled_kernel<4, 4>);
