@@ -115,7 +115,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten plain 1 GiB device-to-device copies (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
-    ap.add_argument("--workload", choices=["verify", "stress", "chain", "sweep", "ceilings"], default="verify",
+    ap.add_argument("--workload", choices=["verify", "stress", "chain", "sweep", "ceilings", "tree"], default="verify",
                     help="verify (default): configs[2] verify step + configs[1] acceptance, the headline line; "
                          "stress: configs[4], 16 sequences x 16 rows of a Qwen2-7B-shaped model; "
                          "chain: configs[3], the full-size three-level chain with the agreement harness; "
@@ -157,6 +157,8 @@ def main():
         return sweep_workload(args, dev)
     if args.workload == "ceilings":
         return ceilings_workload(args, dev)
+    if args.workload == "tree":
+        return tree_workload(args, dev)
 
     shape, gamma, ctx, max_len, temperature = synth.LLAMA2_7B, 8, 1024, 1088, 1.0
     w_cpu = synth.make_weights(shape, 3, torch.bfloat16)
@@ -352,6 +354,77 @@ def main():
         "ceilings": ceilings,
         "attention": attention,
         "roofline": roofline, "cpu_baseline": cpu_baseline, "accept_kernel": accept, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+def tree_workload(args, dev):
+    """A token-tree verify step at the headline shape: LLaMA2-7B-shaped model, 1024-token cache, one binary tree of
+    depth 3 (root + 14 drafted nodes) per step: forward over the tree, acceptance down the tree, compaction of the
+    accepted path.  The drafter is synthetic (q = p + N(0, 0.5^2), children drawn from q at their parent)."""
+    import torch
+    import paper_2510_26527_amd as psd
+    from paper_2510_26527_amd import runtime, synth
+    shape, ctx, max_len = synth.LLAMA2_7B, 1024, 1088
+    parents = [-1] + [(i - 1) // 2 for i in range(1, 15)]
+    n = len(parents)
+    model = runtime.Model(shape, synth.make_weights(shape, 3, torch.bfloat16), dev).pack()
+    kv = runtime.KVCache(model, 1, max_len)
+    ks, vs = synth.make_kv_fill(shape, 1, ctx, 4, torch.bfloat16)
+    kv.load(ks, vs, ctx)
+    tokens = torch.from_numpy(synth.make_tokens(shape.vocab, (1, n), 33)).to(dev)
+    p_buf = torch.empty((1, n, shape.vocab), dtype=torch.float32, device=dev)
+    base = torch.full((1,), ctx, dtype=torch.int32, device=dev)
+    runtime.forward_tree(model, kv, tokens, parents, logits_out=p_buf)
+    psd.psd_kv_truncate_to(kv.handle, ctx)
+    g = torch.Generator(device=dev).manual_seed(7)
+    q_logits = p_buf + 0.5 * torch.randn(p_buf.shape, generator=g, device=dev)
+    gum = -torch.log(-torch.log(torch.rand(p_buf.shape, generator=g, device=dev).clamp_min(1e-12)))
+    for i in range(1, n):                                  # children: draws from the drafter's row at their parent
+        tokens[0, i] = torch.argmax(q_logits[0, parents[i]] + gum[0, i]).to(torch.int32)
+    runtime.forward_tree(model, kv, tokens, parents, logits_out=p_buf)      # the verifier's rows for those tokens
+    psd.psd_kv_truncate_to(kv.handle, ctx)
+    uniforms = synth.make_uniforms((1, n + 1), 6, dev)
+    out = {}
+
+    def step():
+        runtime.forward_tree(model, kv, tokens, parents, logits_out=p_buf)
+        ln, path, tok, fl = runtime.tree_accept(p_buf, q_logits, tokens, parents, uniforms, 1.0)
+        psd.psd_kv_compact_tree(kv.handle, base, path, ln, n, n, ctx + n)
+        psd.psd_kv_truncate_to(kv.handle, ctx)
+        out["len"] = ln
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    prof_steps = min(args.steps, 20)
+    psd.psd_profile_enable((40 * shape.n_layers + 64) * prof_steps)
+    for _ in range(prof_steps):
+        step()
+    prof = psd.psd_profile_collect()
+    psd.psd_profile_enable(0)
+    kernels = {k: {"launches_per_step": c / prof_steps, "avg_us": 1e3 * t / c, "ms_per_step": t / prof_steps}
+               for k, (t, c) in prof.items() if c}
+    kept = []
+    for i in range(32):                                    # committed tokens per step over steps that differ in their uniforms
+        u_i = synth.make_uniforms((1, n + 1), 1000 + i, dev)
+        ln, _, _, _ = runtime.tree_accept(p_buf, q_logits, tokens, parents, u_i, 1.0)
+        kept.append(int(ln.item()) + 1)
+    line = {
+        "metric": "tree verify-step nodes/s (7B shape, binary tree of 15 nodes, ctx 1k)", "value": n * 1e3 / ms,
+        "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "LLaMA2-7B-shaped random-init bf16, batch 1, a 15-node binary token tree per step on a "
+                               "1024-token cache: tree forward + tree acceptance + compaction", "n_nodes": n, "kv_len": ctx},
+        "accepted_path_len_this_step": int(out["len"].item()),
+        "mean_tokens_committed_per_step": sum(kept) / len(kept),
+        "expected_committed_tokens/s": sum(kept) / len(kept) * 1e3 / ms,
+        "kernels": kernels,
     }
     print(json.dumps(line))
 
