@@ -673,7 +673,8 @@ def sweep_workload(args, dev):
                       "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
                       "config": {"workload": "two LLaMA2-7B-shaped layers + lm_head, one forward of M rows on an empty cache",
                                  "weights_GB": 2.0 * params / 1e9},
-                      "note": "useful flops; up to 16 rows: bf16 weights streamed against hi + lo bf16 activations; above: one fp16 MFMA pass"sweep": rows}))
+                      "note": "useful flops; up to 16 rows: bf16 weights streamed against hi + lo bf16 activations; above: one fp16 MFMA pass",
+                      "sweep": rows}))
 
 
 if __name__ == "__main__":
