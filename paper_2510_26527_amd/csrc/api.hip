@@ -280,9 +280,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.width_qkv = hd + 2 * kvd;
     const int n_qkv[3] = {hd, kvd, kvd}, n_o[1] = {d.d_model}, n_gu[2] = {d.d_ffn, d.d_ffn}, n_v[1] = {d.vocab};
     const int Ml = batch * n_logit_rows;
-    // 4-bit models run unfolded: their projections with N = d_model are split along K over several blocks, so no
-    // block owns an output column and the residual add + norm is the stand-alone kernel's
-    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows && !mdl->w4;
+    p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
         if (mdl->w4 && n != n_v) return gemm_w4_splits(K, n, nseg);
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
@@ -290,10 +288,11 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     };
     p.fused_rope = attn_fuses_rope(d.dtype, n_new, d.n_q_heads, d.n_kv_heads, d.d_head);
     p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
-    p.sk_o = p.folded ? 1 : splits(M, hd, d.d_model, n_o, 1);
+    // folded: O runs on the column kernel (one owner per output), or, 4-bit, split along K with the arrival epilogue
+    p.sk_o = p.folded && !mdl->w4 ? 1 : splits(M, hd, d.d_model, n_o, 1);
     p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
     // folded: the down projection runs on the unit kernel with the residual epilogue, its partials in slots
-    p.sk_down = p.folded ? gemm_resid_slots(gemm_pack_tiles(n_o, 1), d.d_ffn) : splits(M, d.d_ffn, d.d_model, n_o, 1);
+    p.sk_down = p.folded && !mdl->w4 ? gemm_resid_slots(gemm_pack_tiles(n_o, 1), d.d_ffn) : splits(M, d.d_ffn, d.d_model, n_o, 1);
     p.sk_head = Ml > 0 ? splits(Ml, d.d_model, d.vocab, n_v, 1) : 1;
     p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
     const size_t act = 4;                                    // activations are fp32 for both dtypes
@@ -448,11 +447,12 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         if (p.folded) {
             GemmArgs g{};
             g.wpack = wpack; g.x = xin; g.x_rows_per_group = M; g.w[0] = w; g.n[0] = d.d_model; g.nseg = 1;
-            g.M = M; g.K = K; g.N = d.d_model; g.splitk = by_units ? sk : 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
+            const bool slots = by_units || m->w4;         // partial slots + arrival epilogue, else one block per 16 columns
+            g.M = M; g.K = K; g.N = d.d_model; g.splitk = slots ? sk : 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
             g.x_resid = x; g.xg_out = xn; g.gain = next_gain; g.sumsq_out = sumsq; g.w4 = m->w4;
-            if (by_units) { g.tile_counter = tile_ctr; g.partial = partial; }
+            if (slots) { g.tile_counter = tile_ctr; g.partial = partial; }
             launch_gemm(d.dtype, g, st);
-            rs.tiles = by_units ? g.pack_tiles : col_tiles;
+            rs.tiles = slots ? g.pack_tiles : col_tiles;
         } else {
             gemm(xin, M, K, w, d.d_model, nullptr, 0, nullptr, 0, sk, partial, wpack);
             launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, xn16, st);

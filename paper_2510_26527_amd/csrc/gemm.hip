@@ -270,6 +270,58 @@ __host__ __device__ __forceinline__ long range_owner(long u, long U, long P) { r
 
 constexpr int kUnitRing = 2;                       // units in flight per wavefront (its 4 KB of each)
 
+// The residual epilogue of one 64-column output tile that several blocks contributed partial sums to.  The calling
+// thread holds, for column `col` of the tile (the 64 lanes of its wavefront = the tile's 64 columns), this block's
+// sums of rows row0, row0 + rstep, ...: it publishes them in partial slot `slot` with agent-scope stores, waits for
+// them, and the block counts itself in on the tile's counter.  Whichever block arrives last adds the tile's
+// n_contrib slots in slot order (so the sum does not depend on who that was), adds into the residual stream, writes
+// the gain-scaled copy and the rows' sums of squares over the tile, and leaves the counter at zero for the next
+// launch.  No block waits for another.  Every thread of the block must call it (it synchronises the block).
+template <int NR>
+__device__ __forceinline__ void resid_tile_finish(const GemmArgs &g, int tile, int slot, int n_contrib, const float (&mine)[NR],
+                                                  int row0, int rstep, bool col_ok, size_t col, int *s_last) {
+    bool last = true;
+    if (n_contrib > 1) {                                        // the same for the whole block
+        if (col_ok)
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                if (row0 + r * rstep < g.M)
+                    __hip_atomic_store(&g.partial[((size_t)slot * g.M + row0 + r * rstep) * g.N + col], mine[r],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            *s_last = __hip_atomic_fetch_add(&g.tile_counter[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                      (unsigned)(n_contrib - 1);
+        __syncthreads();
+        last = *s_last != 0;
+    }
+    if (!last) return;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const int tok = row0 + r * rstep;
+        float v = 0.f, sq = 0.f;
+        if (tok < g.M && col_ok) {
+            if (n_contrib > 1) {
+                for (int sl = 0; sl < n_contrib; ++sl)
+                    v += __hip_atomic_load(&g.partial[((size_t)sl * g.M + tok) * g.N + col], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                v = mine[r];
+            }
+            const size_t o = (size_t)tok * g.N + col;
+            v += g.x_resid[o];
+            g.x_resid[o] = v;
+            if (g.xg_out) g.xg_out[o] = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
+            sq = v * v;
+        }
+        sq = wave_sum(sq);                                      // the tile's 64 columns of row tok sit in this wavefront
+        if ((threadIdx.x & 63) == 0 && tok < g.M && g.sumsq_out) g.sumsq_out[(size_t)tile * g.M + tok] = sq;
+    }
+    if (n_contrib > 1 && threadIdx.x == 0)
+        __hip_atomic_store(&g.tile_counter[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Block b streams the contiguous units [range_begin(b), range_begin(b + 1)); wavefront q multiplies the q-th 4 KB of
 // every unit (K offsets (q>>1)*64 + (q&1)*8 + 16 gq of the unit's 128), so the four wavefronts of a block read 16 KB
 // in one piece and the blocks of the grid adjacent ranges: the access pattern of a plain streaming read.  Weights
@@ -363,47 +415,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_unit_kernel(GemmArgs g) {
                         const int tok = q + 4 * r;
                         mine[r] = ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
                     }
-                    bool last = true;
-                    if (n_contrib > 1) {                                        // the same for the whole block
-                        if (row_ok)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r)
-                                if (q + 4 * r < g.M)
-                                    __hip_atomic_store(&g.partial[((size_t)slot * g.M + q + 4 * r) * g.N + col], mine[r],
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                        __syncthreads();
-                        if (threadIdx.x == 0)
-                            s_last = __hip_atomic_fetch_add(&g.tile_counter[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                                     (unsigned)(n_contrib - 1);
-                        __syncthreads();
-                        last = s_last != 0;
-                    }
-                    if (last) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int tok = q + 4 * r;
-                            float v = 0.f, sq = 0.f;
-                            if (tok < g.M && row_ok) {
-                                if (n_contrib > 1) {
-                                    for (int sl = 0; sl < n_contrib; ++sl)
-                                        v += __hip_atomic_load(&g.partial[((size_t)sl * g.M + tok) * g.N + col], __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                                } else {
-                                    v = mine[r];
-                                }
-                                const size_t o = (size_t)tok * g.N + col;
-                                v += g.x_resid[o];
-                                g.x_resid[o] = v;
-                                if (g.xg_out) g.xg_out[o] = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
-                                sq = v * v;
-                            }
-                            sq = wave_sum(sq);                                  // the tile's 64 columns of row tok sit in this wavefront
-                            if (lane == 0 && tok < g.M && g.sumsq_out) g.sumsq_out[(size_t)tile * g.M + tok] = sq;
-                        }
-                        if (n_contrib > 1 && threadIdx.x == 0)
-                            __hip_atomic_store(&g.tile_counter[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
+                    resid_tile_finish<4>(g, tile, slot, n_contrib, mine, q, 4, row_ok, col, &s_last);
                 } else if (row_ok) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -619,6 +631,7 @@ struct W4Step {
     f32x8 x[4];                     // activations of token i, K offsets of quarter q
 };
 
+template <bool RESID>
 __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
@@ -697,14 +710,22 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
         for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][v];
     __syncthreads();
     // thread t of pass p: column t & 63 of the tile, token (t >> 6) + 8 p
+    const int cn = threadIdx.x & 63;
+    const int col = blockIdx.x * kW4Cols + cn;
+    float mine[2];
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-        const int cn = threadIdx.x & 63, emm = (threadIdx.x >> 6) + 8 * pass;
-        const int col = blockIdx.x * kW4Cols + cn;
+        const int emm = (threadIdx.x >> 6) + 8 * pass;
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < kW4Waves; ++w) v += red[w][cn][emm];
-        if (emm < g.M && col < g.N) g.partial[((size_t)blockIdx.y * g.M + emm) * g.N + col] = v;
+        mine[pass] = v;
+        if (!RESID && emm < g.M && col < g.N) g.partial[((size_t)blockIdx.y * g.M + emm) * g.N + col] = v;
+    }
+    if constexpr (RESID) {
+        // the projections that write the residual stream: the K split that arrives last at this tile finishes it
+        __shared__ int s_last;
+        resid_tile_finish<2>(g, blockIdx.x, blockIdx.y, g.splitk, mine, threadIdx.x >> 6, 8, col < g.N, (size_t)col, &s_last);
     }
 }
 
@@ -1025,7 +1046,10 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
     }
     if (g.M <= kStreamMaxRows && g.wpack && g.w4) {
         ScopedProf sp(PSD_KIND_GEMM_W4, stream);
-        launch_kernel(gemm_w4_tile_kernel, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
+        if (g.x_resid && g.tile_counter)
+            launch_kernel(gemm_w4_tile_kernel<true>, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
+        else
+            launch_kernel(gemm_w4_tile_kernel<false>, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
         return;
     }
     if (g.M <= kStreamMaxRows && g.wpack && g.x_resid && g.tile_counter) {
