@@ -531,16 +531,21 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
 
 // Many query rows per KV head (grouped-query verify at batch, prefill): the four wavefronts of a
 // block own different 16-row query tiles and all walk the same keys, so K and V^T tiles are staged in
-// LDS once per block (16-byte global loads, next tile prefetched into registers during the MFMAs) and
-// read from there as MFMA operands; K/V leave HBM once for up to 128 query rows.  No cross-wavefront
-// merge is needed: each wavefront finishes its own query rows.
+// LDS once per block and read from there as MFMA operands; K/V leave HBM once for up to 128 query rows.  No
+// cross-wavefront merge is needed: each wavefront finishes its own query rows.
+// Everything enters the matrix cores as fp16, one product each: cache entries are bf16, which converts to fp16
+// exactly (on the way into LDS; magnitudes outside fp16's range would not, none occur in a decoder's K / V), and
+// the queries and the softmax weights are rounded to fp16 (11 significant bits).  That halves the MFMAs of a
+// bf16 high + low pair and frees the registers for what bounds this kernel, the bytes a CU keeps in flight: two
+// 64-key tiles travel in registers (stage = tile parity) while a third is multiplied, and the next tile is stored
+// into the second set of LDS tiles in the middle of the current one's MFMAs (one barrier per tile).
 template <int DH, int QW>
 __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float scale_log2, int range) {
     constexpr int KS = DH / 32, DT = DH / 16;
-    constexpr int KSTRIDE = DH + 8;            // bf16 elements per staged K row (+16 B: conflict-free reads)
-    constexpr int VSTRIDE = 64 + 8;            // bf16 elements per staged V^T row
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * KSTRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[DH * VSTRIDE];
+    constexpr int KSTRIDE = DH + 8;            // fp16 elements per staged K row (+16 B: conflict-free reads)
+    constexpr int VSTRIDE = 64 + 8;            // fp16 elements per staged V^T row
+    constexpr int kSetElems = 64 * KSTRIDE + DH * VSTRIDE;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds_wide[];      // two sets of (K tile, V^T tile)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int split = blockIdx.x, qchunk = blockIdx.y;
@@ -554,7 +559,7 @@ __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float s
     const uint16_t *Kc = (const uint16_t *)a.k + ((size_t)b * a.h_kv + hk) * max_len * DH;
     const uint16_t *Vt = (const uint16_t *)a.v + ((size_t)b * a.h_kv + hk) * DH * max_len;
 
-    bf16x8 qh[QW][KS], ql[QW][KS];
+    f16x8 qf[QW][KS];
     int limit[QW];
     size_t out_row[QW];
 #pragma unroll
@@ -569,7 +574,7 @@ __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float s
         for (int s = 0; s < KS; ++s) {
             f32x8 v = load_f32x8(qp + 8 * s);
             if (!valid) v = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            split_bf16(v, &qh[qt][s], &ql[qt][s]);
+            qf[qt][s] = __builtin_bit_cast(f16x8, f32x8_to_f16x8(v));
         }
     }
     f32x4 o[QW][DT];
@@ -584,12 +589,13 @@ __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float s
 
     // staging: K tile 64 keys x DH (DH/8 chunks of 16 B per key), V^T tile DH rows x 64 keys (8 chunks per row)
     constexpr int KCH = 64 * DH / 8 / 256, VCH = DH * 8 / 256;
-    u32x4 kreg[KCH], vreg[VCH];
-    auto load_tile = [&](int kt) {
+    u32x4 kreg[2][KCH], vreg[2][VCH];
+    auto load_tile = [&](auto stage, int kt) {
+        constexpr int st = decltype(stage)::value;
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
             const int chunk = tid + c * 256, key = chunk / (DH / 8), col = (chunk % (DH / 8)) * 8;
-            kreg[c] = *reinterpret_cast<const u32x4 *>(Kc + (size_t)(kt + key) * DH + col);     // kt + 64 <= max_len
+            kreg[st][c] = *reinterpret_cast<const u32x4 *>(Kc + (size_t)(kt + key) * DH + col);     // kt + 64 <= max_len
         }
 #pragma unroll
         for (int c = 0; c < VCH; ++c) {
@@ -603,118 +609,122 @@ __global__ __launch_bounds__(256) void attn_mfma_wide_kernel(AttnArgs a, float s
                     else if (key + 1 >= n_keys) raw[e] &= 0xffffu;
                 }
             }
-            vreg[c] = raw;
+            vreg[st][c] = raw;
         }
     };
-    auto store_tile = [&]() {
+    auto store_tile = [&](auto stage, int set) {
+        constexpr int st = decltype(stage)::value;
+        uint16_t *Ks = lds_wide + set * kSetElems, *Vs = Ks + 64 * KSTRIDE;
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
             const int chunk = tid + c * 256, key = chunk / (DH / 8), col = (chunk % (DH / 8)) * 8;
-            *reinterpret_cast<u32x4 *>(&Ks[key * KSTRIDE + col]) = kreg[c];
+            *reinterpret_cast<u32x4 *>(&Ks[key * KSTRIDE + col]) = bf16x8_to_f16x8(kreg[st][c]);
         }
 #pragma unroll
         for (int c = 0; c < VCH; ++c) {
             const int chunk = tid + c * 256, d = chunk >> 3, col = (chunk & 7) * 8;
-            *reinterpret_cast<u32x4 *>(&Vs[d * VSTRIDE + col]) = vreg[c];
+            *reinterpret_cast<u32x4 *>(&Vs[d * VSTRIDE + col]) = bf16x8_to_f16x8(vreg[st][c]);
         }
     };
-
-    if (kb0 < kb1) {
-        load_tile(kb0);
-        store_tile();
-    }
-    __syncthreads();
-    for (int kt = kb0; kt < kb1; kt += 64) {
-        if (kt + 64 < kb1) load_tile(kt + 64);
+    // 32 keys kb .. kb + 31 of the tile in LDS set `set` (sub = which half of the tile)
+    auto multiply = [&](int set, int sub, int kb) {
+        const uint16_t *Ks = lds_wide + set * kSetElems, *Vs = Ks + 64 * KSTRIDE;
+        f16x8 ka[2][KS], va[DT];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int kb = kt + sub * 32;
-            if (kb >= kb1) break;
-            bf16x8 ka[2][KS], va[DT];
+        for (int t = 0; t < 2; ++t) {
+            const int key = sub * 32 + 8 * (i >> 2) + 4 * t + (i & 3);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int key = sub * 32 + 8 * (i >> 2) + 4 * t + (i & 3);
+            for (int s = 0; s < KS; ++s)
+                ka[t][s] = *reinterpret_cast<const f16x8 *>(&Ks[key * KSTRIDE + g * (DH / 4) + 8 * s]);
+        }
 #pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    ka[t][s] = *reinterpret_cast<const bf16x8 *>(&Ks[key * KSTRIDE + g * (DH / 4) + 8 * s]);
-            }
+        for (int dt = 0; dt < DT; ++dt)
+            va[dt] = *reinterpret_cast<const f16x8 *>(&Vs[(dt * 16 + i) * VSTRIDE + sub * 32 + 8 * g]);
+        // scores of every query tile first, MFMAs interleaved over independent accumulators
+        f32x4 c[QW][2];
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                va[dt] = *reinterpret_cast<const bf16x8 *>(&Vs[(dt * 16 + i) * VSTRIDE + sub * 32 + 8 * g]);
-            // scores of every query tile first, MFMAs interleaved over independent accumulators
-            f32x4 c[QW][2];
+        for (int qt = 0; qt < QW; ++qt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) c[qt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
 #pragma unroll
             for (int qt = 0; qt < QW; ++qt)
 #pragma unroll
-                for (int t = 0; t < 2; ++t) c[qt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-#pragma unroll
-                for (int qt = 0; qt < QW; ++qt)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], qh[qt][s], c[qt][t], 0, 0, 0);
-#pragma unroll
-                for (int qt = 0; qt < QW; ++qt)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][s], ql[qt][s], c[qt][t], 0, 0, 0);
-            }
-            bf16x8 ph[QW], pl[QW];
-#pragma unroll
-            for (int qt = 0; qt < QW; ++qt) {
-                // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
-                float tmax = -INFINITY;
-#pragma unroll
                 for (int t = 0; t < 2; ++t)
+                    c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qf[qt][s], c[qt][t], 0, 0, 0);
+        f16x8 pf[QW];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int key = kb + 8 * g + 4 * t + v;
-                        const float sc = key <= limit[qt] ? c[qt][t][v] * scale_log2 : -INFINITY;
-                        c[qt][t][v] = sc;
-                        tmax = fmaxf(tmax, sc);
-                    }
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-                const float mnew = fmaxf(mrun[qt], tmax);
-                float p[8];
-                if (mnew > -INFINITY) {
-                    const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
-                    float ps = 0.f;
+        for (int qt = 0; qt < QW; ++qt) {
+            // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
+            float tmax = -INFINITY;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
-                        ps += p[e];
-                    }
-                    lrun[qt] = lrun[qt] * alpha + ps;
-                    if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                    }
-                    mrun[qt] = mnew;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) p[e] = 0.f;
+                for (int v = 0; v < 4; ++v) {
+                    const int key = kb + 8 * g + 4 * t + v;
+                    const float sc = key <= limit[qt] ? c[qt][t][v] * scale_log2 : -INFINITY;
+                    c[qt][t][v] = sc;
+                    tmax = fmaxf(tmax, sc);
                 }
-                split_bf16(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}, &ph[qt], &pl[qt]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float mnew = fmaxf(mrun[qt], tmax);
+            float p[8];
+            if (mnew > -INFINITY) {
+                const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+                float ps = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
+                    ps += p[e];
+                }
+                lrun[qt] = lrun[qt] * alpha + ps;
+                if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                }
+                mrun[qt] = mnew;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] = 0.f;
             }
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int qt = 0; qt < QW; ++qt)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], ph[qt], o[qt][dt], 0, 0, 0);
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int qt = 0; qt < QW; ++qt)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pl[qt], o[qt][dt], 0, 0, 0);
+            pf[qt] = __builtin_bit_cast(f16x8, f32x8_to_f16x8(f32x8{p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]}));
         }
-        __syncthreads();
-        if (kt + 64 < kb1) store_tile();
-        __syncthreads();
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int qt = 0; qt < QW; ++qt)
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pf[qt], o[qt][dt], 0, 0, 0);
+    };
+
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    if (kb0 < kb1) {                             // tile t (t-th of this block) travels in stage t & 1
+        load_tile(S0{}, kb0);
+        store_tile(S0{}, 0);
+        if (kb0 + 64 < kb1) load_tile(S1{}, kb0 + 64);
+        if (kb0 + 128 < kb1) load_tile(S0{}, kb0 + 128);
     }
+    __syncthreads();
+    // one tile: its first 32 keys, the next tile from its registers into the other LDS set, those registers refilled
+    // with the tile three ahead, the other 32 keys, one barrier (next tile visible; this set free for the one after)
+    auto k_tile = [&](auto next_stage, int kt) {
+        const int set = ((kt - kb0) >> 6) & 1;
+        multiply(set, 0, kt);
+        if (kt + 64 < kb1) store_tile(next_stage, set ^ 1);
+        if (kt + 192 < kb1) load_tile(next_stage, kt + 192);
+        if (kt + 32 < kb1) multiply(set, 1, kt + 32);
+        __syncthreads();
+    };
+    int kt = kb0;
+    for (; kt + 64 < kb1; kt += 128) {
+        k_tile(S1{}, kt);
+        k_tile(S0{}, kt + 64);
+    }
+    if (kt < kb1) k_tile(S1{}, kt);
 
     // each wavefront writes its own query rows: lane (query i, group g) holds d = dt*16 + 4g + v
 #pragma unroll
@@ -807,8 +817,14 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
         dim3 wgrid(a.splits, (NQ + rows - 1) / rows, a.B * a.h_kv);
         {
             ScopedProf sp(PSD_KIND_ATTN, stream);
-            if (rows == 64) launch_kernel(attn_mfma_wide_kernel<DH, 1>, wgrid, 256, 0, stream, a, scale_log2, range);
-            else launch_kernel(attn_mfma_wide_kernel<DH, 2>, wgrid, 256, 0, stream, a, scale_log2, range);
+            // two sets of (64 keys x (DH + 8), DH x (64 + 8)) fp16 tiles: more than the 64 KB a kernel gets unasked at d_head 128
+            const size_t lds = 2 * (size_t)(64 * (DH + 8) + DH * 72) * sizeof(uint16_t);
+            auto go = [&](auto kernel) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                launch_kernel(kernel, wgrid, 256, lds, stream, a, scale_log2, range);
+            };
+            if (rows == 64) go(attn_mfma_wide_kernel<DH, 1>);
+            else go(attn_mfma_wide_kernel<DH, 2>);
         }
         if (a.splits > 1) {
             ScopedProf sp(PSD_KIND_ATTN_COMBINE, stream);

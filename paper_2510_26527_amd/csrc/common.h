@@ -53,6 +53,24 @@ __device__ __forceinline__ float load_elem(const uint16_t *p, size_t i) { return
 __device__ __forceinline__ void store_elem(float *p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void store_elem(uint16_t *p, size_t i, float v) { p[i] = (uint16_t)f32_to_bf16_bits(v); }
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+// 8 bf16 (as stored) -> 8 fp16, exact for every value the fp16 grid holds
+__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[e] << 16), __uint_as_float(w[e] & 0xffff0000u));
+        r[e] = __builtin_bit_cast(uint32_t, h);
+    }
+    return r;
+}
+// 8 fp32 -> 8 fp16, round to nearest even
+__device__ __forceinline__ u32x4 f32x8_to_f16x8(const f32x8 &x) {
+    const f16x8 h = __builtin_convertvector(x, f16x8);
+    return __builtin_bit_cast(u32x4, h);
+}
+
 template <typename T>
 __device__ __forceinline__ T wave_max(T v) {
 #pragma unroll

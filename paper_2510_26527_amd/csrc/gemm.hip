@@ -743,26 +743,9 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
 // two blocks per CU: one block's staging and barriers overlap the other's MFMAs.
 // The tile width and the K split are chosen per projection by the host so that the number of blocks comes
 // close to a multiple of the 512 block slots.
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 constexpr int kBK = 64, kLdsStride = 72, kMaxNB = 8;
 constexpr int kTallRows = 160;                           // from this many rows on: 256-row blocks
 inline int tiled_block_rows(int M) { return M >= kTallRows ? 256 : 128; }
-
-// 8 bf16 (as stored) -> 8 fp16, exact for every value the fp16 grid holds
-__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
-    u32x4 r;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[e] << 16), __uint_as_float(w[e] & 0xffff0000u));
-        r[e] = __builtin_bit_cast(uint32_t, h);
-    }
-    return r;
-}
-// 8 fp32 -> 8 fp16, round to nearest even
-__device__ __forceinline__ u32x4 f32x8_to_f16x8(const f32x8 &x) {
-    const f16x8 h = __builtin_convertvector(x, f16x8);
-    return __builtin_bit_cast(u32x4, h);
-}
 
 // MW = wavefront rows of the block: 2 (128 activation rows, 256 threads, two blocks per CU) or 4 (256 rows, 512
 // threads, one block per CU: each weight tile then leaves L2 once for 256 rows instead of twice).
