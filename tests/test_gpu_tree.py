@@ -195,3 +195,44 @@ def test_whole_tree_step_on_a_small_model():
     nxt = np.stack([np.concatenate([[int(out_tok[b])], synth.make_tokens(shape.vocab, (3,), 40 + b)]) for b in range(batch)])
     p.step(nxt.astype(np.int32), what="step after the tree")
     p.close()
+
+
+def test_degenerate_trees():
+    """A root alone (nothing drafted): the pass is an ordinary one-row step and the acceptance call is one draw from the
+    verifier's row; a star (every node a child of the root): one level, up to 31 refusals against the running residual."""
+    shape = SMALL_MHA
+    p = Pair(shape, torch.bfloat16, 2, 128, seed=9, ctx=40, lens=[40, 17], std=0.05, pack=True)
+    toks = synth.make_tokens(shape.vocab, (2, 1), 3).astype(np.int32)
+    out = runtime.forward_tree(p.model, p.kv, torch.from_numpy(toks).cuda(), [-1])
+    ref = ofwd.forward(p.cfg, p.w, toks, p.okv)
+    check_logits(out, ref, torch.bfloat16, "root alone")
+    u = torch.rand((2, 2), generator=torch.Generator().manual_seed(1))
+    ln, path, tok, fl = runtime.tree_accept(out, out, torch.from_numpy(toks).cuda(), [-1], u.cuda(), 1.0)
+    torch.cuda.synchronize()
+    lg = out.cpu().double().numpy()
+    for b in range(2):
+        opath, otok = otree.tree_accept(lg[b], lg[b], toks[b], [-1], u[b].double().numpy(), 1.0)
+        assert int(ln[b]) == 0 and opath == [] and int(tok[b]) == otok
+    p.close()
+    parents = [-1] + [0] * 31
+    _, pl, ql, tk, uu = _accept_case(12, "full32", 2000, torch.float32, 77, 1.0)
+    out_len, out_path, out_tok, out_flags = runtime.tree_accept(pl.cuda(), ql.cuda(), tk.cuda(), parents, uu.cuda(), 1.0)
+    torch.cuda.synchronize()
+    for r in range(12):
+        path, tok, flags = otree.tree_accept(pl[r].double().numpy(), ql[r].double().numpy(), tk[r].numpy(), parents,
+                                             uu[r].double().numpy(), 1.0, return_flags=True)
+        if flags & 1 or int(out_flags[r]) & psd.PSD_FLAG_NEAR_TIE:
+            continue
+        assert out_path[r, :int(out_len[r])].cpu().tolist() == path and int(out_tok[r]) == tok
+
+
+def test_tree_forward_on_a_4bit_model():
+    parents = TREES["binary7"]
+    n = len(parents)
+    p = Pair(SMALL_GQA, torch.bfloat16, 2, 192, seed=4, ctx=100, std=0.05, w4=True)
+    toks = synth.make_tokens(SMALL_GQA.vocab, (2, n), 5).astype(np.int32)
+    out = runtime.forward_tree(p.model, p.kv, torch.from_numpy(toks).cuda(), parents)
+    torch.cuda.synchronize()
+    ref = ofwd.forward_tree(p.cfg, p.w, toks, parents, p.okv)
+    print("rel err", check_logits(out, ref, torch.bfloat16, "4-bit tree rows"))
+    p.close()
