@@ -143,6 +143,51 @@ def test_spec_accept_validation(lib):
     assert call(rows=0) == psd.PSD_OK                     # nothing to do, nothing launched
 
 
+def test_tree_calls_validation(lib):
+    """Malformed trees and arguments are refused on the host, before anything is launched."""
+    def par(vals):
+        return ctypes.cast((ctypes.c_int32 * len(vals))(*vals), ctypes.c_void_p)
+    acc = lib.psd_tree_accept
+    P, Q, X, U, LN, PA, TK = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000, 0x70000
+
+    def call(parents=(-1, 0, 0, 1), n=4, temp=1.0, rows=2, V=1000, dtype=psd.PSD_F32, p=P, q=Q, x=X, u=U, ps=None, qs=None,
+             ln=LN, pa=PA, tk=TK):
+        ps = n * V if ps is None else ps
+        qs = n * V if qs is None else qs
+        return acc(p, q, x, par(list(parents)), n, u, temp, ln, pa, tk, rows, V, dtype, ps, qs, 0, 0)
+
+    assert call(parents=(0, 0, 0, 1)) == psd.PSD_ERR_SHAPE           # no root
+    assert call(parents=(-1, 0, 3, 1)) == psd.PSD_ERR_SHAPE          # a parent after its child
+    assert call(parents=(-1, 0, -1, 1)) == psd.PSD_ERR_SHAPE         # two roots
+    assert call(parents=[-1] + [0] * 64, n=65) == psd.PSD_ERR_SHAPE  # more than 64 nodes
+    assert call(n=0, parents=(-1,)) == psd.PSD_ERR_SHAPE
+    assert call(temp=-0.5) == psd.PSD_ERR_TEMPERATURE
+    assert call(dtype=9) == psd.PSD_ERR_DTYPE
+    assert call(V=0) == psd.PSD_ERR_SHAPE
+    assert call(ps=100) == psd.PSD_ERR_SHAPE
+    assert call(q=0) == psd.PSD_ERR_NULL
+    assert call(u=0) == psd.PSD_ERR_NULL
+    assert call(pa=0) == psd.PSD_ERR_NULL
+    assert call(rows=0) == psd.PSD_OK                                # nothing to do, nothing launched
+    m = _create(_desc())
+    kv = ctypes.c_void_p()
+    assert lib.psd_kv_create(m, 1, 128, 0x1000, 0x2000, 0x3000, 100, ctypes.byref(kv)) == psd.PSD_OK
+    need = psd.psd_model_workspace_bytes(m, 1, 8, 128)
+    f = lib.psd_model_forward_tree
+    assert f(m, 0x4000, 3, par([-1, 0, 2]), kv, 0x5000, 0x10000, need, 0) == psd.PSD_ERR_SHAPE       # parent == child
+    assert f(m, 0x4000, 3, par([-1, 0, 0]), kv, 0, 0x10000, need, 0) == psd.PSD_ERR_NULL            # every node gets a row
+    assert f(m, 0x4000, 33, par([-1] + [0] * 32), kv, 0x5000, 0x10000, need, 0) == psd.PSD_ERR_SHAPE   # more than 32 nodes
+    assert f(m, 0x4000, 30, par([-1] + [0] * 29), kv, 0x5000, 0x10000, need, 0) == psd.PSD_ERR_CAPACITY  # 100 + 30 > 128
+    assert f(m, 0x4000, 3, par([-1, 0, 0]), kv, 0x5000, 0x10000, 16, 0) == psd.PSD_ERR_WORKSPACE
+    c = lib.psd_kv_compact_tree
+    assert c(kv, 0, 0x2000, 0x3000, 8, 8, -1, 0) == psd.PSD_ERR_NULL
+    assert c(kv, 0x1000, 0x2000, 0x3000, 3, 8, -1, 0) == psd.PSD_ERR_SHAPE       # path rows shorter than n_nodes - 1
+    assert c(kv, 0x1000, 0x2000, 0x3000, 40, 40, -1, 0) == psd.PSD_ERR_SHAPE     # more than 32 nodes
+    assert c(kv, 0x3000, 0x2000, 0x4000, 8, 8, -1, 0) == psd.PSD_ERR_SHAPE       # the cache's own length array as the base
+    psd.psd_kv_destroy(kv)
+    psd.psd_model_destroy(m)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The build has no multi-GPU path: bench.py says so and exits before touching a device."""
     import subprocess
