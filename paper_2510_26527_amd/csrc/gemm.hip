@@ -12,22 +12,24 @@
 //                            units of a GEMM are contiguous, and the grid is persistent: each block streams
 //                            an equal, contiguous range of units (stream-K), its four wavefronts on the four
 //                            K quarters of every unit, and writes one partial per tile it touches.
-//   gemm_bf16_column_kernel  M <= 16, the projections that write the residual stream: one block per 16
-//                            output columns over the whole K range; the residual add, the gain-scaled copy
-//                            and the RMSNorm statistics happen in its epilogue.
-//   gemm_w4_tile_kernel      M <= 16, 4-bit weight-only quantised projections (groups of 128 along K): one
-//                            block per 32 output columns, the codes multiplied as exact bf16 integers, scale
-//                            and zero point applied per group in fp32, the same epilogue.
-//   gemm_f16_tiled_kernel    M > 16.  128 x (128, 192, 256) x 64 LDS-staged tiles, 32x32x16 fp16 MFMA (weights convert to
-//                            fp16 exactly, activations are rounded to fp16).
-// Activations are fp32 in memory in every case.  The bf16 kernels feed each activation to the
-// matrix cores as a pair of bf16 values hi + lo (two MFMAs against the same weight operand):
-// with plain bf16 activations the logits of the 7B-shaped random-init models are 3e-2 off the
-// fp64 result, above the 2e-2 bar; the weights, which are what streams from HBM, stay bf16.
-// Every kernel but the two single-owner ones writes its result as split-K partials [splitk][M][N]
-// (splitk >= 1); the consumer
-// (the fused row-wise kernels, or gemm_splitk_reduce_kernel for the logits) adds them in split
-// order, so results are bit-reproducible.
+//                            With RESID (the down projection) the block that arrives last at a tile adds the
+//                            tile's partials and runs the residual epilogue below.
+//   gemm_bf16_column_kernel  M <= 16, the O projection (it writes the residual stream and is short along K): one
+//                            block per 16 output columns over the whole K range; the residual add, the
+//                            gain-scaled copy and the RMSNorm statistics happen in its epilogue.
+//   gemm_w4_tile_kernel      M <= 16, 4-bit weight-only quantised projections (groups of 128 along K): grid of
+//                            64-column tiles x K splits, the codes multiplied as exact bf16 integers, scale and
+//                            zero point applied per group in fp32; one partial slot per K split, or (O, down)
+//                            the same residual epilogue run by the split that arrives last.
+//   gemm_f16_tiled_kernel    M > 16.  (128 or 256) x (128, 192, 256) x 64 LDS-staged tiles, 32x32x16 fp16 MFMA
+//                            (weights convert to fp16 exactly, activations are rounded to fp16).
+// Activations are fp32 in memory in every case (the tiled kernel reads an fp16 copy its producers leave beside
+// them).  The M <= 16 bf16 kernels feed each activation to the matrix cores as a pair of bf16 values hi + lo (two
+// MFMAs against the same weight operand): with plain bf16 activations the logits of the 7B-shaped random-init
+// models are 3e-2 off the fp64 result, above the 2e-2 bar; the weights, which are what streams from HBM, stay bf16.
+// Every kernel but the ones with the residual epilogue writes its result as split-K partials [splitk][M][N]
+// (splitk >= 1); the consumer (the fused row-wise kernels, the attention kernel's operand build, or
+// gemm_splitk_reduce_kernel for the logits) adds them in split order, so results are bit-reproducible.
 #include <type_traits>
 #include "common.h"
 #include "kernels.h"
@@ -739,10 +741,12 @@ __global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g)
 // most 3e-8), the fp32 activations are rounded to fp16 (11 significant bits, the error of bf16 divided by 8),
 // which keeps the logits of the 7B-shaped models within 2e-2 of the fp64 result at half the MFMA issue of a
 // bf16 high + low pair.  Activations beyond +-65504 would overflow; none of the decoder's normalised or gated
-// activations come near.  Rows are padded to 72 elements (144 B): conflict-free 16-byte reads.  LDS is dynamic,
-// two blocks per CU: one block's staging and barriers overlap the other's MFMAs.
+// activations come near.  Rows are padded to 72 elements (144 B): conflict-free 16-byte reads.  LDS is dynamic.
+// 128-row blocks run two per CU (one block's staging and barriers overlap the other's MFMAs); 256-row blocks run
+// one per CU with two sets of LDS tiles and two K tiles in flight in registers (what a CU keeps in flight bounds
+// its load rate, and one K tile is too little of it).
 // The tile width and the K split are chosen per projection by the host so that the number of blocks comes
-// close to a multiple of the 512 block slots.
+// close to a multiple of the resident block slots.
 constexpr int kBK = 64, kLdsStride = 72, kMaxNB = 8;
 constexpr int kTallRows = 160;                           // from this many rows on: 256-row blocks
 inline int tiled_block_rows(int M) { return M >= kTallRows ? 256 : 128; }
