@@ -12,7 +12,14 @@
 //                        hi + lo pairs, the cache operands as stored -
 //                        and keeps an online softmax per query column with two cross-lane
 //                        shuffles.  Wavefronts are merged through LDS in a fixed order, splits
-//                        by attn_combine_kernel.
+//                        by attn_combine_kernel.  FUSED (at most 32 query rows per KV head): the kernel
+//                        builds its own operands - it adds the QKV projection's partial sums, applies the
+//                        RMSNorm row scale, rotates q and k by a (cos, sin) table, appends k and v to the
+//                        cache and keeps the step's own rows in LDS as one more key tile - so no rotation /
+//                        append kernel runs before it; a token tree's ancestor mask applies to that tile.
+//   attn_mfma_wide_kernel  bf16, more query rows per KV head than that (grouped-query verify at batch,
+//                        prefill): K / V^T tiles staged in LDS as fp16, one MFMA pass, each wavefront its
+//                        own 16-row query tiles.
 //
 // Why V is stored transposed ([d_head][max_len]): the contraction index of P.V is the key, and an
 // MFMA operand wants 8 consecutive contraction values per lane; with V^T those are one 16-byte
