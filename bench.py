@@ -53,7 +53,15 @@ def measured_traffic_bytes():
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
 
 
-def measure_ceilings(dev, quick=False):
+def projection_bytes(shape):
+    """bf16 weight bytes of the five projections of one layer / of the head."""
+    s = shape
+    hd, kvd = s.n_q_heads * s.d_head, s.n_kv_heads * s.d_head
+    return {"QKV": 2 * s.d_model * (hd + 2 * kvd), "O": 2 * hd * s.d_model, "gate|up": 4 * s.d_model * s.d_ffn,
+            "down": 2 * s.d_ffn * s.d_model, "lm_head": 2 * s.vocab * s.d_model}
+
+
+def measure_ceilings(dev, quick=False, shape=None):
     """What the machine delivers on the two resources the kernels are bound by, from the library's two probe
     kernels: a plain streaming read of 2 GiB (more than the 256 MB Infinity Cache; best of several grid sizes)
     and a loop of nothing but 32x32x16 bf16 MFMAs on random operands.  Each figure is the best of the repeats."""
@@ -74,6 +82,27 @@ def measure_ceilings(dev, quick=False):
             if rep:
                 best = max(best, n_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         read[blocks] = best
+    # a plain read of exactly the bytes of each projection, back to back in a busy stream over rotating slices of
+    # the 2 GiB buffer (nothing is served by a cache): what a step made of separate launches can at best take
+    in_flow = None
+    if shape is not None:
+        in_flow = {}
+        for name, nb in projection_bytes(shape).items():
+            nb = nb // 16 * 16
+            n_slices = max(2, n_bytes // nb)
+            views = [src[i * (nb // 4):(i + 1) * (nb // 4)] for i in range(n_slices)]
+            reps = max(1, 24 // n_slices + 1)
+            for v in views:
+                psd.psd_probe_stream_read(v, sink, 2048)
+            e0.record()
+            for _ in range(reps):
+                for v in views:
+                    psd.psd_probe_stream_read(v, sink, 2048)
+            e1.record()
+            torch.cuda.synchronize()
+            in_flow[name] = {"MB": nb / 1e6, "us": e0.elapsed_time(e1) * 1e3 / (reps * n_slices)}
+        per_layer = sum(in_flow[k]["us"] for k in ("QKV", "O", "gate|up", "down"))
+        in_flow["weights_of_one_step_ms"] = (shape.n_layers * per_layer + in_flow["lm_head"]["us"]) * 1e-3
     del src
     seed = torch.empty(1024, dtype=torch.float32, device=dev).normal_(0, 1).to(torch.bfloat16)
     mfma = {}
@@ -93,12 +122,14 @@ def measure_ceilings(dev, quick=False):
             "stream_read_frac_of_hbm_peak": max(read.values()) / HBM_PEAK_GBS,
             "mfma_bf16_TFLOP/s": max(mfma.values()), "mfma_by_blocks": mfma,
             "mfma_frac_of_published_peak": max(mfma.values()) / MFMA_BF16_PEAK_TFLOPS,
+            "plain_read_of_each_projection_in_a_busy_stream": in_flow,
             "how": "psd_probe_stream_read over 2 GiB (non-temporal 16-byte loads, 8 in flight per lane); psd_probe_mfma "
                    "(32x32x16 bf16 on 4 accumulators per wavefront, random operands); best of the repeats"}
 
 
 def ceilings_workload(args, dev):
-    c = measure_ceilings(dev)
+    from paper_2510_26527_amd import synth
+    c = measure_ceilings(dev, shape=synth.LLAMA2_7B)
     print(json.dumps({"metric": "measured ceilings of this MI355X", "unit": "GB/s and TFLOP/s", "n_gpus": 1,
                       "data": "synthetic", "config": {"workload": "library probe kernels: streaming read, MFMA-only loop"},
                       "published": {"hbm_GB/s": HBM_PEAK_GBS, "mfma_bf16_TFLOP/s": MFMA_BF16_PEAK_TFLOPS},
@@ -231,7 +262,7 @@ def main():
         step9()
     torch.cuda.synchronize()
     ms9 = (time.perf_counter() - t9) * 1e3 / min(args.steps, 30)
-    ceilings = measure_ceilings(dev, quick=True)
+    ceilings = measure_ceilings(dev, quick=True, shape=shape)
 
     # same steps again with every launch bracketed by HIP events on its stream
     launches_per_step = 40 * shape.n_layers + 64          # room in the event buffer: more than any path launches
@@ -351,6 +382,7 @@ def main():
         "with_bonus_row": {"n_new": gamma + 1, "ms_per_step": ms9, "verified_tokens/s": gamma * 1e3 / ms9},
         "step_floor_ms_at_hbm_peak": step_floor_ms,
         "step_floor_ms_at_measured_stream_read": (w_bytes + kv_bytes) / (ceilings["stream_read_GB/s"] * 1e9) * 1e3,
+        "step_floor_ms_separate_launches": ceilings["plain_read_of_each_projection_in_a_busy_stream"]["weights_of_one_step_ms"],
         "ceilings": ceilings,
         "attention": attention,
         "roofline": roofline, "cpu_baseline": cpu_baseline, "accept_kernel": accept, "kernels": kernels,
