@@ -236,3 +236,80 @@ def test_tree_forward_on_a_4bit_model():
     ref = ofwd.forward_tree(p.cfg, p.w, toks, parents, p.okv)
     print("rel err", check_logits(out, ref, torch.bfloat16, "4-bit tree rows"))
     p.close()
+
+
+def test_tree_decoding_loop_small_models():
+    """Several decoding steps with a drafted tree each: a drafter close to the verifier grows a binary tree of depth 2
+    level by level (children = inverse-CDF draws from its own rows), the verifier runs one pass over the tree, the
+    acceptance walks it, both caches keep the accepted path.  The oracle follows the verifier in lockstep: its rows
+    after every compaction must match, and its acceptance on the same rows must commit the same tokens."""
+    from oracle import accept as oacc
+    shape, batch, steps = SMALL_MHA, 2, 6
+    parents = [-1, 0, 0, 1, 1, 2, 2]
+    n = len(parents)
+    p = Pair(shape, torch.bfloat16, batch, 256, seed=31, ctx=60, lens=[60, 33], std=0.05, pack=True)
+    g = torch.Generator().manual_seed(2)
+    wd = {k: (v.float() + 0.03 * torch.randn(v.shape, generator=g)).to(v.dtype) if v.dtype == torch.bfloat16 and "norm" not in k else v
+          for k, v in p.w.items()}
+    draft = runtime.Model(shape, wd).pack()
+    dkv = runtime.KVCache(draft, batch, 256)
+    ks, vs = synth.make_kv_fill(shape, batch, 60, 32, torch.bfloat16)      # the drafter starts from the same context
+    dkv.load(ks, vs, [60, 33])
+    zero = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    root = synth.make_tokens(shape.vocab, (batch,), 4).astype(np.int32)
+    tape = synth.make_uniforms((steps, batch, 6 + n + 1), 12).numpy().astype(np.float64)
+    committed, longest = [[] for _ in range(batch)], 0
+    for step in range(steps):
+        base, dbase = p.kv.lens.clone(), dkv.lens.clone()
+        obase = p.okv.lens.copy()
+        toks = np.zeros((batch, n), np.int32)
+        toks[:, 0] = root
+        q = torch.zeros((batch, n, shape.vocab), dtype=torch.float32, device="cuda")
+        # level 1: the drafter's row at the root, two independent draws from it
+        q0 = runtime.forward_tree(draft, dkv, torch.from_numpy(toks[:, :1]).cuda(), [-1])
+        psd.psd_kv_truncate(dkv.handle, dbase, zero, 0)
+        q[:, 0] = q0[:, 0]
+        for c in (1, 2):
+            toks[:, c] = oacc.sample(q0[:, 0].cpu().numpy(), tape[step, :, c - 1])
+        # level 2: its rows at the two children, two draws from each
+        q12 = runtime.forward_tree(draft, dkv, torch.from_numpy(toks[:, :3]).cuda(), [-1, 0, 0])
+        psd.psd_kv_truncate(dkv.handle, dbase, zero, 0)
+        q[:, 1:3] = q12[:, 1:3]
+        for c in (3, 4, 5, 6):
+            toks[:, c] = oacc.sample(q12[:, parents[c]].cpu().numpy(), tape[step, :, c - 1])
+        # the verifier's pass over the tree, checked against the oracle's on its own (compacted) cache
+        t_dev = torch.from_numpy(toks).cuda()
+        logits = runtime.forward_tree(p.model, p.kv, t_dev, parents)
+        ref = ofwd.forward_tree(p.cfg, p.w, toks, parents, p.okv)
+        check_logits(logits, ref, torch.bfloat16, f"step {step}")
+        u = torch.from_numpy(tape[step, :, 6:].astype(np.float32))
+        ln, path, tok, fl = runtime.tree_accept(logits, q, t_dev, parents, u.cuda(), 1.0)
+        torch.cuda.synchronize()
+        lg, qn = logits.cpu().double().numpy(), q.cpu().double().numpy()
+        paths = []
+        for b in range(batch):
+            opath, otok, oflags = otree.tree_accept(lg[b], qn[b], toks[b], parents, u[b].double().numpy(), 1.0, return_flags=True)
+            assert oflags == 0 and int(fl[b]) == 0
+            assert path[b, :int(ln[b])].cpu().tolist() == opath and int(tok[b]) == otok, (step, b)
+            committed[b] += [int(toks[b, c]) for c in opath] + [otok]
+            paths.append(opath)
+            longest = max(longest, len(opath))
+        bound = int(max(int(obase[b]) + 1 + len(paths[b]) for b in range(batch)))
+        psd.psd_kv_compact_tree(p.kv.handle, base, path, ln, n, n, bound)
+        ofwd.compact_tree(p.okv, obase, paths)
+        # the drafter re-reads the root and the accepted tokens (rows of different length: one sequence at a time would
+        # be the plain way; here the longest path is fed and the lengths are cut back per sequence)
+        width = 1 + max(len(x) for x in paths)
+        feed = np.zeros((batch, width), np.int32)
+        for b in range(batch):
+            feed[b, :1 + len(paths[b])] = [toks[b, 0]] + [toks[b, c] for c in paths[b]]
+        runtime.forward(draft, dkv, torch.from_numpy(feed).cuda(), 0)
+        psd.psd_kv_truncate(dkv.handle, dbase, ln, 1)
+        torch.cuda.synchronize()
+        assert dkv.lens.cpu().tolist() == p.kv.lens.cpu().tolist() == p.okv.lens.tolist()
+        root = tok.cpu().numpy().astype(np.int32)
+    assert all(len(c) >= steps for c in committed) and longest >= 1, (committed, longest)
+    print("tokens committed per sequence:", [len(c) for c in committed], "longest accepted path", longest)
+    dkv.close()
+    draft.close()
+    p.close()
