@@ -77,9 +77,11 @@ constexpr int kKeysPerBlockIter = 256;
 
 // Sum over the S split-K slots (sstride floats apart) of NI pairs (src[it][0], src[it][second]) per thread.  The
 // loads of SPC slots of all pairs are issued together; the additions run in slot order, the order in which the
-// stand-alone rotation kernel adds them.
-template <int NI>
-__device__ __forceinline__ void sum_pairs(const float *const *src, size_t sstride, int S, int second, float *x1, float *x2) {
+// stand-alone rotation kernel adds them.  after_issue() runs once, between the first batch's loads and their use:
+// loads the caller issues there queue up behind these and do not hold their return up.
+template <int NI, typename F>
+__device__ __forceinline__ void sum_pairs(const float *const *src, size_t sstride, int S, int second, float *x1, float *x2,
+                                          F after_issue) {
     constexpr int SPC = 32 / NI;
 #pragma unroll
     for (int it = 0; it < NI; ++it) x1[it] = x2[it] = 0.f;
@@ -93,6 +95,7 @@ __device__ __forceinline__ void sum_pairs(const float *const *src, size_t sstrid
                 t1[it][u] = src[it][off];
                 t2[it][u] = src[it][off + second];
             }
+        if (sp0 == 0) after_issue();
 #pragma unroll
         for (int it = 0; it < NI; ++it)
 #pragma unroll
@@ -101,11 +104,13 @@ __device__ __forceinline__ void sum_pairs(const float *const *src, size_t sstrid
     }
 }
 // the same for a number of pairs known at run time (the first ni of up to 8)
-__device__ __forceinline__ void sum_pairs_n(int ni, const float *const *src, size_t sstride, int S, int second, float *x1, float *x2) {
-    if (ni <= 1) sum_pairs<1>(src, sstride, S, second, x1, x2);
-    else if (ni <= 2) sum_pairs<2>(src, sstride, S, second, x1, x2);
-    else if (ni <= 4) sum_pairs<4>(src, sstride, S, second, x1, x2);
-    else sum_pairs<8>(src, sstride, S, second, x1, x2);
+template <typename F>
+__device__ __forceinline__ void sum_pairs_n(int ni, const float *const *src, size_t sstride, int S, int second, float *x1, float *x2,
+                                            F after_issue) {
+    if (ni <= 1) sum_pairs<1>(src, sstride, S, second, x1, x2, after_issue);
+    else if (ni <= 2) sum_pairs<2>(src, sstride, S, second, x1, x2, after_issue);
+    else if (ni <= 4) sum_pairs<4>(src, sstride, S, second, x1, x2, after_issue);
+    else sum_pairs<8>(src, sstride, S, second, x1, x2, after_issue);
 }
 
 // FUSED: the block builds its operands itself from the QKV projection's split-K partial sums: row scale of the
@@ -155,9 +160,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int key = kb + 8 * (i >> 2) + 4 * t + (i & 3);     // < max_len: kb + 32 <= max_len
-                const uint16_t *kp = Kc + (size_t)key * DH + g * (DH / 4);
+                // k-step s of the contraction takes d = 32 s + 8 g .. + 7: the four lane groups of a key read 64
+                // contiguous bytes per load (fewer cache lines per instruction than a lane-group-major split of d)
+                const uint16_t *kp = Kc + (size_t)key * DH + 8 * g;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) ka[sub][t][s] = *reinterpret_cast<const bf16x8 *>(kp + 8 * s);
+                for (int s = 0; s < KS; ++s) ka[sub][t][s] = *reinterpret_cast<const bf16x8 *>(kp + 32 * s);
             }
             // V^T rows d = dt*16 + i, keys kb + 8g .. kb + 8g + 7
 #pragma unroll
@@ -165,9 +172,15 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                 va[sub][dt] = *reinterpret_cast<const bf16x8 *>(Vt + (size_t)(dt * 16 + i) * max_len + kb + 8 * g);
         }
     };
+    // The wavefront's first K / V^T tile is requested ahead of the loop, so that it streams in while the operands are
+    // built; but behind the loads the build waits for (returns are in order, and all blocks' tiles together are the
+    // kernel's whole traffic: requested first, they would hold the build up for the time the cache takes to arrive).
     constexpr bool HOIST = QT == 1;            // two query tiles leave no registers to hold a tile across the build
     const int kt_first = kb0 + wave * kKeysPerWaveIter;
-    if (HOIST && kt_first < kb1) load_tile(kt_first);
+    auto hoisted_tile = [&]() {
+        if (HOIST && kt_first < kb1) load_tile(kt_first);
+    };
+    if constexpr (!FUSED) hoisted_tile();
 
     if constexpr (FUSED) {
         const int tid = threadIdx.x;
@@ -229,7 +242,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                 src[it] = a.qkv_partial + (size_t)(b * a.R + r) * W + (size_t)(hk * group + hl) * DH + pi;
                 cs[it] = a.rope_cs[(size_t)(b * a.R + r) * HALF + pi];
             }
-            sum_pairs_n(ni, src, sstride, S, HALF, x1, x2);
+            sum_pairs_n(ni, src, sstride, S, HALF, x1, x2, hoisted_tile);
             row_scales();
             __syncthreads();                        // s_scale
 #pragma unroll
@@ -273,7 +286,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                     src[it] = a.qkv_partial + (size_t)(b * a.R + r) * W + col0 + pi;
                     cs[it] = a.rope_cs[(size_t)(b * a.R + r) * HALF + pi];
                 }
-                sum_pairs_n(both ? 2 * nik : nik, src, sstride, S, HALF, x1, x2);
+                sum_pairs_n(both ? 2 * nik : nik, src, sstride, S, HALF, x1, x2, [] {});
 #pragma unroll
                 for (int it = 0; it < 8; ++it) {
                     bool is_v;
@@ -309,8 +322,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         __syncthreads();
     }
 
-    // Q operand (B of S^T = K Q^T): column i of tile qt is query q0 + qt*16 + i; lane group g
-    // holds d_head elements [g*DH/4, (g+1)*DH/4), k-step s the 8 starting at 8*s inside them.
+    // Q operand (B of S^T = K Q^T): column i of tile qt is query q0 + qt*16 + i; k-step s of lane group g
+    // holds d_head elements 32 s + 8 g .. + 7, as the K operand does.
     bf16x8 qh[QT][KS], ql[QT][KS];
     int limit[QT];                   // last key this lane's query may see, -1 for a padding column
     uint32_t own_rows[QT];           // token tree: which rows of this step the query sees (bit j = row j); else unused
@@ -329,11 +342,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
                 own_rows[qt] = valid ? a.tree_anc[r] : 0u;
             }
         }
-        const float *qp = FUSED ? &s_q[qt * 16 + i][g * (DH / 4)]
-                                : a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + g * (DH / 4);
+        const float *qp = FUSED ? &s_q[qt * 16 + i][8 * g]
+                                : a.q + (((size_t)(b * a.R + r)) * a.h_q + hk * group + hl) * DH + 8 * g;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            f32x8 v = load_f32x8(qp + 8 * s);
+            f32x8 v = load_f32x8(qp + 32 * s);
             if (!valid) v = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             split_bf16(v, &qh[qt][s], &ql[qt][s]);
         }
@@ -455,7 +468,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
             for (int t = 0; t < 2; ++t) {
                 const int key = 8 * (i >> 2) + 4 * t + (i & 3);
 #pragma unroll
-                for (int s = 0; s < KS; ++s) ka[0][t][s] = *reinterpret_cast<const bf16x8 *>(&s_k[key][g * (DH / 4) + 8 * s]);
+                for (int s = 0; s < KS; ++s) ka[0][t][s] = *reinterpret_cast<const bf16x8 *>(&s_k[key][32 * s + 8 * g]);
             }
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) va[0][dt] = *reinterpret_cast<const bf16x8 *>(&s_vt[dt * 16 + i][8 * g]);
