@@ -814,12 +814,24 @@ int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int le
     const int NQ = (h_q / h_kv) * R;
     const int QT = q_tiles(NQ);
     const int chunks = use_wide(NQ) ? (NQ + wide_rows(NQ) - 1) / wide_rows(NQ) : (NQ + QT * 16 - 1) / (QT * 16);
-    const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
-    // the LDS-staged kernel loads its 64-128 query rows and writes as many partial rows per block: about one
-    // block per CU keeps that overhead below the K/V bytes (measured at 16 x 4 KV heads x 4096 keys: 4 splits
-    // 78 us, 8 splits 91 us, 16 splits 113 us per layer); the direct kernel has light blocks and wants many
-    int by_grid = (use_wide(NQ) ? 256 : 1024) / (B * h_kv * chunks);
+    // Both kernels: about one block per CU.  The LDS-staged kernel loads its 64-128 query rows and writes as many
+    // partial rows per block, which that keeps below the K/V bytes (measured at 16 x 4 KV heads x 4096 keys: 4 splits
+    // 78 us, 8 splits 91 us, 16 splits 113 us per layer).
+    int by_grid = 256 / (B * h_kv * chunks);
     if (by_grid < 1) by_grid = 1;
+    if (!use_wide(NQ)) {
+        // The direct kernel builds its own operands: the keys already in the cache are split into blocks of 256 (one
+        // 64-key tile per wavefront), and one more split takes the step's own rows alone, so that building and
+        // appending their K / V is nobody's prelude to a tile of cache keys.  Measured at the 7B shape, 1024 keys in
+        // the cache (us per layer): 4 + 1 splits 14.7; 4 splits with the new rows riding on the last 21.4; 8 splits
+        // of 128 keys 17.9; 9 splits 24.5 (every block repeats the operand build, and only one block is resident
+        // per CU, so a 257th block waits for a whole block's lifetime).
+        const int cached = len_bound - R > 1 ? len_bound - R : 1;
+        int old_splits = (cached + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
+        if (old_splits > by_grid - 1) old_splits = by_grid - 1;
+        return old_splits < 1 ? 1 : old_splits + 1;
+    }
+    const int by_len = (len_bound + kKeysPerBlockIter - 1) / kKeysPerBlockIter;
     int s = by_len < by_grid ? by_len : by_grid;
     return s < 1 ? 1 : s;
 }
@@ -829,7 +841,13 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     const int NQ = (a.h_q / a.h_kv) * a.R;
     const int QT = q_tiles(NQ);
     const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
+    // keys per split; the kernel that builds its own operands reads only the keys already in the cache and leaves its
+    // last split (if it has several) to the step's own rows
     int range = (a.len_bound + a.splits - 1) / a.splits;
+    if (!use_wide(NQ) && a.qkv_partial && a.splits > 1) {
+        const int cached = a.len_bound - a.R > 1 ? a.len_bound - a.R : 1;
+        range = (cached + a.splits - 2) / (a.splits - 1);
+    }
     range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
     if (use_wide(NQ)) {
