@@ -266,7 +266,7 @@ struct ForwardPlan {
     int sk_qkv, sk_o, sk_gu, sk_down, sk_head, attn_splits;
     size_t off_x, off_xn, off_q, off_attn, off_h, off_partial, off_po, off_pml, off_sumsq, off_rope, off_tilectr, off_tree, total;
     size_t off_xn16, off_attn16, off_h16;
-    bool half_copies;             // M > kStreamMaxRows, bf16: the producers also leave fp16 copies for the tiled projections
+    bool half_copies;             // bf16, M > kStreamMaxRows or 4-bit projections: the producers also leave fp16 copies of the activations
     bool folded;                  // RMSNorm folded into the projections (bf16, packed weights, M <= kStreamMaxRows)
     bool fused_rope;              // the attention kernel reduces, rotates and appends q / k / v itself
 };
@@ -282,17 +282,18 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     const int Ml = batch * n_logit_rows;
     p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
-        if (mdl->w4 && n != n_v) return gemm_w4_splits(K, n, nseg);
+        if (mdl->w4 && n != n_v) return gemm_w4_slots(K, n, nseg, false);
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
     p.fused_rope = attn_fuses_rope(d.dtype, n_new, d.n_q_heads, d.n_kv_heads, d.d_head);
     p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
-    // folded: O runs on the column kernel (one owner per output), or, 4-bit, split along K with the arrival epilogue
-    p.sk_o = p.folded && !mdl->w4 ? 1 : splits(M, hd, d.d_model, n_o, 1);
+    // folded: O runs on the column kernel (one owner per output), or, 4-bit, on partial slots with the arrival epilogue
+    p.sk_o = p.folded ? (mdl->w4 ? gemm_w4_slots(hd, n_o, 1, true) : 1) : splits(M, hd, d.d_model, n_o, 1);
     p.sk_gu = splits(M, d.d_model, 2 * d.d_ffn, n_gu, 2);
     // folded: the down projection runs on the unit kernel with the residual epilogue, its partials in slots
-    p.sk_down = p.folded && !mdl->w4 ? gemm_resid_slots(gemm_pack_tiles(n_o, 1), d.d_ffn) : splits(M, d.d_ffn, d.d_model, n_o, 1);
+    p.sk_down = p.folded ? (mdl->w4 ? gemm_w4_slots(d.d_ffn, n_o, 1, true) : gemm_resid_slots(gemm_pack_tiles(n_o, 1), d.d_ffn))
+                         : splits(M, d.d_ffn, d.d_model, n_o, 1);
     p.sk_head = Ml > 0 ? splits(Ml, d.d_model, d.vocab, n_v, 1) : 1;
     p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
     const size_t act = 4;                                    // activations are fp32 for both dtypes
@@ -303,7 +304,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.off_q = take((size_t)M * hd * act);
     p.off_attn = take((size_t)M * hd * act);
     p.off_h = take((size_t)M * d.d_ffn * act);
-    p.half_copies = d.dtype == PSD_BF16 && M > kStreamMaxRows;
+    p.half_copies = d.dtype == PSD_BF16 && (M > kStreamMaxRows || (mdl->w4 && p.folded));
     p.off_xn16 = take(p.half_copies ? (size_t)M * d.d_model * 2 : 0);
     p.off_attn16 = take(p.half_copies ? (size_t)M * hd * 2 : 0);
     p.off_h16 = take(p.half_copies ? (size_t)M * d.d_ffn * 2 : 0);
@@ -449,7 +450,8 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
             g.wpack = wpack; g.x = xin; g.x_rows_per_group = M; g.w[0] = w; g.n[0] = d.d_model; g.nseg = 1;
             const bool slots = by_units || m->w4;         // partial slots + arrival epilogue, else one block per 16 columns
             g.M = M; g.K = K; g.N = d.d_model; g.splitk = slots ? sk : 1; g.pack_tiles = gemm_pack_tiles(g.n, 1);
-            g.x_resid = x; g.xg_out = xn; g.gain = next_gain; g.sumsq_out = sumsq; g.w4 = m->w4;
+            g.x_resid = x; g.xg_out = xn; g.xg16_out = xn16; g.gain = next_gain; g.sumsq_out = sumsq; g.w4 = m->w4;
+            g.x16 = xin == attn ? attn16 : (xin == h ? h16 : nullptr);
             if (slots) { g.tile_counter = tile_ctr; g.partial = partial; }
             launch_gemm(d.dtype, g, st);
             rs.tiles = slots ? g.pack_tiles : col_tiles;

@@ -17,10 +17,11 @@
 //   gemm_bf16_column_kernel  M <= 16, the O projection (it writes the residual stream and is short along K): one
 //                            block per 16 output columns over the whole K range; the residual add, the
 //                            gain-scaled copy and the RMSNorm statistics happen in its epilogue.
-//   gemm_w4_tile_kernel      M <= 16, 4-bit weight-only quantised projections (groups of 128 along K): grid of
-//                            64-column tiles x K splits, the codes multiplied as exact bf16 integers, scale and
-//                            zero point applied per group in fp32; one partial slot per K split, or (O, down)
-//                            the same residual epilogue run by the split that arrives last.
+//   gemm_w4_unit_kernel      M <= 16, 4-bit weight-only quantised projections (groups of 128 along K): the unit
+//                            kernel's stream-K over quads of four K steps, the codes multiplied as exact fp16
+//                            integers against fp16-rounded activations, scale and zero point applied per group in
+//                            fp32; one partial slot per block and tile, or (O, down) the residual epilogue run by
+//                            the block that arrives last.
 //   gemm_f16_tiled_kernel    M > 16.  (128 or 256) x (128, 192, 256) x 64 LDS-staged tiles, 32x32x16 fp16 MFMA
 //                            (weights convert to fp16 exactly, activations are rounded to fp16).
 // Activations are fp32 in memory in every case (the tiled kernel reads an fp16 copy its producers leave beside
@@ -314,7 +315,11 @@ __device__ __forceinline__ void resid_tile_finish(const GemmArgs &g, int tile, i
             const size_t o = (size_t)tok * g.N + col;
             v += g.x_resid[o];
             g.x_resid[o] = v;
-            if (g.xg_out) g.xg_out[o] = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
+            if (g.xg_out) {
+                const float xg = v * (g.gain ? bf16_bits_to_f32(((const uint16_t *)g.gain)[col]) : 1.0f);
+                g.xg_out[o] = xg;
+                if (g.xg16_out) g.xg16_out[o] = f32_to_f16_bits(xg);
+            }
             sq = v * v;
         }
         sq = wave_sum(sq);                                      // the tile's 64 columns of row tok sit in this wavefront
@@ -322,6 +327,43 @@ __device__ __forceinline__ void resid_tile_finish(const GemmArgs &g, int tile, i
     }
     if (n_contrib > 1 && threadIdx.x == 0)
         __hip_atomic_store(&g.tile_counter[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A block of a unit kernel is done with a tile (the tile's last unit, or the end of the block's range): red[q][row][token]
+// holds the sums of its four wavefronts.  They are added in wavefront order and the block writes ONE partial, slot =
+// its index among the blocks that share the tile (the block that finishes the tile zeroes the slots nobody writes),
+// or, RESID, hands them to the arrival epilogue above.  upt = units per tile, U = units of the GEMM, P = blocks.
+template <bool RESID>
+__device__ __forceinline__ void unit_tile_flush(const GemmArgs &g, const float (&red)[4][kSkinnyRows][17], int tile, int upt,
+                                                long U, long P, bool tile_end, int *s_last) {
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const TileRef t = find_tile(g, tile, kSkinnyRows);
+    const long first_owner = range_owner((long)tile * upt, U, P);
+    const int slot = (int)(blockIdx.x - first_owner);
+    const int row = t.row0 + lane;                                  // lane = row of the tile
+    const bool row_ok = row < g.n[t.seg];
+    const size_t col = (size_t)t.col0 + row;
+    if constexpr (RESID) {
+        const int n_contrib = (int)(range_owner((long)tile * upt + upt - 1, U, P) - first_owner) + 1;
+        float mine[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int tok = q + 4 * r;
+            mine[r] = ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
+        }
+        resid_tile_finish<4>(g, tile, slot, n_contrib, mine, q, 4, row_ok, col, s_last);
+    } else if (row_ok) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int tok = q + 4 * r;
+            if (tok < g.M) {
+                g.partial[((size_t)slot * g.M + tok) * g.N + col] =
+                    ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
+                if (tile_end)
+                    for (int jj = slot + 1; jj < g.splitk; ++jj) g.partial[((size_t)jj * g.M + tok) * g.N + col] = 0.f;
+            }
+        }
+    }
 }
 
 // Block b streams the contiguous units [range_begin(b), range_begin(b + 1)); wavefront q multiplies the q-th 4 KB of
@@ -399,37 +441,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_unit_kernel(GemmArgs g) {
             step_use = tile_end ? 0 : step_use + 1;
             if (n < n_my && (tile_end || n + 1 == n_my)) {                  // the same for all four wavefronts
                 // acc[s][v] = y[token i][row s*16 + 4*gq + v of the tile] over this wavefront's K quarter
-                const TileRef t = find_tile(g, tile, kSkinnyRows);
-                const int slot = (int)(blockIdx.x - range_owner((long)tile * ns, U, P));
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) red[q][s * 16 + 4 * gq + v][i] = acc[s][v];
                 __syncthreads();
-                const int row = t.row0 + lane;                                  // lane = row of the tile from here on
-                const bool row_ok = row < g.n[t.seg];
-                const size_t col = (size_t)t.col0 + row;
-                if constexpr (RESID) {
-                    const int n_contrib = (int)(range_owner((long)tile * ns + ns - 1, U, P) - range_owner((long)tile * ns, U, P)) + 1;
-                    float mine[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int tok = q + 4 * r;
-                        mine[r] = ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
-                    }
-                    resid_tile_finish<4>(g, tile, slot, n_contrib, mine, q, 4, row_ok, col, &s_last);
-                } else if (row_ok) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int tok = q + 4 * r;
-                        if (tok < g.M) {
-                            g.partial[((size_t)slot * g.M + tok) * g.N + col] =
-                                ((red[0][lane][tok] + red[1][lane][tok]) + red[2][lane][tok]) + red[3][lane][tok];
-                            if (tile_end)
-                                for (int jj = slot + 1; jj < g.splitk; ++jj) g.partial[((size_t)jj * g.M + tok) * g.N + col] = 0.f;
-                        }
-                    }
-                }
+                unit_tile_flush<RESID>(g, red, tile, ns, U, P, tile_end, &s_last);
                 __syncthreads();
 #pragma unroll
                 for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -468,46 +485,54 @@ __global__ __launch_bounds__(256) void gemm_pack_strip_kernel(const uint16_t *W,
     dst[vec] = v;
 }
 
-// 4-bit weights (W4A16, asymmetric, groups of 128 along K = one K step): w = scale * (q - zero).  Strip-major
-// layout for the column kernel: (strip, step) is 1088 bytes = 1 KB of nibbles in lane order (lane (i, gq) owns one
-// 16-byte vector: dword q holds its eight nibbles of K offsets (q>>1)*64 + gq*16 + (q&1)*8 ..+7, element e at bit
-// 4*(e/2) + 16*(e&1), so that (dword >> 4p) & 0x000F000F is the element pair (2p, 2p+1)), then the 16 rows'
-// scales as bf16 and their zero points + 128 as bf16.  The kernel multiplies the nibbles as the exact bf16
-// integers 128 + q (bit pattern 0x4300 | q), and takes scale * (sum (128 + q) x - (128 + zero) sum x) per
-// group, so no weight is ever rounded.
-constexpr int kW4StripBytes = 1024 + 64;
+// 4-bit weights (W4A16, asymmetric, groups of 128 along K = one K step): w = scale * (q - zero).  Packed layout
+// of one GEMM: tiles of 64 rows, each tile ceil(ns / 4) quads, a quad = four consecutive K steps of the tile
+// (K steps past the end of K are stored with scale 0), a step = 4352 bytes: four 1 KB slots of codes, one per
+// strip of 16 rows, in lane order (lane (n, gq) owns one 16-byte vector: dword kb holds its eight nibbles of row
+// strip*16 + n, K offsets kb*32 + gq*8 ..+7 of the step, element e at bit 4*(e/2) + 16*(e&1), so that
+// (dword >> 4p) & 0x000F000F is the element pair (2p, 2p+1)), then 256 bytes of scales and zero points: the word
+// of (row n, strip s) at [n][s] holds the bf16 scale in its high half and the fp16 number 1024 + zero (bit
+// pattern 0x6400 | zero) in its low half.  The kernel multiplies the nibbles as the exact fp16 integers
+// 1024 + q (bit pattern 0x6400 | q) and takes scale * (sum (1024 + q) x - (1024 + zero) sum x) per group, so
+// no weight is ever rounded.
+constexpr int kW4StepBytes = 4096 + 256;
+constexpr int kW4QuadBytes = 4 * kW4StepBytes;
+__host__ __device__ __forceinline__ int w4_quads(int K) { return (K / kSkinnyStepK + 3) / 4; }
 
 __global__ __launch_bounds__(64) void gemm_pack_w4_kernel(const uint8_t *Q, const uint16_t *scale, const uint8_t *zero,
                                                           int N, int K, uint8_t *dst) {
-    const int ns = K / kSkinnyStepK;
-    const size_t strip = blockIdx.x / ns;
-    const int step = blockIdx.x % ns, lane = threadIdx.x, i = lane & 15, gq = lane >> 4;
-    const size_t row = strip * 16 + i;
-    uint8_t *out = dst + (size_t)blockIdx.x * kW4StripBytes;
-    u32x4 v = u32x4{0u, 0u, 0u, 0u};
-    if (row < (size_t)N) {
+    // one block per stored K step: blockIdx.x = tile * (4 * quads) + step
+    const int ns = K / kSkinnyStepK, ns4 = 4 * w4_quads(K);
+    const size_t tile = blockIdx.x / ns4;
+    const int step = blockIdx.x % ns4, lane = threadIdx.x, n = lane & 15, gq = lane >> 4;
+    uint8_t *out = dst + (size_t)blockIdx.x * kW4StepBytes;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int k = step * kSkinnyStepK + (q >> 1) * 64 + gq * 16 + (q & 1) * 8;
-            const uint32_t raw = *reinterpret_cast<const uint32_t *>(Q + (row * K + k) / 2);   // byte b: k + 2b, k + 2b + 1
-            uint32_t w = 0;
+    for (int strip = 0; strip < 4; ++strip) {
+        const size_t row = tile * kSkinnyRows + strip * 16 + n;
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
+        if (row < (size_t)N && step < ns) {
 #pragma unroll
-            for (int bb = 0; bb < 4; ++bb) {
-                w |= ((raw >> (8 * bb)) & 0xFu) << (4 * bb);                // element 2 bb
-                w |= ((raw >> (8 * bb + 4)) & 0xFu) << (16 + 4 * bb);       // element 2 bb + 1
+            for (int kb = 0; kb < 4; ++kb) {
+                const int k = step * kSkinnyStepK + kb * 32 + gq * 8;
+                const uint32_t raw = *reinterpret_cast<const uint32_t *>(Q + (row * K + k) / 2);   // byte b: k + 2b, k + 2b + 1
+                uint32_t w = 0;
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    w |= ((raw >> (8 * bb)) & 0xFu) << (4 * bb);                // element 2 bb
+                    w |= ((raw >> (8 * bb + 4)) & 0xFu) << (16 + 4 * bb);       // element 2 bb + 1
+                }
+                v[kb] = w;
             }
-            v[q] = w;
         }
+        reinterpret_cast<u32x4 *>(out + strip * 1024)[lane] = v;
     }
-    reinterpret_cast<u32x4 *>(out)[lane] = v;
-    if (lane < 16) {
-        uint16_t sc = 0, zp = 0x4300;                                        // rows past the end: scale 0
-        if (row < (size_t)N) {
-            sc = scale[row * ns + step];
-            zp = (uint16_t)(0x4300u | zero[row * ns + step]);               // bf16 of 128 + zero (zero <= 15)
-        }
-        reinterpret_cast<uint16_t *>(out + 1024)[lane] = sc;
-        reinterpret_cast<uint16_t *>(out + 1056)[lane] = zp;
+    {
+        const int strip = lane >> 4;
+        const size_t row = tile * kSkinnyRows + strip * 16 + n;
+        uint32_t sz = 0x6400u;                                                   // rows and steps past the end: scale 0
+        if (row < (size_t)N && step < ns)
+            sz = ((uint32_t)scale[row * ns + step] << 16) | (0x6400u | zero[row * ns + step]);   // zero <= 15
+        reinterpret_cast<uint32_t *>(out + 4096)[n * 4 + strip] = sz;
     }
 }
 
@@ -615,119 +640,106 @@ __global__ __launch_bounds__(kColWaves * 64) void gemm_bf16_column_kernel(GemmAr
 }
 
 // ------------------------------------------------------------------------------ 4-bit weights, M <= 16
-// Grid (64-column tiles, K splits): a block takes four strips of the strip-major 4-bit layout over its share of
-// the K range, its eight wavefronts on different parts of that share, added through LDS in wavefront order; the
-// block's sums go to partial slot blockIdx.y (the consumers add the slots in order, as for every other
-// projection).  4-bit weights are a quarter of the bytes, so the fp32 activations a block reads from L2 weigh as
-// much as its weights already at 64 columns (and four times as much at 16): hence the wide tile; and what one CU
-// can keep in flight bounds a block to a few tens of GB/s, hence the K split for projections with few tiles
-// (N = d_model), so that every projection spreads over the whole chip.  Every wavefront keeps the next K step's
-// codes, scales and activations in flight while it multiplies the current one.
-// Per group of 128 K (one step): u = sum (128 + q) x on the matrix cores with the codes as exact bf16
-// integers, xs = sum x with an all-ones operand, then acc += scale * (u - (128 + zero) * xs) in fp32.
-constexpr int kW4Waves = 8, kW4Strips = 4, kW4Cols = 16 * kW4Strips;
-
-struct W4Step {
-    u32x4 code[kW4Strips];          // this lane's 32 nibbles of each strip (dword q = its MFMA operand of K quarter q)
-    uint2 sc[kW4Strips], zr[kW4Strips];   // scales and 128 + zero of rows 4 gq .. 4 gq + 3 of each strip, as bf16
-    f32x8 x[4];                     // activations of token i, K offsets of quarter q
-};
+// The unit kernel's scheme on the 4-bit layout: the unit is a quad (four K steps of a 64-row tile, 17 KB), block b
+// streams the contiguous quads [range_begin(b), range_begin(b + 1)), wavefront q multiplies step q of every quad
+// (its 4352 contiguous bytes), the four wavefronts' sums meet in LDS at the end of a tile, one partial slot per
+// block and tile or the arrival epilogue (O, down).  Codes, scales and activations travel through a ring of
+// register stages filled by buffer loads that return zeros past the end of the block's range.
+// The activations are the MFMA's row operand here and the weights its column operand, so that a lane holds four
+// tokens of ONE weight row per strip and applies that row's scale and zero point as two scalars per group:
+// u = sum (1024 + q) x on the matrix cores with the codes as exact fp16 integers, xs = sum x with an all-ones
+// operand, then acc += scale * (u - (1024 + zero) * xs) in fp32.  The activations are read from the fp16 copy their
+// producers leave beside the fp32 ones (11 significant bits, as for the tiled kernel; activations beyond +-65504
+// would overflow): half the bytes every block re-reads from L2, which weigh as much as the 4-bit weights themselves.
+constexpr int kW4Ring = 2;                         // quads in flight per wavefront (its K step of each)
 
 template <bool RESID>
-__global__ __launch_bounds__(kW4Waves * 64) void gemm_w4_tile_kernel(GemmArgs g) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__global__ __launch_bounds__(256) void gemm_w4_unit_kernel(GemmArgs g) {
+    constexpr int R = kW4Ring;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int i = lane & 15, gq = lane >> 4;
-    const int K = g.K, ns = K / kSkinnyStepK;
-    const int S = g.splitk * kW4Waves, slot = blockIdx.y * kW4Waves + wave;
-    const int s0 = (int)((long)slot * ns / S), s1 = (int)((long)(slot + 1) * ns / S);
-    const bool xvalid = i < g.M;
-    const float *xp = g.x + x_row(g, min(i, g.M - 1)) * K + gq * 16;
-    const uint8_t *wq = (const uint8_t *)g.wpack + (size_t)blockIdx.x * kW4Strips * ns * kW4StripBytes;
-    const size_t strip_stride = (size_t)ns * kW4StripBytes;
-    const u32x4 ones4 = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+    const int K = g.K, ns = K / kSkinnyStepK, nq = w4_quads(K);
+    const long U = (long)g.pack_tiles * nq, P = gridDim.x;
+    const int u0 = (int)range_begin(blockIdx.x, U, P), u1 = (int)range_begin(blockIdx.x + 1, U, P);
+    if (u0 >= u1) return;
+    const int n_my = u1 - u0;
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        (char *)const_cast<void *>(g.wpack) + (size_t)u0 * kW4QuadBytes, 0, n_my * kW4QuadBytes, 0x00020000);
+    // activations (the fp16 copy): offsets from the first row's source row; a row past M points past the buffer and
+    // reads zeros.  Lane (token i, gq) multiplies K offsets kb*32 + gq*8 ..+7 of its step in MFMA kb.
+    const size_t row_first = x_row(g, 0);
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(g.x16) + row_first * K, 0, 0x7ffffff0, 0x00020000);
+    const unsigned xbase = i < g.M ? (unsigned)((x_row(g, i) - row_first) * K * 2) + gq * 16u : 0x80000000u;
 
-    f32x4 acc[kW4Strips];
+    u32x4 C[R][4], S[R], X[R][4];
+    int quad_issue = u0 % nq;
+    auto issue = [&](int j, int n) {                       // n = index of the quad inside the block's range
+        const unsigned woff = (unsigned)n * kW4QuadBytes + q * kW4StepBytes;
 #pragma unroll
-    for (int s = 0; s < kW4Strips; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto load_step = [&](W4Step &d, int step) {
+        for (int s = 0; s < 4; ++s) C[j][s] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff + s * 1024 + lane * 16u, 0, 2);   // 2: streaming
+        S[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff + 4096 + i * 16u, 0, 2);
+        const int step = quad_issue * 4 + q;
+        const unsigned xoff = n < n_my && step < ns ? xbase + (unsigned)step * (kSkinnyStepK * 2) : 0x80000000u;
 #pragma unroll
-        for (int s = 0; s < kW4Strips; ++s) {
-            const uint8_t *base = wq + s * strip_stride + (size_t)step * kW4StripBytes;
-            d.code[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + lane);
-            d.sc[s] = *reinterpret_cast<const uint2 *>(base + 1024 + gq * 8);     // rows 4 gq .. 4 gq + 3
-            d.zr[s] = *reinterpret_cast<const uint2 *>(base + 1056 + gq * 8);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            d.x[q] = load_act8(xp, step * kSkinnyStepK + (q >> 1) * 64 + (q & 1) * 8, xvalid);
+        for (int kb = 0; kb < 4; ++kb) X[j][kb] = __builtin_amdgcn_raw_buffer_load_b128(rx, xoff + kb * 64, 0, 0);
+        quad_issue = quad_issue + 1 == nq ? 0 : quad_issue + 1;
     };
-    auto multiply = [&](const W4Step &d) {
-        f32x4 u[kW4Strips], xs = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 ones4 = u32x4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
+    const f16x8 ones = __builtin_bit_cast(f16x8, ones4);
+    f32x4 acc[4];
 #pragma unroll
-        for (int s = 0; s < kW4Strips; ++s) u[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __shared__ float red[4][kSkinnyRows][17];
+    __shared__ int s_last;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bf16x8 bh, bl;
-            split_bf16(d.x[q], &bh, &bl);
+    for (int j = 0; j < R; ++j) issue(j, j);
+    int quad_use = u0 % nq, tile = u0 / nq;
+    for (int base = 0; base < n_my; base += R) {
 #pragma unroll
-            for (int s = 0; s < kW4Strips; ++s) {
-                const uint32_t w = d.code[s][q];
-                const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x43004300u, ((w >> 4) & 0x000F000Fu) | 0x43004300u,
-                                       ((w >> 8) & 0x000F000Fu) | 0x43004300u, ((w >> 12) & 0x000F000Fu) | 0x43004300u};
-                const bf16x8 aw = __builtin_bit_cast(bf16x8, wi);
-                u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bh, u[s], 0, 0, 0);
-                u[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw, bl, u[s], 0, 0, 0);
+        for (int j = 0; j < R; ++j) {
+            const int n = base + j;
+            if (n >= n_my) break;                                           // the same for all four wavefronts
+            f32x4 u[4], xs = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) u[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const f16x8 xa = __builtin_bit_cast(f16x8, X[j][kb]);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint32_t w = C[j][s][kb];
+                    const u32x4 wi = u32x4{(w & 0x000F000Fu) | 0x64006400u, ((w >> 4) & 0x000F000Fu) | 0x64006400u,
+                                           ((w >> 8) & 0x000F000Fu) | 0x64006400u, ((w >> 12) & 0x000F000Fu) | 0x64006400u};
+                    u[s] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, __builtin_bit_cast(f16x8, wi), u[s], 0, 0, 0);
+                }
+                xs = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, ones, xs, 0, 0, 0);       // sum of x over the group
             }
-            xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bh, xs, 0, 0, 0);       // sum of x over the group
-            xs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bl, xs, 0, 0, 0);
+            // u[s][v] = sum over the group of x[token 4 gq + v] * (1024 + q[row s*16 + i]); xs[v] = sum of x[token 4 gq + v]
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint32_t sz = S[j][s];
+                const float sc = __uint_as_float(sz & 0xffff0000u);
+                const float zf = (float)__builtin_bit_cast(_Float16, (uint16_t)(sz & 0xffffu));
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[s][v] += sc * (u[s][v] - zf * xs[v]);
+            }
+            issue(j, n + R);
+            const bool tile_end = quad_use + 1 == nq;
+            quad_use = tile_end ? 0 : quad_use + 1;
+            if (tile_end || n + 1 == n_my) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) red[q][s * 16 + i][4 * gq + v] = acc[s][v];
+                __syncthreads();
+                unit_tile_flush<RESID>(g, red, tile, nq, U, P, tile_end, &s_last);
+                __syncthreads();
+#pragma unroll
+                for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            if (tile_end) ++tile;
         }
-#pragma unroll
-        for (int s = 0; s < kW4Strips; ++s) {
-            const float scl[4] = {__uint_as_float(d.sc[s].x << 16), __uint_as_float(d.sc[s].x & 0xffff0000u),
-                                  __uint_as_float(d.sc[s].y << 16), __uint_as_float(d.sc[s].y & 0xffff0000u)};
-            const float zpt[4] = {__uint_as_float(d.zr[s].x << 16), __uint_as_float(d.zr[s].x & 0xffff0000u),
-                                  __uint_as_float(d.zr[s].y << 16), __uint_as_float(d.zr[s].y & 0xffff0000u)};
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[s][v] += scl[v] * (u[s][v] - zpt[v] * xs[v]);
-        }
-    };
-
-    // two K steps per round, the second one and the next round's first always in flight
-    W4Step a, b;
-    if (s0 < s1) load_step(a, s0);
-    for (int step = s0; step < s1; step += 2) {
-        if (step + 1 < s1) load_step(b, step + 1);
-        multiply(a);
-        if (step + 2 < s1) load_step(a, step + 2);
-        if (step + 1 < s1) multiply(b);
-    }
-
-    // acc[s][v] = y[token i][tile column s*16 + 4*gq + v] over this wavefront's K steps
-    __shared__ float red[kW4Waves][kW4Cols][17];
-#pragma unroll
-    for (int s = 0; s < kW4Strips; ++s)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][s * 16 + 4 * gq + v][i] = acc[s][v];
-    __syncthreads();
-    // thread t of pass p: column t & 63 of the tile, token (t >> 6) + 8 p
-    const int cn = threadIdx.x & 63;
-    const int col = blockIdx.x * kW4Cols + cn;
-    float mine[2];
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int emm = (threadIdx.x >> 6) + 8 * pass;
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < kW4Waves; ++w) v += red[w][cn][emm];
-        mine[pass] = v;
-        if (!RESID && emm < g.M && col < g.N) g.partial[((size_t)blockIdx.y * g.M + emm) * g.N + col] = v;
-    }
-    if constexpr (RESID) {
-        // the projections that write the residual stream: the K split that arrives last at this tile finishes it
-        __shared__ int s_last;
-        resid_tile_finish<2>(g, blockIdx.x, blockIdx.y, g.splitk, mine, threadIdx.x >> 6, 8, col < g.N, (size_t)col, &s_last);
     }
 }
 
@@ -943,11 +955,11 @@ int gemm_resid_grid(int tiles, int K) {
 }
 
 // largest number of blocks that share one tile, i.e. partial slots per output element
-static int gemm_slots_of(int tiles, int K, int grid);
-int gemm_resid_slots(int tiles, int K) { return gemm_slots_of(tiles, K, gemm_resid_grid(tiles, K)); }
-int gemm_stream_slots(int tiles, int K) { return gemm_slots_of(tiles, K, gemm_stream_grid(tiles, K)); }
-static int gemm_slots_of(int tiles, int K, int grid) {
-    const long ns = K / kSkinnyStepK, U = (long)tiles * ns, P = grid;
+static int gemm_slots_of(int tiles, int units_per_tile, int grid);
+int gemm_resid_slots(int tiles, int K) { return gemm_slots_of(tiles, K / kSkinnyStepK, gemm_resid_grid(tiles, K)); }
+int gemm_stream_slots(int tiles, int K) { return gemm_slots_of(tiles, K / kSkinnyStepK, gemm_stream_grid(tiles, K)); }
+static int gemm_slots_of(int tiles, int units_per_tile, int grid) {
+    const long ns = units_per_tile, U = (long)tiles * ns, P = grid;
     long worst = 1;
     for (long t = 0; t < tiles; ++t) {
         const long span = range_owner((t + 1) * ns - 1, U, P) - range_owner(t * ns, U, P) + 1;
@@ -975,31 +987,29 @@ void launch_gemm_pack(const void *const *w, const int *n, int nseg, int K, void 
 }
 
 size_t gemm_pack_w4_bytes(const int *n, int nseg, int K) {
-    size_t strips = 0;
-    for (int s = 0; s < nseg; ++s) strips += (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * 4;
-    return strips * (K / kSkinnyStepK) * kW4StripBytes;
+    return (size_t)tiles_of(n, nseg, kSkinnyRows) * w4_quads(K) * kW4QuadBytes;
 }
 
 void launch_gemm_pack_w4(const void *const *q, const void *const *scale, const void *const *zero, const int *n,
                          int nseg, int K, void *dst, hipStream_t stream) {
     uint8_t *out = (uint8_t *)dst;
-    const int ns = K / kSkinnyStepK;
+    const int ns4 = 4 * w4_quads(K);
     for (int s = 0; s < nseg; ++s) {
-        const size_t strips = (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows) * 4;
-        launch_kernel(gemm_pack_w4_kernel, (unsigned)(strips * ns), 64, 0, stream, (const uint8_t *)q[s],
+        const size_t tiles = (size_t)((n[s] + kSkinnyRows - 1) / kSkinnyRows);
+        launch_kernel(gemm_pack_w4_kernel, (unsigned)(tiles * ns4), 64, 0, stream, (const uint8_t *)q[s],
                       (const uint16_t *)scale[s], (const uint8_t *)zero[s], n[s], K, out);
-        out += strips * ns * kW4StripBytes;
+        out += tiles * ns4 * kW4StepBytes;
     }
 }
 
-// K splits of a 4-bit projection: enough blocks to cover the chip, at least one K step per wavefront
-int gemm_w4_splits(int K, const int *n, int nseg) {
-    const int tiles = tiles_of(n, nseg, kW4Cols), ns = K / kSkinnyStepK;
-    int want = (256 + tiles - 1) / tiles, cap = ns / kW4Waves;
-    if (cap < 1) cap = 1;
-    if (want > cap) want = cap;
-    if (want > 8) want = 8;
-    return want < 1 ? 1 : want;
+// grid and partial slots of a 4-bit projection: the unit kernel's policy with the quad as the unit
+static int gemm_w4_grid(int tiles, int K, bool resid) {
+    const long U = (long)tiles * w4_quads(K), cap = resid ? kStreamBlocks / 2 : kStreamBlocks;
+    return (int)(U < cap ? (U < 1 ? 1 : U) : cap);
+}
+int gemm_w4_slots(int K, const int *n, int nseg, bool resid) {
+    const int tiles = tiles_of(n, nseg, kSkinnyRows);
+    return gemm_slots_of(tiles, w4_quads(K), gemm_w4_grid(tiles, K, resid));
 }
 
 int gemm_packed_splits(int M, int K, const int *n, int nseg) {
@@ -1032,11 +1042,14 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
         return;
     }
     if (g.M <= kStreamMaxRows && g.wpack && g.w4) {
+        // 32-bit offsets from the first activation row: these projections read M <= 16 consecutive rows
         ScopedProf sp(PSD_KIND_GEMM_W4, stream);
-        if (g.x_resid && g.tile_counter)
-            launch_kernel(gemm_w4_tile_kernel<true>, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
+        const bool resid = g.x_resid && g.tile_counter;
+        const int grid = gemm_w4_grid(g.pack_tiles, g.K, resid);
+        if (resid)
+            launch_kernel(gemm_w4_unit_kernel<true>, grid, 256, 0, stream, g);
         else
-            launch_kernel(gemm_w4_tile_kernel<false>, dim3(g.N / kW4Cols, g.splitk), kW4Waves * 64, 0, stream, g);
+            launch_kernel(gemm_w4_unit_kernel<false>, grid, 256, 0, stream, g);
         return;
     }
     if (g.M <= kStreamMaxRows && g.wpack && g.x_resid && g.tile_counter) {

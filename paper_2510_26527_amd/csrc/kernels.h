@@ -68,12 +68,13 @@ struct GemmArgs {
     // columns one block finishes; the consumer of the next projection's output multiplies by r_m (RowScale).
     float *x_resid;
     float *xg_out;
+    uint16_t *xg16_out;           // optional: xg_out rounded to fp16 (the operand of the 4-bit projections)
     const void *gain;             // [N] bf16
     float *sumsq_out;             // [N/16][M] (column kernel) or [N/64][M] (unit kernel with the residual epilogue)
     unsigned *tile_counter;       // non-NULL selects the unit kernel for this projection: [N/64] arrival counters, zero
                                   //   before the launch and left at zero by it; `partial` then holds gemm_resid_slots() slots
-    // -- 4-bit weights (W4A16, groups of 128 along K): wpack holds the strip-major 4-bit layout of
-    // launch_gemm_pack_w4; the projection writes `splitk` partial slots (gemm_w4_splits)
+    // -- 4-bit weights (W4A16, groups of 128 along K): wpack holds the 4-bit quad layout of
+    // launch_gemm_pack_w4; the projection writes `splitk` partial slots (gemm_w4_slots)
     bool w4;
     RowScale scale;               // applied when writing `reduced` (row = the source row of m)
     int scale_rows;               //   rows per tile slab of scale.sumsq
@@ -82,7 +83,7 @@ int gemm_pick_splitk(int dtype, int M, int K, int N, const int *n, int nseg);
 // repacked weights for the M <= kStreamMaxRows path
 int gemm_pack_tiles(const int *n, int nseg);
 size_t gemm_pack_bytes(const int *n, int nseg, int K);
-int gemm_w4_splits(int K, const int *n, int nseg);             // K splits (partial slots) of a 4-bit projection
+int gemm_w4_slots(int K, const int *n, int nseg, bool resid);  // partial slots of a 4-bit projection (resid: the arrival epilogue's grid)
 int gemm_packed_splits(int M, int K, const int *n, int nseg);   // partial slots (the splitk to use) with packed weights
 int gemm_stream_grid(int tiles, int K);
 int gemm_stream_slots(int tiles, int K);
