@@ -518,32 +518,48 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, float scale_
         __syncthreads();
     }
 
-    // ---- write: directly when there is one split, else the unnormalised partial
-    for (int e = threadIdx.x; e < QT * 16 * DH; e += 256) {
-        const int qc = e / DH, d = e % DH;
+    // ---- write: directly when there is one split, else the unnormalised partial.  One thread per query row works
+    // out where the row goes and how its slabs combine; the element loop then only multiplies and adds.
+    __shared__ float s_f[NSLAB][QT * 16], s_M[QT * 16], s_L[QT * 16];
+    __shared__ int s_row[QT * 16];
+    if (threadIdx.x < QT * 16) {
+        const int qc = threadIdx.x;
         const int qi = qchunk * QT * 16 + qc;
-        if (qi >= NQ) continue;
-        const int hl = qi / a.R, r = qi % a.R;
-        const size_t row = ((size_t)(b * a.R + r)) * a.h_q + hk * group + hl;       // [B][R][h_q]
+        int row = -1;
+        if (qi < NQ) {
+            const int hl = qi / a.R, r = qi % a.R;
+            row = (b * a.R + r) * a.h_q + hk * group + hl;                           // [B][R][h_q]
+        }
         float M = sm_m[0][qc];
 #pragma unroll
         for (int sl = 1; sl < NSLAB; ++sl) M = fmaxf(M, sm_m[sl][qc]);
-        float acc = 0.f, L = 0.f;
+        float L = 0.f;
 #pragma unroll
         for (int sl = 0; sl < NSLAB; ++sl) {
             const float ms = sm_m[sl][qc];
             const float f = ms > -INFINITY ? __builtin_amdgcn_exp2f(ms - M) : 0.f;
-            acc += sm_o[sl][qc][d] * f;
+            s_f[sl][qc] = f;
             L += sm_l[sl][qc] * f;
         }
+        s_row[qc] = row; s_M[qc] = M; s_L[qc] = L;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < QT * 16 * DH; e += 256) {
+        const int qc = e / DH, d = e % DH;
+        if (s_row[qc] < 0) continue;
+        const size_t row = (size_t)s_row[qc];
+        float acc = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < NSLAB; ++sl) acc += sm_o[sl][qc][d] * s_f[sl][qc];
         if (a.splits == 1) {
+            const float L = s_L[qc];
             a.out[row * DH + d] = acc / L;
             if (a.out16) a.out16[row * DH + d] = f32_to_f16_bits(acc / L);
         } else {
             a.part_o[(row * a.splits + split) * DH + d] = acc;
             if (d == 0) {
-                a.part_ml[(row * a.splits + split) * 2] = M;
-                a.part_ml[(row * a.splits + split) * 2 + 1] = L;
+                a.part_ml[(row * a.splits + split) * 2] = s_M[qc];
+                a.part_ml[(row * a.splits + split) * 2 + 1] = s_L[qc];
             }
         }
     }
