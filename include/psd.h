@@ -97,12 +97,13 @@ psd_status psd_model_destroy(psd_model *m);
  * k = 2b in its low nibble and k = 2b + 1 in its high nibble.  scale_ptrs / zero_ptrs: 7 * n_layers device
  * pointers in the order (wq, wk, wv, wo, w_gate, w_up, w_down) per layer, to bf16 [n][K/128] and to uint8
  * [n][K/128] with values 0..15.  Embedding, norm gains, lm_head and the KV cache stay bf16; activations are
- * handled as in PSD_BF16 models; no weight is rounded: the codes enter the matrix cores as exact integers and
- * scale and zero point are applied per group in fp32.
- * Such a model must be packed (psd_model_pack) before its first forward (PSD_ERR_UNIMPLEMENTED otherwise).  Its
- * projections exist for steps of at most 16 rows (batch * n_new <= 16): a longer step of ONE sequence (a prompt)
- * is run by psd_model_forward as consecutive steps of 16 rows, which computes the same function; a longer step of
- * several sequences is PSD_ERR_UNIMPLEMENTED.  Further limit: n_kv_heads * d_head a multiple of 64. */
+ * rounded to fp16 (11 significant bits) on their way into these projections; in steps of at most 16 rows no weight
+ * is rounded: the codes enter the matrix cores as exact integers and scale and zero point are applied per group
+ * in fp32.
+ * Such a model must be packed (psd_model_pack) before its first forward (PSD_ERR_UNIMPLEMENTED otherwise).  Steps
+ * of at most 16 rows (batch * n_new <= 16) stream the packed 4-bit copy and multiply the codes exactly; longer steps
+ * read the caller's codes, scales and zero points and round each weight scale * (q - zero) to fp16 once.  A token
+ * tree on such a model is limited to 16 rows.  Further limit: n_kv_heads * d_head a multiple of 64. */
 psd_status psd_model_create_w4(const psd_model_desc *desc, const void *const *weight_ptrs, int32_t n_ptrs,
                                const void *const *scale_ptrs, const void *const *zero_ptrs,
                                int32_t n_quant_ptrs, psd_model **out);

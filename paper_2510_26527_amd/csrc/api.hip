@@ -282,7 +282,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     const int Ml = batch * n_logit_rows;
     p.folded = mdl->packed && d.dtype == PSD_BF16 && M <= kStreamMaxRows;
     auto splits = [&](int rows, int K, int N, const int *n, int nseg) {
-        if (mdl->w4 && n != n_v) return gemm_w4_slots(K, n, nseg, false);
+        if (mdl->w4 && n != n_v && rows <= kStreamMaxRows) return gemm_w4_slots(K, n, nseg, false);
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
@@ -338,16 +338,6 @@ extern "C" {
 
 size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_new, int32_t max_len) {
     if (!m || max_len <= 0 || !forward_shape_ok(m, batch, n_new)) return 0;
-    if (m->w4 && batch * n_new > kStreamMaxRows) {
-        // a longer step of one sequence runs as consecutive steps of at most kStreamMaxRows rows: the largest need of those
-        if (batch != 1) return 0;
-        size_t worst = 0;
-        for (int r = 1; r <= kStreamMaxRows; ++r) {
-            const size_t b = psd_model_workspace_bytes(m, 1, r, max_len);
-            worst = b > worst ? b : worst;
-        }
-        return worst;
-    }
     // split choices depend on the cache length bound and on how many rows get logits:
     // take the largest need over all of them
     size_t worst = 0;
@@ -375,23 +365,6 @@ psd_status psd_model_forward(psd_model *m, const int32_t *tokens_dev, int32_t n_
     if (n_logit_rows > 0 && !logits_out_dev) return PSD_ERR_NULL;
     if (kv->len_ub + n_new > kv->max_len) return PSD_ERR_CAPACITY;
     if (m->w4 && !m->packed) return PSD_ERR_UNIMPLEMENTED;
-    if (m->w4 && B * n_new > kStreamMaxRows) {
-        // 4-bit projections exist for steps of up to kStreamMaxRows rows: a longer step of one sequence (a prompt)
-        // runs as consecutive steps of that size, which computes the same function (the cache carries the prefix)
-        if (B != 1) return PSD_ERR_UNIMPLEMENTED;
-        if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < psd_model_workspace_bytes(m, 1, n_new, kv->max_len))
-            return PSD_ERR_WORKSPACE;
-        const int first_logit = n_new - n_logit_rows;
-        for (int c0 = 0; c0 < n_new; c0 += kStreamMaxRows) {
-            const int c1 = c0 + kStreamMaxRows < n_new ? c0 + kStreamMaxRows : n_new;
-            const int from = c0 > first_logit ? c0 : first_logit;            // first row of this piece that wants logits
-            const int rows = c1 > from ? c1 - from : 0;
-            float *out = rows ? logits_out_dev + (size_t)(from - first_logit) * m->d.vocab : nullptr;
-            const psd_status s = forward_once(m, tokens_dev + c0, c1 - c0, kv, out, rows, workspace, ws_bytes, hip_stream);
-            if (s != PSD_OK) return s;      // pieces already enqueued stay enqueued: the cache then holds a prefix of the step
-        }
-        return PSD_OK;
-    }
     return forward_once(m, tokens_dev, n_new, kv, logits_out_dev, n_logit_rows, workspace, ws_bytes, hip_stream);
 }
 
@@ -419,8 +392,9 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
 
     (void)hipGetLastError();
     auto norm_gain = [&](int l) { return l < d.n_layers ? m->layer(l, W_ATTN_NORM) : m->final_norm(); };
+    // ql, qj: layer and index of the first segment among the layer's 4-bit projections (q k v o gate up down), if any
     auto gemm = [&](const float *xin, int rows, int K, const void *w0, int n0, const void *w1, int n1,
-                    const void *w2, int n2, int sk, float *dst, const void *wpack) {
+                    const void *w2, int n2, int sk, float *dst, const void *wpack, int ql = -1, int qj = -1) {
         GemmArgs g{};
         g.wpack = rows <= kStreamMaxRows ? wpack : nullptr;
         g.x = xin; g.x_rows_per_group = rows > 0 ? rows : 1; g.x_group_stride = 0; g.x_group_offset = 0;
@@ -429,7 +403,8 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         g.nseg = w2 ? 3 : (w1 ? 2 : 1);
         g.M = rows; g.K = K; g.N = n0 + n1 + n2; g.partial = dst; g.splitk = sk; g.reduced = nullptr;
         g.pack_tiles = gemm_pack_tiles(g.n, g.nseg);
-        g.w4 = m->w4;
+        g.w4 = m->w4 && qj >= 0;
+        for (int sgm = 0; sgm < g.nseg && g.w4; ++sgm) { g.w4_scale[sgm] = m->qscale(ql, qj + sgm); g.w4_zero[sgm] = m->qzero(ql, qj + sgm); }
         launch_gemm(d.dtype, g, st);
     };
     // Folded mode: no RMSNorm kernel runs.  The projections that write the residual stream add into it and
@@ -444,7 +419,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
     const float *act = xn;     // what QKV / gate|up / lm_head read: rmsnorm(x) * gain, or x * gain when folded
     unsigned *tile_ctr = p.folded ? (unsigned *)(ws + p.off_tilectr) : nullptr;
     auto resid_gemm = [&](const float *xin, int K, const void *w, int sk, const void *wpack, const void *next_gain,
-                          bool by_units) {
+                          bool by_units, int ql, int qj) {
         if (p.folded) {
             GemmArgs g{};
             g.wpack = wpack; g.x = xin; g.x_rows_per_group = M; g.w[0] = w; g.n[0] = d.d_model; g.nseg = 1;
@@ -456,7 +431,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
             launch_gemm(d.dtype, g, st);
             rs.tiles = slots ? g.pack_tiles : col_tiles;
         } else {
-            gemm(xin, M, K, w, d.d_model, nullptr, 0, nullptr, 0, sk, partial, wpack);
+            gemm(xin, M, K, w, d.d_model, nullptr, 0, nullptr, 0, sk, partial, wpack, ql, qj);
             launch_reduce_residual_norm(d.dtype, partial, sk, x, next_gain, xn, M, d.d_model, d.rms_eps, xn16, st);
         }
     };
@@ -477,7 +452,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
     rs.tiles = 1;
     for (int l = 0; l < d.n_layers; ++l) {
         gemm(act, M, d.d_model, m->layer(l, W_Q), hd, m->layer(l, W_K), kvd, m->layer(l, W_V), kvd, p.sk_qkv, partial,
-             m->pack(l, P_QKV));
+             m->pack(l, P_QKV), l, 0);
         char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
         if (!p.fused_rope)
             launch_reduce_rope_append(d.dtype, partial, p.sk_qkv, rs, q, kl, vl, kv->lens, B, n_new, d.n_q_heads,
@@ -490,11 +465,11 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
         a.splits = p.attn_splits;
         launch_attention(d.dtype, a, st);
 
-        resid_gemm(attn, hd, m->layer(l, W_O), p.sk_o, m->pack(l, P_O), m->layer(l, W_FFN_NORM), false);
+        resid_gemm(attn, hd, m->layer(l, W_O), p.sk_o, m->pack(l, P_O), m->layer(l, W_FFN_NORM), false, l, 3);
         gemm(act, M, d.d_model, m->layer(l, W_GATE), d.d_ffn, m->layer(l, W_UP), d.d_ffn, nullptr, 0, p.sk_gu, partial,
-             m->pack(l, P_GU));
+             m->pack(l, P_GU), l, 4);
         launch_reduce_swiglu(partial, p.sk_gu, rs, h, M, d.d_ffn, h16, st);
-        resid_gemm(h, d.d_ffn, m->layer(l, W_DOWN), p.sk_down, m->pack(l, P_DOWN), norm_gain(l + 1), true);
+        resid_gemm(h, d.d_ffn, m->layer(l, W_DOWN), p.sk_down, m->pack(l, P_DOWN), norm_gain(l + 1), true, l, 6);
     }
     if (n_logit_rows > 0) {
         // lm_head on the last n_logit_rows rows of every sequence (unfolded: xn already holds the final norm)

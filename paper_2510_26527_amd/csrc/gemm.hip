@@ -743,6 +743,24 @@ __global__ __launch_bounds__(256) void gemm_w4_unit_kernel(GemmArgs g) {
     }
 }
 
+typedef __attribute__((ext_vector_type(2))) uint32_t uint2v;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+// 8 four-bit codes (element e in bits 4e .. 4e+3) -> 8 fp16 weights scale * (q - zero); sz = fp16 scale in the high
+// half, fp16 1024 + zero in the low half
+__device__ __forceinline__ u32x4 w4x8_to_f16x8(uint32_t raw, uint32_t sz) {
+    const _Float16 zf = __builtin_bit_cast(_Float16, (uint16_t)(sz & 0xffffu));
+    const _Float16 sf = __builtin_bit_cast(_Float16, (uint16_t)(sz >> 16));
+    const f16x2 z2 = f16x2{zf, zf}, s2 = f16x2{sf, sf};
+    u32x4 r;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t t = raw >> (8 * p);
+        const uint32_t pair = (t & 0xFu) | ((t & 0xF0u) << 12) | 0x64006400u;   // fp16 1024 + q of elements 2p, 2p+1
+        r[p] = __builtin_bit_cast(uint32_t, (__builtin_bit_cast(f16x2, pair) - z2) * s2);
+    }
+    return r;
+}
+
 // ------------------------------------------------------------------------------ tiled (M > 16)
 // Block tile 128 or 256 rows of activations x 32*NB rows of W x 64 of K (NB = 4, 6, 8); wavefronts in a 2 x 2 or
 // 4 x 2 grid, each on 64 activation rows x 16*NB weight rows: 2 x NB/2 tiles of the 32x32x16 MFMA, so that per 16-wide K step
@@ -765,7 +783,11 @@ inline int tiled_block_rows(int M) { return M >= kTallRows ? 256 : 128; }
 
 // MW = wavefront rows of the block: 2 (128 activation rows, 256 threads, two blocks per CU) or 4 (256 rows, 512
 // threads, one block per CU: each weight tile then leaves L2 once for 256 rows instead of twice).
-template <int NB, int MW>
+// W4: the weights are 4-bit codes as the caller stores them (row-major, low nibble = even k) with a bf16 scale and
+// a zero point per row and group of 128 k.  A thread's 8 weights of a K tile are 4 bytes of codes; on the way into
+// LDS they become the fp16 numbers scale * (q - zero): (1024 + q) - (1024 + zero) is exact in fp16, the product
+// with the scale (itself exact in fp16 down to 6e-5) is rounded once, to 11 significant bits.
+template <int NB, int MW, bool W4 = false>
 __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kernel(GemmArgs g) {
     constexpr int BM = 64 * MW, BN = 32 * NB, NH = NB / 2, NT = MW * 128;
     constexpr int XCH = BM * 8 / NT;                        // 16-byte chunks of the fp16 X tile per thread (BM x 64)
@@ -792,6 +814,7 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
     // global -> register staging per K tile: XCH x 8 activations (fp16 copy if there is one, else fp32 rounded
     // here) and WCH x 8 bf16 of W per thread
     uint32_t xsrc[XCH], wsrc[WCH];                       // element offsets from the matrices' first elements
+    uint32_t wgrp[WCH];                                  // W4: index of the row's first group in scale / zero
     int xoff[XCH], woff[WCH];
 #pragma unroll
     for (int c = 0; c < XCH; ++c) {
@@ -803,14 +826,20 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
     for (int c = 0; c < WCH; ++c) {
         const int chunk = tid + c * NT, row = chunk >> 3, col = (chunk & 7) * 8;
         wsrc[c] = (uint32_t)((size_t)min(t.row0 + row, seg_rows - 1) * K + col);
+        wgrp[c] = (uint32_t)(min(t.row0 + row, seg_rows - 1) * (K / kSkinnyStepK));
         woff[c] = row * kLdsStride + col;
     }
+    const uint8_t *Wq = (const uint8_t *)g.w[t.seg];
+    const uint16_t *Wscale = (const uint16_t *)g.w4_scale[t.seg];
+    const uint8_t *Wzero = (const uint8_t *)g.w4_zero[t.seg];
     const bool have16 = g.x16 != nullptr;
     // Register stages of the global -> LDS path.  What one CU keeps in flight bounds its load rate (bytes in flight /
     // latency), and one K tile per block is too little of it: with two sets of LDS tiles the block also keeps two
     // K tiles in flight in registers (stage = tile parity), except at the widest tile where the registers run out.
     constexpr int NST = (DB && NB <= 6) ? 2 : 1;
-    u32x4 xr[NST][XCH], wr[NST][WCH];
+    using WReg = std::conditional_t<W4, uint2v, u32x4>;   // what a thread holds of one 8-weight chunk
+    u32x4 xr[NST][XCH];
+    WReg wr[NST][WCH];
     auto load_tiles = [&](auto stage, int kt) {
         constexpr int st = decltype(stage)::value;
 #pragma unroll
@@ -819,7 +848,17 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
             else xr[st][c] = f32x8_to_f16x8(load_f32x8(g.x + xsrc[c] + kt * kBK));
         }
 #pragma unroll
-        for (int c = 0; c < WCH; ++c) wr[st][c] = *reinterpret_cast<const u32x4 *>(W + wsrc[c] + kt * kBK);
+        for (int c = 0; c < WCH; ++c) {
+            if constexpr (W4) {
+                // [0]: the 8 codes; [1]: fp16 scale (high half) and fp16 1024 + zero (low half) of the row's group
+                const uint32_t grp = wgrp[c] + (uint32_t)(kt * kBK / kSkinnyStepK);
+                const _Float16 sc = (_Float16)bf16_bits_to_f32(Wscale[grp]);
+                wr[st][c][0] = *reinterpret_cast<const uint32_t *>(Wq + (wsrc[c] + kt * kBK) / 2);
+                wr[st][c][1] = ((uint32_t)__builtin_bit_cast(uint16_t, sc) << 16) | 0x6400u | Wzero[grp];
+            } else {
+                wr[st][c] = *reinterpret_cast<const u32x4 *>(W + wsrc[c] + kt * kBK);
+            }
+        }
     };
     auto store_tiles = [&](auto stage, int set) {
         constexpr int st = decltype(stage)::value;
@@ -827,7 +866,10 @@ __global__ __launch_bounds__(MW * 128, MW == 2 ? 2 : 1) void gemm_f16_tiled_kern
 #pragma unroll
         for (int c = 0; c < XCH; ++c) *reinterpret_cast<u32x4 *>(&Xs[xoff[c]]) = xr[st][c];
 #pragma unroll
-        for (int c = 0; c < WCH; ++c) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = bf16x8_to_f16x8(wr[st][c]);
+        for (int c = 0; c < WCH; ++c) {
+            if constexpr (W4) *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = w4x8_to_f16x8(wr[st][c][0], wr[st][c][1]);
+            else *reinterpret_cast<u32x4 *>(&Ws[woff[c]]) = bf16x8_to_f16x8(wr[st][c]);
+        }
     };
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, NST - 1>;      // the second stage, or the only one
@@ -1092,7 +1134,15 @@ void launch_gemm(int dtype, const GemmArgs &g, hipStream_t stream) {
                                       (int)lds);
             launch_kernel(kernel, grid, bm * 2, lds, stream, g);
         };
-        if (bm == 256) {
+        if (g.w4 && bm == 256) {
+            if (nb == 4) go(gemm_f16_tiled_kernel<4, 4, true>);
+            else if (nb == 6) go(gemm_f16_tiled_kernel<6, 4, true>);
+            else go(gemm_f16_tiled_kernel<8, 4, true>);
+        } else if (g.w4) {
+            if (nb == 4) go(gemm_f16_tiled_kernel<4, 2, true>);
+            else if (nb == 6) go(gemm_f16_tiled_kernel<6, 2, true>);
+            else go(gemm_f16_tiled_kernel<8, 2, true>);
+        } else if (bm == 256) {
             if (nb == 4) go(gemm_f16_tiled_kernel<4, 4>);
             else if (nb == 6) go(gemm_f16_tiled_kernel<6, 4>);
             else go(gemm_f16_tiled_kernel<8, 4>);

@@ -76,6 +76,7 @@ struct GemmArgs {
     // -- 4-bit weights (W4A16, groups of 128 along K): wpack holds the 4-bit quad layout of
     // launch_gemm_pack_w4; the projection writes `splitk` partial slots (gemm_w4_slots)
     bool w4;
+    const void *w4_scale[3], *w4_zero[3];   // M > kStreamMaxRows: w[] are the codes [n][K/2], these the bf16 scales and uint8 zero points [n][K/128]
     RowScale scale;               // applied when writing `reduced` (row = the source row of m)
     int scale_rows;               //   rows per tile slab of scale.sumsq
 };

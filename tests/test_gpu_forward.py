@@ -361,26 +361,30 @@ def test_w4_small_models(shape, steps, ctx):
     p.close()
 
 
-def test_w4_long_step_of_one_sequence_and_its_limit():
-    """More than 16 rows in one call: the library runs a single sequence's step as consecutive 16-row steps (same
-    function: the oracle does it in one go), logits for the trailing rows only or for all of them; a long step of
-    several sequences is refused."""
+def test_w4_more_than_16_rows():
+    """More than 16 rows in one call run on the tiled kernel with the 4-bit weights dequantised on their way into
+    LDS: a long step of one sequence (a prompt), logits for the trailing rows only or for all of them, then steps of
+    several ragged sequences at 18 and 160 rows (both block heights of the tiled kernel), and back to a short step."""
     shape = SMALL_GQA
     p = Pair(shape, torch.bfloat16, 1, 256, seed=77, ctx=40, std=0.05, w4=True)
-    toks = synth.make_tokens(shape.vocab, (1, 70), 5)
+    toks = synth.make_tokens(shape.vocab, (1, 86), 5)
     e1 = p.step(toks[:, :37], what="37 rows, all logits")
-    e2 = p.step(toks[:, 37:70], n_logit_rows=21, what="33 rows, last 21 logits (crossing a piece boundary)")
-    print("w4 long steps rel err", e1, e2)
-    assert int(p.kv.lens[0]) == 110 and psd.psd_kv_len_upper_bound(p.kv.handle) == 110
+    e2 = p.step(toks[:, 37:70], n_logit_rows=21, what="33 rows, last 21 logits")
+    e3 = p.step(toks[:, 70:86], what="16 rows after the long steps")
+    print("w4 long steps rel err", e1, e2, e3)
+    assert int(p.kv.lens[0]) == 126 and psd.psd_kv_len_upper_bound(p.kv.handle) == 126
     p.close()
-    p2 = Pair(shape, torch.bfloat16, 2, 128, seed=78, ctx=10, std=0.05, w4=True)
-    assert psd.psd_model_workspace_bytes(p2.model.handle, 2, 9, 128) == 0
-    ws = p2.model.workspace(2, 8, 128)
-    with pytest.raises(psd.PsdError) as e:
-        psd.psd_model_forward(p2.model.handle, torch.zeros((2, 9), dtype=torch.int32, device="cuda"), 9, p2.kv.handle,
-                              None, 0, ws)
-    assert e.value.status == psd.PSD_ERR_UNIMPLEMENTED
+    p2 = Pair(shape, torch.bfloat16, 2, 128, seed=78, ctx=10, lens=[10, 3], std=0.05, w4=True)
+    assert psd.psd_model_workspace_bytes(p2.model.handle, 2, 9, 128) > 0
+    toks = synth.make_tokens(shape.vocab, (2, 12), 6)
+    e4 = p2.step(toks[:, :9], what="2 sequences x 9 rows")
+    e5 = p2.step(toks[:, 9:12], what="2 sequences x 3 rows after it")
     p2.close()
+    p3 = Pair(SMALL_G7, torch.bfloat16, 8, 128, seed=79, ctx=50, lens=[50, 1, 33, 17, 40, 8, 25, 49], std=0.05, w4=True)
+    toks = synth.make_tokens(SMALL_G7.vocab, (8, 20), 7)
+    e6 = p3.step(toks, n_logit_rows=2, what="8 sequences x 20 rows, last 2 logits rows")
+    print("w4 batched long steps rel err", e4, e5, e6)
+    p3.close()
 
 
 def test_w4_batch_of_sequences():
