@@ -271,7 +271,7 @@ struct ForwardPlan {
     bool fused_rope;              // the attention kernel reduces, rotates and appends q / k / v itself
 };
 
-ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound) {
+ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit_rows, int len_bound, bool tree) {
     const psd_model_desc &d = mdl->d;
     ForwardPlan p{};
     const int M = batch * n_new;
@@ -286,7 +286,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
         if (mdl->packed && rows <= kStreamMaxRows) return gemm_packed_splits(rows, K, n, nseg);
         return gemm_pick_splitk(d.dtype, rows, K, N, n, nseg);
     };
-    p.fused_rope = attn_fuses_rope(d.dtype, n_new, d.n_q_heads, d.n_kv_heads, d.d_head);
+    p.fused_rope = attn_fuses_rope(d.dtype, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, tree);
     p.sk_qkv = splits(M, d.d_model, p.width_qkv, n_qkv, 3);
     // folded: O runs on the column kernel (one owner per output), or, 4-bit, on partial slots with the arrival epilogue
     p.sk_o = p.folded ? (mdl->w4 ? gemm_w4_slots(hd, n_o, 1, true) : 1) : splits(M, hd, d.d_model, n_o, 1);
@@ -295,7 +295,7 @@ ForwardPlan plan_forward(const psd_model *mdl, int batch, int n_new, int n_logit
     p.sk_down = p.folded ? (mdl->w4 ? gemm_w4_slots(d.d_ffn, n_o, 1, true) : gemm_resid_slots(gemm_pack_tiles(n_o, 1), d.d_ffn))
                          : splits(M, d.d_ffn, d.d_model, n_o, 1);
     p.sk_head = Ml > 0 ? splits(Ml, d.d_model, d.vocab, n_v, 1) : 1;
-    p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound);
+    p.attn_splits = attn_pick_splits(d.dtype, batch, n_new, d.n_q_heads, d.n_kv_heads, d.d_head, len_bound, tree);
     const size_t act = 4;                                    // activations are fp32 for both dtypes
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += align256(bytes); return o; };
@@ -338,15 +338,16 @@ extern "C" {
 
 size_t psd_model_workspace_bytes(const psd_model *m, int32_t batch, int32_t n_new, int32_t max_len) {
     if (!m || max_len <= 0 || !forward_shape_ok(m, batch, n_new)) return 0;
-    // split choices depend on the cache length bound and on how many rows get logits:
-    // take the largest need over all of them
+    // split choices depend on the cache length bound, on how many rows get logits and on whether the rows are a
+    // token tree: take the largest need over all of them
     size_t worst = 0;
-    for (int rows = 0; rows <= n_new; ++rows) {
-        const size_t a = plan_forward(m, batch, n_new, rows, max_len).total;
-        const size_t b = plan_forward(m, batch, n_new, rows, n_new).total;
-        worst = a > worst ? a : worst;
-        worst = b > worst ? b : worst;
-    }
+    for (int rows = 0; rows <= n_new; ++rows)
+        for (int tree = 0; tree < 2; ++tree) {
+            const size_t a = plan_forward(m, batch, n_new, rows, max_len, tree != 0).total;
+            const size_t b = plan_forward(m, batch, n_new, rows, n_new, tree != 0).total;
+            worst = a > worst ? a : worst;
+            worst = b > worst ? b : worst;
+        }
     return worst;
 }
 
@@ -374,7 +375,7 @@ static psd_status forward_once(psd_model *m, const int32_t *tokens_dev, int32_t 
     const psd_model_desc &d = m->d;
     const int B = kv->batch;
     const int len_bound = kv->len_ub + n_new;
-    const ForwardPlan p = plan_forward(m, B, n_new, n_logit_rows, len_bound);
+    const ForwardPlan p = plan_forward(m, B, n_new, n_logit_rows, len_bound, tree != nullptr);
     if (!workspace || (uintptr_t)workspace % 256 || ws_bytes < p.total) return PSD_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;

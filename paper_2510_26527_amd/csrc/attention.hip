@@ -817,25 +817,31 @@ inline int q_tiles(int NQ) { return NQ <= 16 ? 1 : 2; }
 
 }  // namespace
 
-// more than 32 query rows per KV head: the LDS-staged kernel, 64 or 128 rows per block
-inline bool use_wide(int NQ) { return NQ > 32; }
+// Which kernel: the LDS-staged one (64 or 128 query rows per block) from 11 query rows per KV head on, the direct one
+// below that and for token trees of up to 32 rows (only it knows the ancestor mask).  The direct kernel builds its
+// operands itself (no rotation kernel in front), which pays while a block's build stays small; measured per layer,
+// direct kernel + combine against rotation kernel + LDS-staged kernel + combine (us): LLaMA2-7B shape, 1024 keys,
+// 8 rows 18.9 / 19.9, 10 rows 19.7 / 19.9, 12 rows 20.4 / 19.9, 16 rows 22.1 / 20.1, 24 rows 31.1 / 22.8;
+// LLaMA3-8B shape (4 query heads per KV head), 300 keys, 2 rows 17.1 / 17.1, 4 rows 18.1 / 17.6, 7 rows 24.6 / 17.7.
+inline bool use_wide(int NQ, bool tree) { return NQ > 32 || (!tree && NQ > 10); }
 inline int wide_rows(int NQ) { return NQ <= 64 ? 64 : 128; }
 
-bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h) {
-    return dtype == PSD_BF16 && (d_h == 64 || d_h == 128) && R <= 32 && !use_wide((h_q / h_kv) * R);
+bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h, bool tree) {
+    return dtype == PSD_BF16 && (d_h == 64 || d_h == 128) && R <= 32 && !use_wide((h_q / h_kv) * R, tree);
 }
 
-int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound) {
+int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound, bool tree) {
     if (dtype != PSD_BF16) return 1;
     const int NQ = (h_q / h_kv) * R;
     const int QT = q_tiles(NQ);
-    const int chunks = use_wide(NQ) ? (NQ + wide_rows(NQ) - 1) / wide_rows(NQ) : (NQ + QT * 16 - 1) / (QT * 16);
+    const bool wide = use_wide(NQ, tree);
+    const int chunks = wide ? (NQ + wide_rows(NQ) - 1) / wide_rows(NQ) : (NQ + QT * 16 - 1) / (QT * 16);
     // Both kernels: about one block per CU.  The LDS-staged kernel loads its 64-128 query rows and writes as many
     // partial rows per block, which that keeps below the K/V bytes (measured at 16 x 4 KV heads x 4096 keys: 4 splits
     // 78 us, 8 splits 91 us, 16 splits 113 us per layer).
     int by_grid = 256 / (B * h_kv * chunks);
     if (by_grid < 1) by_grid = 1;
-    if (!use_wide(NQ)) {
+    if (!wide) {
         // The direct kernel builds its own operands: the keys already in the cache are split into blocks of 256 (one
         // 64-key tile per wavefront), and one more split takes the step's own rows alone, so that building and
         // appending their K / V is nobody's prelude to a tile of cache keys.  Measured at the 7B shape, 1024 keys in
@@ -857,16 +863,17 @@ static void launch_mfma(const AttnArgs &a, hipStream_t stream) {
     const int NQ = (a.h_q / a.h_kv) * a.R;
     const int QT = q_tiles(NQ);
     const int chunks = (NQ + QT * 16 - 1) / (QT * 16);
+    const bool wide = use_wide(NQ, a.tree_anc != nullptr);
     // keys per split; the kernel that builds its own operands reads only the keys already in the cache and leaves its
     // last split (if it has several) to the step's own rows
     int range = (a.len_bound + a.splits - 1) / a.splits;
-    if (!use_wide(NQ) && a.qkv_partial && a.splits > 1) {
+    if (!wide && a.qkv_partial && a.splits > 1) {
         const int cached = a.len_bound - a.R > 1 ? a.len_bound - a.R : 1;
         range = (cached + a.splits - 2) / (a.splits - 1);
     }
     range = (range + kKeysPerWaveIter - 1) / kKeysPerWaveIter * kKeysPerWaveIter;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-    if (use_wide(NQ)) {
+    if (wide) {
         const int rows = wide_rows(NQ);
         dim3 wgrid(a.splits, (NQ + rows - 1) / rows, a.B * a.h_kv);
         {

@@ -125,8 +125,8 @@ struct AttnArgs {
     const uint32_t *tree_anc;
 };
 // whether launch_attention builds its operands itself for this shape (then no rotation / append kernel runs before it)
-bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h);
-int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound);
+bool attn_fuses_rope(int dtype, int R, int h_q, int h_kv, int d_h, bool tree);
+int attn_pick_splits(int dtype, int B, int R, int h_q, int h_kv, int d_h, int len_bound, bool tree);
 void launch_attention(int dtype, const AttnArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- token trees (tree.hip)
