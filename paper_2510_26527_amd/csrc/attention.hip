@@ -610,7 +610,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_wide_kernel(AttnArgs a, flo
         for (int s = 0; s < KS; ++s) {
             f32x8 v = load_f32x8(qp + 8 * s);
             if (!valid) v = f32x8{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            qf[qt][s] = __builtin_bit_cast(f16x8, f32x8_to_f16x8(v));
+            qf[qt][s] = __builtin_bit_cast(f16x8, f32x8_to_f16x8(v * scale_log2));   // scores come out in log2 units
         }
     }
     f32x4 o[QW][DT];
@@ -691,39 +691,45 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_wide_kernel(AttnArgs a, flo
                 for (int t = 0; t < 2; ++t)
                     c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qf[qt][s], c[qt][t], 0, 0, 0);
         f16x8 pf[QW];
+        const bool all_visible = kb + 31 <= S_b;       // every valid row sees all 32 keys: no mask (rows past NQ are never written)
 #pragma unroll
         for (int qt = 0; qt < QW; ++qt) {
             // lane (query column i, group g): c[qt][t][v] is key kb + 8g + 4t + v
             float tmax = -INFINITY;
+            if (!all_visible) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (kb + 8 * g + 4 * t + v > limit[qt]) c[qt][t][v] = -INFINITY;
+            }
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int key = kb + 8 * g + 4 * t + v;
-                    const float sc = key <= limit[qt] ? c[qt][t][v] * scale_log2 : -INFINITY;
-                    c[qt][t][v] = sc;
-                    tmax = fmaxf(tmax, sc);
-                }
+                for (int v = 0; v < 4; ++v) tmax = fmaxf(tmax, c[qt][t][v]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float mnew = fmaxf(mrun[qt], tmax);
+            // The reference maximum of a row only moves when the scores outgrow it by more than 2^8: until then the
+            // weights are taken against the old one (at most 256, well inside fp16 and fp32), and the accumulators
+            // are rescaled a few times per row instead of at nearly every tile.  (m, l, O) stay consistent.
+            if (tmax > mrun[qt] + 8.0f) {
+                const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - tmax);
+                lrun[qt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
+                mrun[qt] = tmax;
+            }
             float p[8];
-            if (mnew > -INFINITY) {
-                const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - mnew);
+            if (mrun[qt] > -INFINITY) {
                 float ps = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mnew);
+                    p[e] = __builtin_amdgcn_exp2f(c[qt][e >> 2][e & 3] - mrun[qt]);
                     ps += p[e];
                 }
-                lrun[qt] = lrun[qt] * alpha + ps;
-                if (mnew != mrun[qt]) {             // the running max moved: rescale the accumulators
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) o[qt][dt][v] *= alpha;
-                }
-                mrun[qt] = mnew;
+                lrun[qt] += ps;
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) p[e] = 0.f;
