@@ -156,8 +156,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=512, help="tokens to generate (--workload chain)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (sequences of a batch are independent and "
+              "would shard across GPUs without any exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

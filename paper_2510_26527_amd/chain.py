@@ -12,9 +12,9 @@ outputs land.  Every tensor stays on the GPU:
     which it needs to steer the loop, then rolls every cache at or below that level back with
     psd_kv_truncate_to.
 
-Readings of Algorithm 1 (drafting continues after the tokens already validated; accepted
-prefix plus one corrected / bonus token at every stage; a level hands up exactly gamma
-tokens) are stated in the design doc.  The per-level counters F_i and the event timers T_i feed the
+Readings of Algorithm 1 used here: drafting continues after the tokens already validated; every
+stage commits the accepted prefix plus one corrected or bonus token; a level hands up exactly
+gamma tokens.  The per-level counters F_i and the event timers T_i feed the
 cost model of Eq. (2) and Lemma 3.1 (costmodel.py).
 """
 import numpy as np
