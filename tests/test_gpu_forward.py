@@ -397,11 +397,16 @@ def test_w4_batch_of_sequences():
 
 def test_w4_llama3_8b_full_size():
     """The paper's intermediate at full size: a 4-bit, group-128 copy of the LLaMA3-8B-shaped target, 11 rows
-    (gamma_intermediate + 1) on a 300-token cache, against the oracle on the dequantised weights."""
+    (gamma_intermediate + 1) on a 300-token cache and then 20 rows in one step, against the oracle on the dequantised
+    weights."""
     _progress("w4: generating and quantising LLaMA3-8B-shaped weights")
     p = Pair(synth.LLAMA3_8B, torch.bfloat16, 1, 384, seed=41, ctx=300, oracle_kv_dtype=np.float32, w4=True)
-    toks = synth.make_tokens(synth.LLAMA3_8B.vocab, (1, 11), 44)
+    toks = synth.make_tokens(synth.LLAMA3_8B.vocab, (1, 31), 44)
     _progress("w4: forward 11 rows, both sides")
-    e = p.step(toks, what="w4 target 11 rows")
+    e = p.step(toks[:, :11], what="w4 target 11 rows")
     _progress(f"w4: rel err {e:.3e}")
+    # 20 more rows in one step: the projections dequantise the caller's codes on their way into the tiled kernel
+    _progress("w4: forward 20 rows, both sides")
+    e = p.step(toks[:, 11:], n_logit_rows=4, what="w4 target 20 rows, last 4 logits rows")
+    _progress(f"w4: rel err at 20 rows {e:.3e}")
     p.close()
