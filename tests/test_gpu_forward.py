@@ -131,7 +131,7 @@ SMALL_G7 = synth.Shape(1, 896, 7, 1, 128, 1152, 2048, 1.0e6)          # Qwen2-li
 
 
 @pytest.mark.parametrize("shape,n_new,ctx", [
-    (SMALL_GQA, 1, 300), (SMALL_GQA, 8, 300), (SMALL_GQA, 9, 1000), (SMALL_GQA, 17, 129), (SMALL_GQA, 40, 64),
+    (SMALL_GQA, 1, 300), (SMALL_GQA, 5, 200), (SMALL_GQA, 8, 300), (SMALL_GQA, 9, 1000), (SMALL_GQA, 17, 129), (SMALL_GQA, 40, 64),
     (SMALL_MHA, 8, 1024), (SMALL_MHA, 11, 77), (SMALL_MHA, 70, 200), (SMALL_MHA, 130, 0), (SMALL_MHA, 200, 30),
     (SMALL_GQA, 170, 0),
     (SMALL_G7, 16, 520), (SMALL_G7, 17, 4096), (SMALL_G7, 3, 5),
@@ -141,8 +141,8 @@ def test_bf16_small_models(shape, n_new, ctx, pack):
     """Both weight layouts of the M <= 16 path (row-major split-K kernel, packed stream-K kernels).
     Covers the skinny GEMM at 1-3 row tiles, the tiled GEMM (70, 130 rows: 128-row blocks; 170, 200 rows: 256-row
     blocks with two sets of LDS tiles), ragged N and M,
-    attention with 1, 2 and 4 query tiles, several query chunks (7 x 17 rows), split counts from
-    1 to 17 and a prefill with an empty cache.  std 0.05 keeps the signal above bf16 noise."""
+    attention on both sides of the switch between its two kernels (10 and 11 query rows per KV head), with 1, 2 and 4
+    query tiles, several query chunks (7 x 17 rows), split counts from 1 to 17 and a prefill with an empty cache.  std 0.05 keeps the signal above bf16 noise."""
     max_len = (ctx + n_new + 70 + 63) // 64 * 64
     p = Pair(shape, torch.bfloat16, 1, max_len, seed=n_new, ctx=ctx or None, std=0.05, pack=pack)
     toks = synth.make_tokens(shape.vocab, (1, n_new + 6), n_new + ctx)
