@@ -381,10 +381,15 @@ def test_workload4_insertion_criterion_live(chain4_models):
     # the quantity the proof starts from, on the measured numbers: three-model minus two-model time by Lemma 3.1
     change = costmodel.insertion_time_change(n_gen, T_new, T_i, T_next, L_new, L_i, L_i_new, two["beta"])
     t_two, t_three = two["eq2_ms"] + two["accept_ms"], three["eq2_ms"] + three["accept_ms"]
-    clear = all(abs(l - r) > 0.1 * max(abs(l), abs(r)) for l, r in (c1, c2))     # neither inequality near equality
+    # Neither inequality near equality.  Thm 3.2 takes T_i and T_{i+1} as constants; here the target verifies 7 rows
+    # per step in the two-level chain and 11 in the three-level one, and its measured step time differs between the two
+    # (a few per cent), so the band around equality is 10 % plus how far the measured times depart from that assumption.
+    drift = abs(three["T_ms"][0] - T_i) / T_i + abs(three["T_ms"][2] - T_next) / T_next
+    clear = all(abs(l - r) > (0.1 + drift) * max(abs(l), abs(r)) for l, r in (c1, c2))
     rep = {"two_level": two, "three_level": three, "condition_1": c1, "condition_2": c2, "theorem_says_helps": helps,
            "measured_helps": measured_helps, "lemma31_predicted_change_ms": change,
-           "measured_change_ms": t_three - t_two, "conditions_clear_of_equality": clear}
+           "measured_change_ms": t_three - t_two, "conditions_clear_of_equality": clear,
+           "forward_time_drift_between_the_two_chains": drift}
     os.makedirs("gpurun_out", exist_ok=True)
     with open("gpurun_out/chain4_insertion.json", "w") as f:
         json.dump(rep, f, indent=1)
