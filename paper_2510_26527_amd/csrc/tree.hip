@@ -19,6 +19,7 @@
 // Everything that decides a token runs in fp64 with a fixed summation order.
 #include "common.h"
 #include "kernels.h"
+#include "exp64.h"
 #include "prof.h"
 #include "../../include/psd.h"
 
@@ -68,15 +69,19 @@ __global__ __launch_bounds__(kTreeThreads) void tree_accept_kernel(TreeAcceptArg
     __shared__ int s_par[kTreeMaxAcceptNodes];
     __shared__ int s_pick, s_lastpos;
     __shared__ unsigned long long s_best;
+    __shared__ double s_exp2[64];                           // kExp2Table, for exp_nonpos
     const int row = blockIdx.x, tid = threadIdx.x, n = a.n_nodes, V = a.vocab;
     for (int j = tid; j < n; j += kTreeThreads) s_par[j] = a.parents[j];
+    if (tid < 64) s_exp2[tid] = kExp2Table[tid];
     __syncthreads();
     const T *P = (const T *)a.p + (size_t)row * a.p_stride;
     const T *Q = (const T *)a.q + (size_t)row * a.q_stride;
     const int32_t *tok = a.tokens + (size_t)row * n;
     const float *u = a.uniforms ? a.uniforms + (size_t)row * (n + 1) : nullptr;
     const bool greedy = a.temperature == 0.f;
-    const double Tm = (double)a.temperature;
+    const double Tm = (double)a.temperature, inv_t = 1.0 / Tm;
+    // exp(logit / T - max / T): the scaled logit minus the row's scaled maximum is never positive
+    auto ex = [&](float logit, double m) { return exp_nonpos(fma((double)logit, inv_t, -m), s_exp2); };
     int32_t *path = a.out_path + (size_t)row * n;
     int node = 0, plen = 0, flags = 0;
 
@@ -119,13 +124,14 @@ __global__ __launch_bounds__(kTreeThreads) void tree_accept_kernel(TreeAcceptArg
             mpf = fmaxf(mpf, load_elem(lp, (size_t)i));
             mqf = fmaxf(mqf, load_elem(lq, (size_t)i));
         }
-        const double mp = (double)block_max_f(mpf, s_wf) / Tm, mq = (double)block_max_f(mqf, s_wf) / Tm;
+        const double mp = (double)block_max_f(mpf, s_wf) * inv_t, mq = (double)block_max_f(mqf, s_wf) * inv_t;
         double zp = 0.0, zq = 0.0;
         for (int i = tid; i < V; i += kTreeThreads) {
-            zp += exp((double)load_elem(lp, (size_t)i) / Tm - mp);
-            zq += exp((double)load_elem(lq, (size_t)i) / Tm - mq);
+            zp += ex(load_elem(lp, (size_t)i), mp);
+            zq += ex(load_elem(lq, (size_t)i), mq);
         }
         const double Zp = block_sum_d(zp, s_wd), Zq = block_sum_d(zq, s_wd);
+        const double inv_zp = 1.0 / Zp, inv_zq = 1.0 / Zq;       // one division per row, not one per entry
         double c = 0.0, mass = 1.0;                         // the residual here is max(0, p - c q) / mass
 
         int next = -1;
@@ -133,8 +139,8 @@ __global__ __launch_bounds__(kTreeThreads) void tree_accept_kernel(TreeAcceptArg
             if (s_par[ch] != node) continue;
             int x = tok[ch];
             x = min(max(x, 0), V - 1);
-            const double px = exp((double)load_elem(lp, (size_t)x) / Tm - mp) / Zp;
-            const double qx = exp((double)load_elem(lq, (size_t)x) / Tm - mq) / Zq;
+            const double px = ex(load_elem(lp, (size_t)x), mp) * inv_zp;
+            const double qx = ex(load_elem(lq, (size_t)x), mq) * inv_zq;
             const double rx = fmax(px - c * qx, 0.0);
             const double ratio = qx == 0.0 ? INFINITY : rx / (mass * qx);
             const double thr = fmin(1.0, ratio), uu = (double)u[ch];
@@ -144,8 +150,8 @@ __global__ __launch_bounds__(kTreeThreads) void tree_accept_kernel(TreeAcceptArg
             const double c2 = c + mass;
             double m2 = 0.0;
             for (int i = tid; i < V; i += kTreeThreads) {
-                const double pi = exp((double)load_elem(lp, (size_t)i) / Tm - mp) / Zp;
-                const double qi = exp((double)load_elem(lq, (size_t)i) / Tm - mq) / Zq;
+                const double pi = ex(load_elem(lp, (size_t)i), mp) * inv_zp;
+                const double qi = ex(load_elem(lq, (size_t)i), mq) * inv_zq;
                 m2 += fmax(pi - c2 * qi, 0.0);
             }
             m2 = block_sum_d(m2, s_wd);
@@ -165,8 +171,8 @@ __global__ __launch_bounds__(kTreeThreads) void tree_accept_kernel(TreeAcceptArg
         double w = 0.0;
         int lastpos = -1;
         for (int i = i0; i < i1; ++i) {
-            const double pi = exp((double)load_elem(lp, (size_t)i) / Tm - mp) / Zp;
-            const double qi = exp((double)load_elem(lq, (size_t)i) / Tm - mq) / Zq;
+            const double pi = ex(load_elem(lp, (size_t)i), mp) * inv_zp;
+            const double qi = ex(load_elem(lq, (size_t)i), mq) * inv_zq;
             const double r = fmax(pi - c * qi, 0.0);
             if (r > 0.0) lastpos = i;
             w += r;
@@ -196,8 +202,8 @@ __global__ __launch_bounds__(kTreeThreads) void tree_accept_kernel(TreeAcceptArg
             double cum = before + incl - w;
             int token = lastpos;                            // rounding left no crossing inside: the last positive entry
             for (int i = i0; i < i1; ++i) {
-                const double pi = exp((double)load_elem(lp, (size_t)i) / Tm - mp) / Zp;
-                const double qi = exp((double)load_elem(lq, (size_t)i) / Tm - mq) / Zq;
+                const double pi = ex(load_elem(lp, (size_t)i), mp) * inv_zp;
+                const double qi = ex(load_elem(lq, (size_t)i), mq) * inv_zq;
                 cum += fmax(pi - c * qi, 0.0);
                 if (cum > target) { token = i; break; }
             }
