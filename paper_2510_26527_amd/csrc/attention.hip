@@ -663,10 +663,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_wide_kernel(AttnArgs a, flo
             *reinterpret_cast<u32x4 *>(&Vs[d * VSTRIDE + col]) = bf16x8_to_f16x8(vreg[st][c]);
         }
     };
-    // 32 keys kb .. kb + 31 of the tile in LDS set `set` (sub = which half of the tile)
-    auto multiply = [&](int set, int sub, int kb) {
-        const uint16_t *Ks = lds_wide + set * kSetElems, *Vs = Ks + 64 * KSTRIDE;
-        f16x8 ka[2][KS], va[DT];
+    // 32 keys of the tile in LDS set `set` (sub = which half of the tile), in two steps so that the scores of the second
+    // half can be on the matrix cores while the first half's softmax runs on the vector ALU: the scores
+    auto scores = [&](int set, int sub, f32x4 (&c)[QW][2]) {
+        const uint16_t *Ks = lds_wide + set * kSetElems;
+        f16x8 ka[2][KS];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int key = sub * 32 + 8 * (i >> 2) + 4 * t + (i & 3);
@@ -674,11 +675,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_wide_kernel(AttnArgs a, flo
             for (int s = 0; s < KS; ++s)
                 ka[t][s] = *reinterpret_cast<const f16x8 *>(&Ks[key * KSTRIDE + g * (DH / 4) + 8 * s]);
         }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-            va[dt] = *reinterpret_cast<const f16x8 *>(&Vs[(dt * 16 + i) * VSTRIDE + sub * 32 + 8 * g]);
-        // scores of every query tile first, MFMAs interleaved over independent accumulators
-        f32x4 c[QW][2];
+        // every query tile, MFMAs interleaved over independent accumulators
 #pragma unroll
         for (int qt = 0; qt < QW; ++qt)
 #pragma unroll
@@ -690,6 +687,14 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_wide_kernel(AttnArgs a, flo
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
                     c[qt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qf[qt][s], c[qt][t], 0, 0, 0);
+    };
+    // ... and the softmax update and P V of keys kb .. kb + 31
+    auto finish = [&](int set, int sub, int kb, f32x4 (&c)[QW][2]) {
+        const uint16_t *Vs = lds_wide + set * kSetElems + 64 * KSTRIDE;
+        f16x8 va[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            va[dt] = *reinterpret_cast<const f16x8 *>(&Vs[(dt * 16 + i) * VSTRIDE + sub * 32 + 8 * g]);
         f16x8 pf[QW];
         const bool all_visible = kb + 31 <= S_b;       // every valid row sees all 32 keys: no mask (rows past NQ are never written)
 #pragma unroll
@@ -752,14 +757,19 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_wide_kernel(AttnArgs a, flo
         if (kb0 + 128 < kb1) load_tile(S0{}, kb0 + 128);
     }
     __syncthreads();
-    // one tile: its first 32 keys, the next tile from its registers into the other LDS set, those registers refilled
-    // with the tile three ahead, the other 32 keys, one barrier (next tile visible; this set free for the one after)
+    // one tile: the scores of both halves, the first half's softmax and P V, the next tile from its registers into the
+    // other LDS set, those registers refilled with the tile three ahead, the second half's softmax and P V, one barrier
+    // (next tile visible; this set free for the one after)
     auto k_tile = [&](auto next_stage, int kt) {
         const int set = ((kt - kb0) >> 6) & 1;
-        multiply(set, 0, kt);
+        const bool second = kt + 32 < kb1;
+        f32x4 c0[QW][2], c1[QW][2];
+        scores(set, 0, c0);
+        if (second) scores(set, 1, c1);
+        finish(set, 0, kt, c0);
         if (kt + 64 < kb1) store_tile(next_stage, set ^ 1);
         if (kt + 192 < kb1) load_tile(next_stage, kt + 192);
-        if (kt + 32 < kb1) multiply(set, 1, kt + 32);
+        if (second) finish(set, 1, kt + 32, c1);
         __syncthreads();
     };
     int kt = kb0;
