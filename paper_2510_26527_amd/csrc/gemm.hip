@@ -990,7 +990,8 @@ int gemm_stream_grid(int tiles, int K) {
 }
 
 // grid of the unit kernel with the residual epilogue: one block per CU, so that few blocks share a tile (the last of
-// them to arrive adds their partials)
+// them to arrive adds their partials).  Measured on the 7B down projection, O and down averaged: 256 blocks 16.2 us,
+// 384 blocks 18.5 us, 512 blocks 17.8 us, 128 blocks slower still.
 int gemm_resid_grid(int tiles, int K) {
     const long U = (long)tiles * (K / kSkinnyStepK);
     return (int)(U < kStreamBlocks / 2 ? (U < 1 ? 1 : U) : kStreamBlocks / 2);
