@@ -102,8 +102,7 @@ psd_status psd_model_destroy(psd_model *m);
  * in fp32.
  * Such a model must be packed (psd_model_pack) before its first forward (PSD_ERR_UNIMPLEMENTED otherwise).  Steps
  * of at most 16 rows (batch * n_new <= 16) stream the packed 4-bit copy and multiply the codes exactly; longer steps
- * read the caller's codes, scales and zero points and round each weight scale * (q - zero) to fp16 once.  A token
- * tree on such a model is limited to 16 rows.  Further limit: n_kv_heads * d_head a multiple of 64. */
+ * read the caller's codes, scales and zero points and round each weight scale * (q - zero) to fp16 once.  Further limit: n_kv_heads * d_head a multiple of 64. */
 psd_status psd_model_create_w4(const psd_model_desc *desc, const void *const *weight_ptrs, int32_t n_ptrs,
                                const void *const *scale_ptrs, const void *const *zero_ptrs,
                                int32_t n_quant_ptrs, psd_model **out);

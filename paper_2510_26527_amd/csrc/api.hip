@@ -620,7 +620,7 @@ psd_status psd_model_forward_tree(psd_model *m, const int32_t *tokens_dev, int32
     TreeShape ts{};
     if (!forward_shape_ok(m, B, n_nodes) || !tree_shape_from_parents(parents_host, n_nodes, kTreeMaxNodes, &ts)) return PSD_ERR_SHAPE;
     if (kv->len_ub + n_nodes > kv->max_len) return PSD_ERR_CAPACITY;
-    if (m->w4 && (!m->packed || B * n_nodes > kStreamMaxRows)) return PSD_ERR_UNIMPLEMENTED;
+    if (m->w4 && !m->packed) return PSD_ERR_UNIMPLEMENTED;
     return forward_once(m, tokens_dev, n_nodes, kv, logits_out_dev, n_nodes, workspace, ws_bytes, hip_stream, &ts);
 }
 

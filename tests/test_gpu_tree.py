@@ -226,8 +226,10 @@ def test_degenerate_trees():
         assert out_path[r, :int(out_len[r])].cpu().tolist() == path and int(out_tok[r]) == tok
 
 
-def test_tree_forward_on_a_4bit_model():
-    parents = TREES["binary7"]
+@pytest.mark.parametrize("name", ["binary7", "comb16"])
+def test_tree_forward_on_a_4bit_model(name):
+    """Two sequences: 14 rows in all (the streaming 4-bit projections) and 32 (the tiled ones)."""
+    parents = TREES[name]
     n = len(parents)
     p = Pair(SMALL_GQA, torch.bfloat16, 2, 192, seed=4, ctx=100, std=0.05, w4=True)
     toks = synth.make_tokens(SMALL_GQA.vocab, (2, n), 5).astype(np.int32)
