@@ -69,6 +69,8 @@ def test_w4_model_create_validation(lib):
     n, nq = 3 + 9 * d.n_layers, 7 * d.n_layers
     m = psd.psd_model_create_w4(d, [0x1000] * n, [0x2000] * nq, [0x3000] * nq)
     assert psd.psd_model_packed_bytes(m) > 0
+    # steps of any row count have a workspace size: up to 16 rows on the packed 4-bit copy, the tiled kernel above
+    assert 0 < psd.psd_model_workspace_bytes(m, 1, 7, 128) < psd.psd_model_workspace_bytes(m, 2, 20, 128)
     # a 4-bit model must be packed before its first forward; nothing is launched
     kv = ctypes.c_void_p()
     assert lib.psd_kv_create(m, 1, 128, 0x1000, 0x2000, 0x3000, 0, ctypes.byref(kv)) == psd.PSD_OK
